@@ -1,0 +1,136 @@
+/*
+ * BalanceRoute CPU oracle -- TEST INFRASTRUCTURE ONLY.
+ *
+ * A plain, slow, single-threaded implementation of the per-decode-step routing
+ * decision of BalanceRoute (BR-0 and BR-H), written from the paper so that the
+ * GPU path can be checked against it.  It shares no code with the GPU library
+ * and must never be called from a product path: only tests, the smoke check and
+ * the benchmark's CPU-baseline leg may use it.
+ *
+ * What it follows:
+ *   - load model and sticky assignment:        Sec. 2.2 (workload profile, L_g(k))
+ *   - BR-0 score:                              Sec. 3.1, eq. (br0-Fscore)
+ *   - BR-0 two-stage procedure:                Sec. 3.2 and Appendix, Alg. BR-0
+ *   - horizon score:                           Sec. 4.1, eq. (brh-Fscore)
+ *   - BR-H two-stage procedure:                Sec. 4.2 and Appendix, Alg. BR-H
+ *   - in-window contribution, projected loads: Appendix "Short-horizon prediction
+ *     interface", eqs. (two-stage), (composite), (wprofile-new); gate and floor from
+ *     Appendix "Refresh logic"
+ *   - exhaustive subset search of Stage 2:     Appendix "Bit-set subset selection"
+ *
+ * BR-0/BR-H are heuristics without an exactness claim, so the oracle is the
+ * algorithm itself, step by step.  Integer quantities are int64; BR-H scores are
+ * IEEE fp32 in a fixed evaluation order (compile with -ffp-contract=off).
+ *
+ * Pins (tests/test_oracle_*.py): closed form of the BR-0 score at its breakpoints;
+ * score == drop of the imbalance G*M - sum(L); BR-H at H=0,(alpha,beta)=(1,G) == BR-0;
+ * discounted-imbalance identity of the horizon score; survival-sum == two-stage
+ * composite; subset enumeration == best over reachable sums; structural invariants
+ * of a round (sticky, disjoint, slot limit, load conservation, work conservation,
+ * telescoping of the imbalance); brute force over all assignments on tiny instances.
+ *
+ * Parity unpinned (the paper is silent; fixed here by choice): worker / request / subset tie-breaks, the Stage-1 threshold default,
+ * the descending sort of the waiting set, the token-watermark admission filter, the
+ * waiting-queue cap with counted drops.
+ */
+#ifndef BR_ORACLE_H
+#define BR_ORACLE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ORC_MAX_G 64
+#define ORC_MAX_H 128
+#define ORC_MAX_RMAX 8
+#define ORC_NSTATS 16
+#define ORC_MAX_S 32768
+
+/* stats slots (int64 each) */
+enum {
+  ORC_ST_ADMITTED = 0,
+  ORC_ST_DEFERRED = 1,
+  ORC_ST_DROPPED = 2,
+  ORC_ST_STAGE1 = 3,
+  ORC_ST_STAGE2_POPS = 4,
+  ORC_ST_GUARD = 5,
+  ORC_ST_OVERCAP = 6,
+  ORC_ST_I_BEFORE = 7,
+  ORC_ST_I_AFTER = 8,
+  ORC_ST_SPREAD = 9,
+  ORC_ST_QLEN = 10,
+  ORC_ST_WORKERS_DROPPED = 11
+};
+
+typedef struct {
+  int32_t G, B, max_wait, H;
+  int32_t R_max, S_greedy;
+  int32_t token_watermark, token_cap;
+  int32_t pred_mode; /* 0: per-step hazards p[1..H]; 1: direct c_hat (one float) */
+  int32_t force_float; /* evaluate the horizon score in fp32 even when H == 0 (reduction check) */
+  float alpha, beta, gamma, gate_pfin;
+} orc_params;
+
+/* One admission event (a single request in Stage 1, a subset in Stage 2). */
+typedef struct {
+  int32_t g;
+  int32_t stage;    /* 1 or 2; 3 = starvation guard inside Stage 2 */
+  int32_t n_req;    /* requests bound by this event */
+  int32_t pad;
+  int64_t delta;    /* sum of their prefill lengths */
+  double score;     /* F_g(Q) at the moment of the decision (exact for both score types) */
+} orc_event;
+
+/* All arrays of ONE instance; every pointer is caller-owned host memory. */
+typedef struct {
+  /* active state (in/out) */
+  int64_t *L;      /* [G] */
+  int32_t *n;      /* [G] */
+  int32_t *kv;     /* [G][B] dense lists */
+  int32_t *rem;    /* [G][B] */
+  float *pred;     /* [G][B][P] or NULL when H == 0 */
+  /* waiting queue in arrival order (in/out) */
+  int32_t *qlen;   /* [1] */
+  int32_t *qs, *qo, *qid; /* [max_wait] */
+  float *qpred;    /* [max_wait][P] */
+  /* arrivals of this step (in) */
+  int32_t a_count;
+  int32_t pad0;
+  const int32_t *a_s, *a_o, *a_id;
+  const float *a_pred;
+  /* outputs, each optional (NULL to skip) */
+  int32_t *assign;     /* [max_wait] worker per queue entry (order after append), -1 = deferred */
+  int32_t *assign_id;  /* [max_wait] id of that queue entry, -1 beyond the queue */
+  int64_t *stats;      /* [ORC_NSTATS] */
+  int32_t *F_i32;      /* [max_wait][G] snapshot scores, BR-0 */
+  float *F_f32;        /* [max_wait][G] snapshot scores, BR-H */
+  int32_t *best_g;     /* [max_wait] */
+  int32_t *best_i;     /* [G] */
+  int64_t *Lh;         /* [G][H+1] projected loads at step start */
+  int64_t *Mh;         /* [H+1] envelope */
+  int64_t *mh;         /* [G][H+1] margins */
+  int64_t *minm;       /* [G] */
+  float *chat;         /* [G][B] in-window contribution per active slot */
+  orc_event *events;   /* [max_wait] */
+  int32_t *n_events;   /* [1] */
+} orc_io;
+
+/* scores */
+int64_t orc_score_br0(int64_t G, int64_t m, int64_t delta);
+float orc_score_brh(int32_t H, float alpha, float beta, float gamma, const int64_t *m, int64_t delta);
+/* in-window contribution from the prediction inputs of one request */
+float orc_chat(int32_t H, int32_t pred_mode, float gate_pfin, const float *p);
+/* Stage-2 subset search on an explicit window; returns the chosen mask (0 = none feasible) */
+int32_t orc_best_subset(const orc_params *P, const int64_t *m_g, int64_t L_g, int32_t cap_g,
+                        const int32_t *win_s, int32_t w, double *best_score);
+
+int32_t orc_project(const orc_params *P, orc_io *io);
+int32_t orc_route_step(const orc_params *P, orc_io *io);
+int32_t orc_advance(const orc_params *P, orc_io *io, int32_t n_steps);
+
+#ifdef __cplusplus
+}
+#endif
+#endif
