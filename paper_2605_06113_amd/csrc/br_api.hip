@@ -1,0 +1,283 @@
+// C-ABI entry points (include/br.h): argument checks, workspace layout, kernel launches.
+// Host code only; every step of the path runs in the kernels.
+#include <hip/hip_runtime.h>
+
+#include <new>
+#include <vector>
+
+#include "br.h"
+#include "br_device.h"
+#include "br_launch.h"
+
+namespace {
+
+struct EvPair {
+  hipEvent_t a, b;
+  int kid;
+};
+
+uint64_t align_up(uint64_t x) { return (x + 255u) & ~(uint64_t)255u; }
+
+int pred_width(const br_config &c) { return c.H == 0 ? 0 : (c.pred_mode == 1 ? 1 : c.H); }
+
+bool config_ok(const br_config *c) {
+  if (!c) return false;
+  if (c->n_inst < 1 || c->G < 1 || c->G > BR_MAX_G || c->B < 1 || c->B > BR_MAX_B) return false;
+  if (c->max_wait < 1 || c->max_wait > BR_MAX_WAIT || c->H < 0 || c->H > BR_MAX_H) return false;
+  if (c->R_max < 1 || c->R_max > BR_MAX_RMAX || c->S_greedy < 0) return false;
+  if (c->token_watermark < 0 || c->token_cap < 0) return false;
+  if (c->pred_mode != 0 && c->pred_mode != 1) return false;
+  if (c->H > 0) {
+    if (!(c->alpha > 0.0f) || !(c->beta >= 0.0f) || !(c->gamma > 0.0f) || !(c->gamma <= 1.0f)) return false;
+  }
+  return true;
+}
+
+void make_layout(const br_config &c, br_layout *l) {
+  const uint64_t N = (uint64_t)c.n_inst, G = (uint64_t)c.G, Q = (uint64_t)c.max_wait, H1 = (uint64_t)c.H + 1;
+  const uint64_t P = (uint64_t)pred_width(c);
+  const uint64_t Bs = ((uint64_t)c.B + 3u) & ~(uint64_t)3u;
+  uint64_t off = 0;
+  auto take = [&](uint64_t words) {
+    const uint64_t at = off;
+    off = align_up(off + words * 4u);
+    return at;
+  };
+  l->L = take(N * G);
+  l->n = take(N * G);
+  l->kv = take(N * G * Bs);
+  l->rem = take(N * G * Bs);
+  l->pred = take(N * G * Bs * P);
+  l->qlen = take(N);
+  l->qs = take(N * Q);
+  l->qo = take(N * Q);
+  l->qid = take(N * Q);
+  l->qpred = take(N * Q * P);
+  l->Lh = take(N * G * H1);
+  l->Mh = take(N * H1);
+  l->mh = take(N * G * H1);
+  l->minm = take(N * G);
+  l->total_bytes = off;
+  l->B_stride = (int32_t)Bs;
+  l->P = (int32_t)P;
+}
+
+}  // namespace
+
+struct br_ctx {
+  br_config cfg;
+  br_layout lay;
+  BrParams p;
+  hipStream_t st;
+  int32_t last_hip;
+  bool prof;
+  std::vector<EvPair> pending, spare;
+  double ms[BR_NKERNELS];
+  int64_t launches[BR_NKERNELS];
+};
+
+namespace {
+
+int32_t fail_hip(br_ctx *ctx, hipError_t e) {
+  ctx->last_hip = (int32_t)e;
+  return BR_EHIP;
+}
+
+// Enqueue one kernel; with profiling on, bracket it with an event pair on the same stream.
+template <class Fn>
+int32_t enqueue(br_ctx *ctx, int kid, Fn &&fn) {
+  EvPair ev{};
+  if (ctx->prof) {
+    if (!ctx->spare.empty()) {
+      ev = ctx->spare.back();
+      ctx->spare.pop_back();
+    } else {
+      hipError_t e = hipEventCreate(&ev.a);
+      if (e != hipSuccess) return fail_hip(ctx, e);
+      e = hipEventCreate(&ev.b);
+      if (e != hipSuccess) return fail_hip(ctx, e);
+    }
+    ev.kid = kid;
+    hipError_t e = hipEventRecord(ev.a, ctx->st);
+    if (e != hipSuccess) return fail_hip(ctx, e);
+  }
+  fn();
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail_hip(ctx, e);
+  if (ctx->prof) {
+    e = hipEventRecord(ev.b, ctx->st);
+    if (e != hipSuccess) return fail_hip(ctx, e);
+    ctx->pending.push_back(ev);
+  }
+  return BR_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+uint64_t br_workspace_bytes(const br_config *cfg) {
+  if (!config_ok(cfg)) return 0;
+  br_layout l;
+  make_layout(*cfg, &l);
+  return l.total_bytes;
+}
+
+int32_t br_init(const br_config *cfg, const br_init_state *init, br_ctx **out) {
+  if (!out || !config_ok(cfg) || !cfg->workspace) return BR_EINVAL;
+  if (((uintptr_t)cfg->workspace & 255u) != 0) return BR_EINVAL;
+  br_layout l;
+  make_layout(*cfg, &l);
+  if (cfg->workspace_bytes < l.total_bytes) return BR_ENOMEM;
+  const int P = pred_width(*cfg);
+  if (init && (!init->n || !init->kv || !init->rem || (P > 0 && !init->pred))) return BR_EINVAL;
+
+  br_ctx *ctx = new (std::nothrow) br_ctx();
+  if (!ctx) return BR_ENOMEM;
+  ctx->cfg = *cfg;
+  ctx->lay = l;
+  ctx->st = (hipStream_t)cfg->stream;
+  ctx->last_hip = 0;
+  ctx->prof = false;
+  for (int k = 0; k < BR_NKERNELS; ++k) {
+    ctx->ms[k] = 0.0;
+    ctx->launches[k] = 0;
+  }
+
+  BrParams &p = ctx->p;
+  p.N = cfg->n_inst;
+  p.G = cfg->G;
+  p.B = cfg->B;
+  p.Bs = l.B_stride;
+  p.Q = cfg->max_wait;
+  p.H = cfg->H;
+  p.P = P;
+  p.R_max = cfg->R_max;
+  p.S_greedy = cfg->S_greedy;
+  p.W = cfg->token_watermark;
+  p.C = cfg->token_cap;
+  p.pred_mode = cfg->pred_mode;
+  p.gate = cfg->gate_pfin;
+  // discount vector d = (1, gamma, ..., gamma^H) by repeated product, D = 1^T d summed upwards
+  // (Sec. 4.1); fp32 throughout so the device sees the same constants a float reference does
+  for (int h = 0; h <= BR_HP; ++h) p.d[h] = 0.0f;
+  volatile float acc = 0.0f, dh = 1.0f;
+  for (int h = 0; h <= cfg->H; ++h) {
+    if (h > 0) dh = dh * cfg->gamma;
+    p.d[h] = dh;
+    acc = acc + dh;
+  }
+  volatile float aD = cfg->alpha * acc;
+  p.aD = cfg->H > 0 ? (float)aD : 1.0f;
+  p.beta = cfg->H > 0 ? cfg->beta : (float)cfg->G;
+
+  char *base = (char *)cfg->workspace;
+  p.L = (int32_t *)(base + l.L);
+  p.n = (int32_t *)(base + l.n);
+  p.kv = (int32_t *)(base + l.kv);
+  p.rem = (int32_t *)(base + l.rem);
+  p.pred = (float *)(base + l.pred);
+  p.qlen = (int32_t *)(base + l.qlen);
+  p.qs = (int32_t *)(base + l.qs);
+  p.qo = (int32_t *)(base + l.qo);
+  p.qid = (int32_t *)(base + l.qid);
+  p.qpred = (float *)(base + l.qpred);
+  p.Lh = (int32_t *)(base + l.Lh);
+  p.Mh = (int32_t *)(base + l.Mh);
+  p.mh = (int32_t *)(base + l.mh);
+  p.minm = (int32_t *)(base + l.minm);
+
+  int32_t rc = enqueue(ctx, BR_K_INIT, [&] { br_launch_clear(p, ctx->st); });
+  if (rc == BR_OK && init)
+    rc = enqueue(ctx, BR_K_INIT, [&] { br_launch_load_init(p, init->n, init->kv, init->rem, init->pred, ctx->st); });
+  if (rc != BR_OK) {
+    delete ctx;
+    return rc;
+  }
+  *out = ctx;
+  return BR_OK;
+}
+
+int32_t br_route_step(br_ctx *ctx, const br_arrivals *in, const br_step_out *out) {
+  if (!ctx) return BR_EINVAL;
+  BrArr a{};
+  if (in && in->count && in->arr_cap > 0) {
+    if (!in->s || !in->o || (ctx->p.P > 0 && !in->pred)) return BR_EINVAL;
+    a.count = in->count;
+    a.s = in->s;
+    a.o = in->o;
+    a.id = in->id;
+    a.pred = in->pred;
+    a.arr_cap = in->arr_cap;
+  }
+  BrOut o{};
+  if (out) {
+    o.assign = out->assign;
+    o.assign_id = out->assign_id;
+    o.stats = (long long *)out->stats;
+    o.F = out->F;
+    o.best_g = out->best_g;
+    o.best_i = out->best_i;
+  }
+  const BrParams &p = ctx->p;
+  int32_t rc = BR_OK;
+  if (p.H > 0) rc = enqueue(ctx, BR_K_PROJECT, [&] { br_launch_project(p, ctx->st); });
+  if (rc == BR_OK && (o.F || o.best_g || o.best_i))
+    rc = enqueue(ctx, BR_K_SCORE, [&] { br_launch_score(p, a, o, ctx->st); });
+  if (rc == BR_OK) rc = enqueue(ctx, BR_K_ASSIGN, [&] { br_launch_assign(p, a, o, ctx->st); });
+  return rc;
+}
+
+int32_t br_advance_decode(br_ctx *ctx, int32_t n_steps) {
+  if (!ctx || n_steps < 0) return BR_EINVAL;
+  if (n_steps == 0) return BR_OK;
+  return enqueue(ctx, BR_K_ADVANCE, [&] { br_launch_advance(ctx->p, n_steps, ctx->st); });
+}
+
+void br_free(br_ctx *ctx) {
+  if (!ctx) return;
+  for (auto &v : {&ctx->pending, &ctx->spare})
+    for (EvPair &e : *v) {
+      (void)hipEventDestroy(e.a);
+      (void)hipEventDestroy(e.b);
+    }
+  delete ctx;
+}
+
+int32_t br_last_hip_error(const br_ctx *ctx) { return ctx ? ctx->last_hip : 0; }
+
+int32_t br_get_layout(const br_ctx *ctx, br_layout *out) {
+  if (!ctx || !out) return BR_EINVAL;
+  *out = ctx->lay;
+  return BR_OK;
+}
+
+int32_t br_profile_enable(br_ctx *ctx, int32_t on) {
+  if (!ctx) return BR_EINVAL;
+  ctx->prof = on != 0;
+  return BR_OK;
+}
+
+int32_t br_profile_read(br_ctx *ctx, double *ms, int64_t *launches) {
+  if (!ctx || !ms || !launches) return BR_EINVAL;
+  for (EvPair &e : ctx->pending) {
+    hipError_t r = hipEventSynchronize(e.b);
+    if (r != hipSuccess) return fail_hip(ctx, r);
+    float t = 0.0f;
+    r = hipEventElapsedTime(&t, e.a, e.b);
+    if (r != hipSuccess) return fail_hip(ctx, r);
+    ctx->ms[e.kid] += (double)t;
+    ctx->launches[e.kid] += 1;
+    ctx->spare.push_back(e);
+  }
+  ctx->pending.clear();
+  for (int k = 0; k < BR_NKERNELS; ++k) {
+    ms[k] = ctx->ms[k];
+    launches[k] = ctx->launches[k];
+    ctx->ms[k] = 0.0;
+    ctx->launches[k] = 0;
+  }
+  return BR_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,147 @@
+// Device-side helpers shared by the gfx950 kernels: wave64 reductions on DPP,
+// the two score functions, and the parameter block the host passes by value.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#define BR_WAVE 64
+#define BR_HP 8          // horizon offsets h = 0..BR_HP are carried in registers
+#define BR_LOW (-(1 << 30))  // "minus infinity" load of a lane that holds no worker
+#define BR_MAX_G_DEV 64
+#define BR_MAX_S_DEV 32768
+#define BR_IDX_BITS 11   // queue positions fit 11 bits (max_wait <= 2048)
+
+struct BrParams {
+  int32_t N, G, B, Bs, Q, H, P, R_max, S_greedy, W, C, pred_mode;
+  float aD, beta, gate;
+  float d[BR_HP + 1];  // discount vector, zero beyond H
+  // workspace arrays
+  int32_t *L, *n, *kv, *rem;
+  float *pred;
+  int32_t *qlen, *qs, *qo, *qid;
+  float *qpred;
+  int32_t *Lh, *Mh, *mh, *minm;
+};
+
+struct BrArr {  // arrivals of one round (device pointers, may be null when none)
+  const int32_t *count, *s, *o, *id;
+  const float *pred;
+  int32_t arr_cap;
+};
+
+struct BrOut {
+  int32_t *assign, *assign_id;
+  long long *stats;
+  void *F;
+  int32_t *best_g, *best_i;
+};
+
+// ---------------------------------------------------------------- wave64 reductions
+// Cross-lane data movement on the DPP path (no LDS traffic).  Every lane of the wave
+// must be active when these run.  Pattern: swap within pairs, within quads, mirror
+// within half rows, mirror within rows of 16, then carry lane 15 of each row into the
+// next row and lane 31 into the upper half; lane 63 ends up with the full reduction.
+
+template <int CTRL, int ROW_MASK = 0xF>
+__device__ __forceinline__ int br_dpp(int old, int src) {
+  return __builtin_amdgcn_update_dpp(old, src, CTRL, ROW_MASK, 0xF, false);
+}
+
+__device__ __forceinline__ int br_wave_max(int x) {
+  x = max(x, br_dpp<0xB1>(x, x));         // quad_perm [1,0,3,2]
+  x = max(x, br_dpp<0x4E>(x, x));         // quad_perm [2,3,0,1]
+  x = max(x, br_dpp<0x141>(x, x));        // row_half_mirror
+  x = max(x, br_dpp<0x140>(x, x));        // row_mirror
+  x = max(x, br_dpp<0x142, 0xA>(x, x));   // row_bcast:15 into rows 1 and 3
+  x = max(x, br_dpp<0x143, 0xC>(x, x));   // row_bcast:31 into rows 2 and 3
+  return __builtin_amdgcn_readlane(x, 63);
+}
+
+__device__ __forceinline__ int br_wave_min(int x) {
+  x = min(x, br_dpp<0xB1>(x, x));
+  x = min(x, br_dpp<0x4E>(x, x));
+  x = min(x, br_dpp<0x141>(x, x));
+  x = min(x, br_dpp<0x140>(x, x));
+  x = min(x, br_dpp<0x142, 0xA>(x, x));
+  x = min(x, br_dpp<0x143, 0xC>(x, x));
+  return __builtin_amdgcn_readlane(x, 63);
+}
+
+__device__ __forceinline__ int br_wave_sum(int x) {
+  x += br_dpp<0xB1>(0, x);
+  x += br_dpp<0x4E>(0, x);
+  x += br_dpp<0x141>(0, x);
+  x += br_dpp<0x140>(0, x);
+  x += br_dpp<0x142, 0xA>(0, x);
+  x += br_dpp<0x143, 0xC>(0, x);
+  return __builtin_amdgcn_readlane(x, 63);
+}
+
+__device__ __forceinline__ unsigned long long br_ballot(bool p) { return __builtin_amdgcn_ballot_w64(p); }
+
+__device__ __forceinline__ int br_lane() { return (int)(threadIdx.x & 63u); }
+
+// number of set bits of m in lanes below the caller
+__device__ __forceinline__ int br_rank_below(unsigned long long m) {
+  return (int)__builtin_amdgcn_mbcnt_hi((unsigned)(m >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)m, 0u));
+}
+
+__device__ __forceinline__ int br_uniform(int x) { return __builtin_amdgcn_readfirstlane(x); }
+
+// ---------------------------------------------------------------- scores
+// Scores are compared as int32 keys: the BR-0 score is its own key; an fp32 horizon score
+// maps to the integer with the same ordering, so that one set of integer reductions serves
+// both.  key <= 0 exactly when the score is <= 0.
+
+__device__ __forceinline__ int br_ord(float f) {
+  int b = __float_as_int(f);
+  return b ^ ((b >> 31) & 0x7fffffff);
+}
+
+__device__ __forceinline__ float br_unord(int k) { return __int_as_float(k ^ ((k >> 31) & 0x7fffffff)); }
+
+#define BR_KEY_NONE INT32_MIN
+
+// Sec. 3.1, eq. (br0-Fscore): F = Delta - G (Delta - m)_+ in exact int32.
+__device__ __forceinline__ int br_score0(int G, int m, int delta) { return delta - G * max(delta - m, 0); }
+
+// Sec. 4.1, eq. (brh-Fscore): alpha (1^T d) Delta - beta ((Delta 1 - m)_+)^T d, fp32, each
+// operation rounded on its own, penalty accumulated from h = 0 upwards.  Offsets beyond H carry
+// a zero discount and add exactly +0.
+__device__ __forceinline__ float br_scoreh(const BrParams &p, const int (&m)[BR_HP + 1], int delta) {
+  float pen = 0.0f;
+#pragma unroll
+  for (int h = 0; h <= BR_HP; ++h)
+    pen = __fadd_rn(pen, __fmul_rn(p.d[h], (float)max(delta - m[h], 0)));
+  return __fsub_rn(__fmul_rn(p.aD, (float)delta), __fmul_rn(p.beta, pen));
+}
+
+template <bool BRH>
+__device__ __forceinline__ int br_score_key(const BrParams &p, const int (&m)[BR_HP + 1], int delta) {
+  if constexpr (BRH) return br_ord(br_scoreh(p, m, delta));
+  else return br_score0(p.G, m[0], delta);
+}
+
+// In-window contribution c_hat of one active request (Appendix "Short-horizon prediction
+// interface"): survival sum of the hazards = E[min(r, H)] (eq. (two-stage)/(composite)), the
+// p_fin gate and the floor of Appendix "Refresh logic", clip to [1, H].
+__device__ __forceinline__ float br_chat(const BrParams &p, const float *pr) {
+  const float Hf = (float)p.H;
+  float c;
+  if (p.pred_mode == 1) {
+    c = pr[0];
+  } else {
+    float S = 1.0f;
+    c = 0.0f;
+    for (int j = 0; j < p.H; ++j) {
+      c = __fadd_rn(c, S);
+      S = __fmul_rn(S, __fsub_rn(1.0f, pr[j]));
+    }
+    const float pfin = __fsub_rn(1.0f, S);
+    if (p.gate > 0.0f && pfin < p.gate) c = Hf;
+  }
+  c = c < 1.0f ? 1.0f : c;
+  c = c > Hf ? Hf : c;
+  return c;
+}

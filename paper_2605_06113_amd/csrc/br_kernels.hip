@@ -1,0 +1,298 @@
+// gfx950 kernels of the BalanceRoute route step, except the sequential assignment
+// (br_assign.hip): state initialisation, decode step, horizon projection, and the
+// F-score matrix with its stage-one reductions.
+#include "br_device.h"
+#include "br_launch.h"
+
+// ------------------------------------------------------------------ initialisation
+
+__global__ void br_k_clear(BrParams p) {
+  const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t rows = (int64_t)p.N * p.G;
+  if (tid < rows) {
+    p.L[tid] = 0;
+    p.n[tid] = 0;
+  }
+  if (tid < p.N) p.qlen[tid] = 0;
+}
+
+// One wave per (cluster, worker): copy the caller's dense active list into the workspace
+// layout and derive L_g = sum of kv (Sec. 2.2).
+__global__ __launch_bounds__(256) void br_k_load_init(BrParams p, const int32_t *n_in, const int32_t *kv_in,
+                                                     const int32_t *rem_in, const float *pred_in) {
+  const int64_t row = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  if (row >= (int64_t)p.N * p.G) return;  // whole wave leaves together
+  const int lane = br_lane();
+  int n_g = n_in[row];
+  n_g = min(max(n_g, 0), p.B);
+  int acc = 0;
+  for (int j = lane; j < n_g; j += BR_WAVE) {
+    const int kv = kv_in[row * p.B + j];
+    p.kv[row * p.Bs + j] = kv;
+    p.rem[row * p.Bs + j] = max(rem_in[row * p.B + j], 1);
+    for (int q = 0; q < p.P; ++q) p.pred[(row * p.Bs + j) * p.P + q] = pred_in[(row * p.B + j) * p.P + q];
+    acc += kv;
+  }
+  const int tot = br_wave_sum(acc);
+  if (lane == 0) {
+    p.L[row] = tot;
+    p.n[row] = n_g;
+  }
+}
+
+// ------------------------------------------------------------------ decode step
+// Sec. 2.2: each active request advances one decode iteration per step: its KV length and
+// the load of its worker grow by one token; after its last step it leaves and its whole KV
+// footprint goes with it.  t steps are applied in closed form: a request with rem <= t
+// leaves (net load change -kv), the others gain t tokens.  One wave owns one worker's dense
+// list and compacts it in place, order preserved (writes never run ahead of reads).
+__global__ __launch_bounds__(256) void br_k_advance(BrParams p, int t) {
+  const int64_t row = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  if (row >= (int64_t)p.N * p.G) return;
+  const int lane = br_lane();
+  const int n_g = p.n[row];
+  const int64_t base = row * p.Bs;
+  int kept = 0;  // uniform
+  int dL = 0;
+  for (int c = 0; c < n_g; c += BR_WAVE) {
+    const int j = c + lane;
+    const bool used = j < n_g;
+    const int kv = used ? p.kv[base + j] : 0;
+    const int rem = used ? p.rem[base + j] : 0;
+    const bool stay = used && rem > t;
+    dL += used ? (stay ? t : -kv) : 0;
+    const unsigned long long bal = br_ballot(stay);
+    const int nj = kept + br_rank_below(bal);
+    if (stay) {
+      p.kv[base + nj] = kv + t;
+      p.rem[base + nj] = rem - t;
+      if (p.P && nj != j)
+        for (int q = 0; q < p.P; ++q) p.pred[(base + nj) * p.P + q] = p.pred[(base + j) * p.P + q];
+    }
+    kept += __builtin_popcountll(bal);
+  }
+  const int tot = br_wave_sum(dL);
+  if (lane == 0) {
+    p.L[row] += tot;
+    p.n[row] = kept;
+  }
+}
+
+// ------------------------------------------------------------------ horizon projection
+// Preparation step of Alg. BR-H: per worker and offset h = 0..H the projected load
+// L_g(k+h) = sum over active requests of (kv + h) while h <= c_hat (eq. (wprofile-new)); then the
+// envelope M_h = max_g L_g(k+h), margins m_{g,h} = (M_h - L_g(k+h))_+ and min_h m_{g,h}.
+// One block per cluster; each wave walks whole worker lists.
+__global__ __launch_bounds__(1024) void br_k_project(BrParams p) {
+  __shared__ int sLh[BR_MAX_G_DEV * (BR_HP + 1)];
+  __shared__ int sMh[BR_HP + 1];
+  const int inst = blockIdx.x;
+  const int lane = br_lane();
+  const int wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  const int H1 = p.H + 1;
+  for (int g = wave; g < p.G; g += nw) {
+    const int64_t row = (int64_t)inst * p.G + g;
+    const int n_g = p.n[row];
+    const int64_t base = row * p.Bs;
+    int acc[BR_HP + 1];
+#pragma unroll
+    for (int h = 0; h <= BR_HP; ++h) acc[h] = 0;
+    for (int j = lane; j < n_g; j += BR_WAVE) {
+      const int kv = p.kv[base + j];
+      const float c = br_chat(p, p.pred + (base + j) * p.P);
+#pragma unroll
+      for (int h = 0; h <= BR_HP; ++h)
+        if (h <= p.H && (float)h <= c) acc[h] += kv + h;
+    }
+#pragma unroll
+    for (int h = 0; h <= BR_HP; ++h) {
+      const int v = br_wave_sum(acc[h]);
+      if (lane == 0) sLh[g * (BR_HP + 1) + h] = v;
+    }
+  }
+  __syncthreads();
+  if ((int)threadIdx.x < H1) {
+    int M = sLh[threadIdx.x];
+    for (int g = 1; g < p.G; ++g) M = max(M, sLh[g * (BR_HP + 1) + threadIdx.x]);
+    sMh[threadIdx.x] = M;
+    p.Mh[(int64_t)inst * H1 + threadIdx.x] = M;
+  }
+  __syncthreads();
+  for (int e = threadIdx.x; e < p.G * H1; e += blockDim.x) {
+    const int g = e / H1, h = e - g * H1;
+    const int lh = sLh[g * (BR_HP + 1) + h];
+    p.Lh[((int64_t)inst * p.G + g) * H1 + h] = lh;
+    p.mh[((int64_t)inst * p.G + g) * H1 + h] = max(sMh[h] - lh, 0);
+  }
+  if ((int)threadIdx.x < p.G) {
+    const int g = threadIdx.x;
+    int mn = INT32_MAX;
+    for (int h = 0; h < H1; ++h) mn = min(mn, max(sMh[h] - sLh[g * (BR_HP + 1) + h], 0));
+    p.minm[(int64_t)inst * p.G + g] = mn;
+  }
+}
+
+// ------------------------------------------------------------------ F-score matrix + reductions
+// Scores every (waiting request, worker) pair on the step-start snapshot: eq. (br0-Fscore) in
+// int32 or eq. (brh-Fscore) in fp32.  Pass A maps lanes to requests (coalesced request-major
+// reads, worker margins broadcast from LDS), reduces over workers in registers (best worker per
+// request) and, if asked, stages the 64 x G tile in LDS so that the matrix leaves in full-width
+// contiguous stores.  Pass B maps lanes to (request sub-slot, worker) and keeps a running best
+// request per worker, combined across lanes and waves at the end.
+template <bool BRH>
+__global__ __launch_bounds__(512) void br_k_score(BrParams p, BrArr a, BrOut o, int want_tile) {
+  extern __shared__ int lds[];
+  const int G = p.G;
+  int *sm = lds;                         // [G][BR_HP+1] margins
+  int *sL = sm + G * (BR_HP + 1);        // [G]
+  int *scap = sL + G;                    // [G]
+  int *ss = scap + G;                    // [Q] prefill lengths of the waiting set
+  int *cand = ss + p.Q;                  // [3][blockDim] candidates of pass B
+  int *tiles = cand + 3 * blockDim.x;    // [waves][64][G+1] when the matrix is written out
+  const int inst = blockIdx.x;
+  const int tid = threadIdx.x, lane = br_lane(), wave = tid >> 6, nw = blockDim.x >> 6;
+
+  const int q0 = min(max(p.qlen[inst], 0), p.Q);
+  int cnt = a.count ? a.count[inst] : 0;
+  cnt = min(max(cnt, 0), a.arr_cap);
+  const int qn = q0 + min(cnt, p.Q - q0);
+
+  if (tid < G) {
+    sL[tid] = p.L[(int64_t)inst * G + tid];
+    scap[tid] = p.B - p.n[(int64_t)inst * G + tid];
+  }
+  for (int e = tid; e < G * (BR_HP + 1); e += blockDim.x) {
+    const int g = e / (BR_HP + 1), h = e - g * (BR_HP + 1);
+    sm[e] = (BRH && h <= p.H) ? p.mh[((int64_t)inst * G + g) * (p.H + 1) + h] : 0;
+  }
+  for (int i = tid; i < qn; i += blockDim.x) {
+    int s = i < q0 ? p.qs[(int64_t)inst * p.Q + i] : a.s[(int64_t)inst * a.arr_cap + (i - q0)];
+    ss[i] = min(max(s, 1), BR_MAX_S_DEV);
+  }
+  __syncthreads();
+  if (!BRH) {  // M(k) = max_g L_g, m_g = M - L_g
+    if (tid < G) {
+      int M = sL[0];
+      for (int g = 1; g < G; ++g) M = max(M, sL[g]);
+      sm[tid * (BR_HP + 1)] = M - sL[tid];
+    }
+    __syncthreads();
+  }
+
+  // pass A: one request per lane, loop over workers
+  int *tile = tiles + wave * (BR_WAVE * (G + 1));
+  for (int t0 = wave * BR_WAVE; t0 < qn; t0 += nw * BR_WAVE) {
+    const int i = t0 + lane;
+    const bool valid = i < qn;
+    const int s = valid ? ss[i] : 1;
+    int bk = BR_KEY_NONE, bg = -1;
+    for (int g = 0; g < G; ++g) {
+      int m[BR_HP + 1];
+#pragma unroll
+      for (int h = 0; h <= BR_HP; ++h) m[h] = (BRH || h == 0) ? sm[g * (BR_HP + 1) + h] : 0;
+      const int key = br_score_key<BRH>(p, m, s);
+      if (want_tile) tile[lane * (G + 1) + g] = key;
+      const bool ok = scap[g] > 0 && (p.W <= 0 || sL[g] + s <= p.W);
+      if (ok && key > bk) {
+        bk = key;
+        bg = g;
+      }
+    }
+    if (valid && o.best_g) o.best_g[(int64_t)inst * p.Q + i] = bg;
+    if (want_tile) {
+      const int rows = min(BR_WAVE, qn - t0);
+      int *Fi = (int *)o.F + ((int64_t)inst * p.Q + t0) * G;
+      for (int e = lane; e < rows * G; e += BR_WAVE) {
+        const int r = e / G, g = e - r * G;
+        const int key = tile[r * (G + 1) + g];
+        Fi[e] = BRH ? __float_as_int(br_unord(key)) : key;
+      }
+    }
+  }
+  if (o.best_g)
+    for (int i = qn + tid; i < p.Q; i += blockDim.x) o.best_g[(int64_t)inst * p.Q + i] = -1;
+
+  // pass B: lane = (sub-slot, worker); running best request per worker
+  if (o.best_i) {
+    int Gp = 1;
+    while (Gp < G) Gp <<= 1;
+    const int nsub = BR_WAVE / Gp;
+    const int sub = lane / Gp, g = lane - sub * Gp;
+    const bool act = g < G;
+    int m[BR_HP + 1];
+#pragma unroll
+    for (int h = 0; h <= BR_HP; ++h) m[h] = (act && (BRH || h == 0)) ? sm[g * (BR_HP + 1) + h] : 0;
+    const int Lg = act ? sL[g] : 0;
+    const bool free_slot = act && scap[g] > 0;
+    int bk = BR_KEY_NONE, bs = 0, bi = -1;
+    for (int i = wave * nsub + sub; i < qn; i += nw * nsub) {
+      const int s = ss[i];
+      const int key = br_score_key<BRH>(p, m, s);
+      const bool ok = free_slot && (p.W <= 0 || Lg + s <= p.W);
+      if (ok && (key > bk || (key == bk && s > bs))) {
+        bk = key;
+        bs = s;
+        bi = i;
+      }
+    }
+    cand[tid] = bk;
+    cand[blockDim.x + tid] = bs;
+    cand[2 * blockDim.x + tid] = bi;
+    __syncthreads();
+    if (tid < G) {
+      bk = BR_KEY_NONE, bs = 0, bi = -1;
+      for (int w = 0; w < nw; ++w)
+        for (int sb = 0; sb < nsub; ++sb) {
+          const int c = w * BR_WAVE + sb * Gp + tid;
+          const int k = cand[c], s = cand[blockDim.x + c], i = cand[2 * blockDim.x + c];
+          if (i < 0) continue;
+          if (bi < 0 || k > bk || (k == bk && (s > bs || (s == bs && i < bi)))) {
+            bk = k;
+            bs = s;
+            bi = i;
+          }
+        }
+      o.best_i[(int64_t)inst * G + tid] = bi;
+    }
+  }
+}
+
+// ------------------------------------------------------------------ launchers
+
+void br_launch_clear(const BrParams &p, hipStream_t st) {
+  const int64_t n = (int64_t)p.N * p.G;
+  hipLaunchKernelGGL(br_k_clear, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p);
+}
+
+void br_launch_load_init(const BrParams &p, const int32_t *n, const int32_t *kv, const int32_t *rem, const float *pred,
+                         hipStream_t st) {
+  const int64_t rows = (int64_t)p.N * p.G;
+  hipLaunchKernelGGL(br_k_load_init, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, p, n, kv, rem, pred);
+}
+
+void br_launch_advance(const BrParams &p, int t, hipStream_t st) {
+  const int64_t rows = (int64_t)p.N * p.G;
+  hipLaunchKernelGGL(br_k_advance, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, p, t);
+}
+
+void br_launch_project(const BrParams &p, hipStream_t st) {
+  const int waves = p.G < 16 ? p.G : 16;
+  hipLaunchKernelGGL(br_k_project, dim3((unsigned)p.N), dim3(64 * waves), 0, st, p);
+}
+
+void br_launch_score(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st) {
+  int waves = (p.Q + 255) / 256;
+  waves = waves < 1 ? 1 : (waves > 8 ? 8 : waves);
+  const int want_tile = o.F != nullptr;
+  auto lds_words = [&](int w) {
+    size_t words = (size_t)p.G * (BR_HP + 1) + 2 * (size_t)p.G + (size_t)p.Q + 3 * 64 * (size_t)w;
+    if (want_tile) words += (size_t)w * 64 * (size_t)(p.G + 1);
+    return words;
+  };
+  while (waves > 1 && lds_words(waves) * 4 > 60 * 1024) --waves;  // stay within the default 64 KiB of LDS per block
+  const size_t lds = lds_words(waves) * 4;
+  if (p.H > 0)
+    hipLaunchKernelGGL(br_k_score<true>, dim3((unsigned)p.N), dim3(64 * waves), lds, st, p, a, o, want_tile);
+  else
+    hipLaunchKernelGGL(br_k_score<false>, dim3((unsigned)p.N), dim3(64 * waves), lds, st, p, a, o, want_tile);
+}

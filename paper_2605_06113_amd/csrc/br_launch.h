@@ -1,0 +1,14 @@
+// Host-side launchers of the gfx950 kernels (one per kernel; each only enqueues).
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include "br_device.h"
+
+void br_launch_clear(const BrParams &p, hipStream_t st);
+void br_launch_load_init(const BrParams &p, const int32_t *n, const int32_t *kv, const int32_t *rem, const float *pred,
+                         hipStream_t st);
+void br_launch_advance(const BrParams &p, int t, hipStream_t st);
+void br_launch_project(const BrParams &p, hipStream_t st);
+void br_launch_score(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st);
+void br_launch_assign(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st);

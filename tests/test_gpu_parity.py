@@ -1,0 +1,172 @@
+"""Parity of the HIP path (called through the C ABI) against the CPU oracle, element by element
+on the same seeded inputs.  Integer results (assignments, loads, slot tables, queue, BR-0 scores,
+statistics) must be bit-exact; fp32 horizon scores within 1e-5 relative."""
+import sys
+
+import numpy as np
+import pytest
+
+from oracle import br_oracle
+from paper_2605_06113_amd import binding, workloads as wl
+from tests.parity import compare_outputs, compare_state, run_pair
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def test_c1_single_step():
+    cfg = wl.config("c1")
+    _say("c1")
+    oc, r = run_pair(cfg, wl.initial_state(cfg), wl.initial_waiting(cfg), tag="c1")
+    r.close()
+
+
+CASES = [
+    # (G, B, Q, H, extra)                        spans every register layout (Q<=256/512/1024/2048)
+    (4, 16, 32, 0, {}),
+    (16, 24, 256, 0, {}),
+    (16, 24, 200, 0, dict(tie_heavy=True)),
+    (7, 9, 300, 0, dict(R_max=3)),
+    (33, 40, 700, 0, dict(R_max=8, S_greedy=40)),
+    (64, 12, 2048, 0, dict(R_max=5)),
+    (1, 8, 64, 0, {}),
+    (5, 1, 17, 0, dict(R_max=1)),
+    (16, 20, 256, 0, dict(token_watermark=30000, token_cap=28000)),
+    (8, 16, 128, 0, dict(S_greedy=0)),
+    (8, 16, 128, 0, dict(S_greedy=10 ** 6)),
+    (8, 16, 96, 4, dict(gate_pfin=0.0)),
+    (8, 16, 96, 4, dict(gate_pfin=0.5)),
+    (32, 24, 512, 4, dict(gate_pfin=0.0, gamma=0.64, beta=14.67)),
+    (64, 10, 2048, 8, dict(gate_pfin=0.0, R_max=4)),
+    (13, 30, 333, 8, dict(gate_pfin=0.3, R_max=8, tie_heavy=True)),
+    (16, 20, 256, 3, dict(pred_mode=1)),
+    (16, 20, 256, 8, dict(gate_pfin=0.0, token_watermark=40000)),
+    (6, 12, 64, 1, dict(gate_pfin=0.0, gamma=1.0)),
+]
+
+
+@pytest.mark.parametrize("case", range(len(CASES)))
+def test_random_rounds(case):
+    G, B, Q, H, extra = CASES[case]
+    for seed in range(3):
+        kw = dict(extra)
+        _say(f"case {case} seed {seed}: G={G} B={B} Q={Q} H={H} {kw}")
+        cfg, init, arr = wl.random_case(1000 * case + seed, N=6, G=G, B=B, max_wait=Q, H=H,
+                                        fill=[0.3, 0.6, 0.9][seed], s_hi=[4096, 32768, 512][seed], **kw)
+        oc, r = run_pair(cfg, init, arr, tag=f"case{case}/{seed}")
+        # a second and third round on the evolved state, with fresh arrivals and ragged counts
+        for rnd in range(2):
+            _, _, arr2 = wl.random_case(77 + 1000 * case + seed + rnd, N=6, G=G, B=B, max_wait=Q, H=H,
+                                        n_wait=max(1, Q // 3), **kw)
+            ref = oc.route_step(arr2)
+            out = r.route_step(arr2)
+            compare_outputs(ref, out, cfg, f"case{case}/{seed}/r{rnd}")
+            oc.advance(2 + rnd)
+            r.advance(2 + rnd)
+            compare_state(oc, r.state(), cfg, f"case{case}/{seed}/r{rnd}")
+        r.close()
+
+
+def test_edge_cases():
+    # no arrivals at all (NULL), empty queue
+    cfg, init, arr = wl.random_case(5, N=3, G=4, B=8, max_wait=32, H=0)
+    _say("edge: null arrivals")
+    oc, r = br_oracle.OracleCluster(cfg, init), binding.Router(cfg, init)
+    ref, out = oc.route_step(None), r.route_step(None)
+    compare_outputs(ref, out, cfg, "null")
+    compare_state(oc, r.state(), cfg, "null")
+    # zero counts
+    arr0 = wl.Arrivals(np.zeros_like(arr.count), arr.s, arr.o, arr.id, arr.pred)
+    compare_outputs(oc.route_step(arr0), r.route_step(arr0), cfg, "zero")
+    # count beyond the queue cap -> drops; then nothing free -> everything deferred
+    _say("edge: overflow")
+    arrx = wl.Arrivals(np.full_like(arr.count, arr.s.shape[1]), arr.s, arr.o, arr.id, arr.pred)
+    for k in range(3):
+        compare_outputs(oc.route_step(arrx), r.route_step(arrx), cfg, f"overflow{k}")
+        compare_state(oc, r.state(), cfg, f"overflow{k}")
+    r.close()
+    # all workers full: S_tot = 0
+    _say("edge: full")
+    cfg, init, arr = wl.random_case(6, N=2, G=4, B=8, max_wait=32, H=2, fill=1.0, gate_pfin=0.0)
+    oc, r = run_pair(cfg, init, arr, tag="full")
+    r.close()
+    # empty cluster, more requests than slots
+    _say("edge: empty cluster")
+    cfg, init, arr = wl.random_case(8, N=2, G=3, B=4, max_wait=64, H=0, fill=0.0, n_wait=64)
+    oc, r = run_pair(cfg, init, arr, tag="emptycluster")
+    r.close()
+    # maximum sizes
+    _say("edge: max sizes")
+    cfg, init, arr = wl.random_case(9, N=2, G=64, B=1024, max_wait=2048, H=8, fill=0.97, n_wait=2048,
+                                    gate_pfin=0.0, R_max=8, s_hi=32768)
+    oc, r = run_pair(cfg, init, arr, matrix=True, tag="max")
+    r.close()
+
+
+def test_advance_many_steps_closed_form():
+    """n decode steps in one call equal n single steps of the oracle (requests leave mid-way)."""
+    for H in (0, 4):
+        cfg, init, arr = wl.random_case(21 + H, N=5, G=9, B=150, max_wait=64, H=H, fill=0.8, gate_pfin=0.0)
+        _say(f"advance H={H}")
+        oc, r = br_oracle.OracleCluster(cfg, init), binding.Router(cfg, init)
+        for t in (1, 3, 7, 40):
+            oc.advance(t)
+            r.advance(t)
+            compare_state(oc, r.state(), cfg, f"adv{t}")
+        r.close()
+
+
+@pytest.mark.parametrize("name,steps,over", [
+    ("c2", 400, dict()),
+    ("c2", 300, dict(arrival_rate=4.0, seed=1001)),                    # balanced: stages alternate
+    ("c3", 300, dict(gate_pfin=0.0)),
+    ("c3", 200, dict(gate_pfin=0.5, beta=14.67, gamma=0.64)),
+    ("c5", 150, dict(gate_pfin=0.0)),
+])
+def test_replay(name, steps, over):
+    cfg = wl.config(name, **over)
+    _say(f"replay {name} {steps} {over}")
+    tr = wl.arrival_trace(cfg, steps, informative=(name == "c3" and over.get("gate_pfin") == 0.5))
+    oc, r = br_oracle.OracleCluster(cfg), binding.Router(cfg)
+    for k in range(steps):
+        a = tr.step(k)
+        ref = oc.route_step(a, want_scores=(k % 25 == 0))
+        out = r.route_step(a, scores=(k % 25 == 0))
+        compare_outputs(ref, out, cfg, f"{name} step {k}")
+        oc.advance(1)
+        r.advance(1)
+        if k % 25 == 0 or k == steps - 1:
+            compare_state(oc, r.state(), cfg, f"{name} step {k}")
+    r.close()
+
+
+def test_c4_full_size_bench_configuration():
+    """The batched throughput workload at full size, in the launch configuration bench.py times
+    (no score matrix written, best_g / best_i on): every instance against the oracle."""
+    cfg = wl.config("c4")
+    _say("c4 full size")
+    init, arr = wl.initial_state(cfg), wl.initial_waiting(cfg)
+    oc, r = br_oracle.OracleCluster(cfg, init), binding.Router(cfg, init)
+    ref = oc.route_step(arr)
+    out = r.route_step(arr, matrix=False)
+    compare_outputs(ref, out, cfg, "c4")
+    assert (ref["stats"][:, br_oracle.ST["admitted"]] == 256).all()
+    oc.advance(1)
+    r.advance(1)
+    compare_state(oc, r.state(), cfg, "c4")
+    r.close()
+
+
+def test_determinism():
+    cfg, init, arr = wl.random_case(31, N=16, G=16, B=24, max_wait=256, H=4, gate_pfin=0.0, tie_heavy=True)
+    outs = []
+    for _ in range(2):
+        r = binding.Router(cfg, init)
+        outs.append(r.route_step(arr))
+        r.close()
+    for k in outs[0]:
+        assert np.array_equal(outs[0][k], outs[1][k]), k
