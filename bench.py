@@ -1,0 +1,208 @@
+#!/usr/bin/env python3
+"""Benchmark of the BalanceRoute route-step path on one MI355X.
+
+A "step" is one pass of the whole hot path over one batch of synthetic input: one scheduling
+round (score matrix reductions + two-stage assignment; horizon projection when H > 0) followed
+by one decode step, on the batched throughput workload: 4096 independent BR-0 clusters, G=16,
+B=144, 256 waiting requests and 128 active requests per worker each.  Every timed step runs on
+its own copy of the cluster state (prepared before the timed region), so all steps do identical
+work on data that is resident in HBM but not warm in cache.
+
+Prints ONE JSON line (see README for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+# integer vector peak: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz, one int32 op per lane per clock
+ALU_INT_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
+
+
+def cpu_baseline(cfg, init, arr, min_seconds=10.0):
+    """The oracle as it stands, single thread, on the same workload (repeated whole batches)."""
+    from oracle import br_oracle
+    pairs = 0
+    decisions = 0
+    elapsed = 0.0
+    reps = 0
+    while elapsed < min_seconds and reps < 50:
+        oc = br_oracle.OracleCluster(cfg, init)
+        t0 = time.perf_counter()
+        out = oc.route_step(arr, want_scores=True)
+        oc.advance(1)
+        elapsed += time.perf_counter() - t0
+        pairs += int(out["stats"][:, br_oracle.ST["qlen"]].sum()) * cfg.G
+        decisions += int(out["stats"][:, br_oracle.ST["admitted"]].sum())
+        reps += 1
+    return dict(value=pairs / elapsed, unit="pairs/s", cores=1, kind="oracle",
+                sample=f"{reps} x the full batch of {cfg.n_inst} instances (route + decode step), "
+                       f"{elapsed:.1f} s of single-thread CPU time",
+                decisions_per_s=decisions / elapsed)
+
+
+def latency_run(steps, device):
+    """Single-instance BR-H stress shape (G=64, H=8, queue cap 2048): host wall-clock per round."""
+    import torch
+    from paper_2605_06113_amd import binding, workloads as wl
+    cfg = wl.config("c5", gate_pfin=0.0)
+    tr = wl.arrival_trace(cfg, steps)
+    r = binding.Router(cfg, None, device=device)
+    P = r.P
+    t = lambda a, dt: torch.as_tensor(np.ascontiguousarray(a, dt), device=device)
+    count, s, o, ids, pred = t(tr.count, np.int32), t(tr.s, np.int32), t(tr.o, np.int32), t(tr.id, np.int32), \
+        t(tr.pred, np.float32)
+    out = r.alloc_outputs(scores=True, matrix=False)
+    ostruct = r.out_struct(out)
+    import ctypes as C
+    lat = np.zeros(steps)
+    qlen = np.zeros(steps, np.int64)
+    cap = int(tr.s.shape[-1])
+    torch.cuda.synchronize()
+    for k in range(steps):
+        a = binding.Arrivals(count=count[k].data_ptr(), s=s[k].data_ptr(), o=o[k].data_ptr(),
+                             id=ids[k].data_ptr(), pred=pred[k].data_ptr(), arr_cap=cap, pad=0)
+        t0 = time.perf_counter()
+        rc = r.lib.br_route_step(r.ctx, C.byref(a), C.byref(ostruct))
+        r.stream.synchronize()
+        lat[k] = time.perf_counter() - t0
+        assert rc == 0
+        r.advance(1)
+    torch.cuda.synchronize()
+    st = out["stats"].cpu().numpy()
+    steady = lat[steps // 2:]
+    res = dict(workload="c5 shape: BR-H H=8, G=64, B=96, queue cap 2048, MMPP arrivals 60/300, one instance",
+               steps=steps, p50_us=float(np.percentile(lat, 50) * 1e6), p99_us=float(np.percentile(lat, 99) * 1e6),
+               max_us=float(lat.max() * 1e6), steady_p50_us=float(np.percentile(steady, 50) * 1e6),
+               steady_p99_us=float(np.percentile(steady, 99) * 1e6), final_qlen=int(st[0, binding.ST["deferred"]]))
+    r.close()
+    return res
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--latency-steps", type=int, default=1000)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--traffic-kib", type=float, default=None,
+                    help="HBM KiB per launch of the dominant kernel from rocprofv3 --pmc runs, if known")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (instances shard across GPUs with no exchange); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2605_06113_amd import binding, workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(1)
+    device = "cuda:0"
+    binding.load()
+
+    cfg = wl.config("c4")
+    init, arr = wl.initial_state(cfg), wl.initial_waiting(cfg)
+    K, W = args.steps, args.warmup
+    routers = [binding.Router(cfg, init, device=device) for _ in range(K + W)]
+    darr = binding.DeviceArrivals(arr, device, 0)
+    out = routers[0].alloc_outputs(scores=True, matrix=False)
+    torch.cuda.synchronize()
+
+    def step(r):
+        r.route_step_device(darr, out)
+        r.advance(1)
+
+    for r in routers[:W]:
+        step(r)
+    torch.cuda.synchronize()
+    for r in routers[W:]:
+        r.profile(True)
+    t0 = time.perf_counter()
+    for r in routers[W:]:
+        step(r)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    elapsed = t1 - t0
+
+    stats = out["stats"].cpu().numpy()
+    admitted = int(stats[:, binding.ST["admitted"]].sum())
+    qn = int(stats[:, binding.ST["qlen"]].sum())
+    pairs_per_step = qn * cfg.G
+    kern = {k: [0.0, 0] for k in binding.KERNEL_NAMES}
+    for r in routers[W:]:
+        for k, (ms, c) in r.profile_read().items():
+            kern[k][0] += ms
+            kern[k][1] += c
+    for r in routers:
+        r.close()
+
+    # algorithmic work per launch of each kernel (stated in the design doc)
+    N, G, B, Q = cfg.n_inst, cfg.G, cfg.B, cfg.max_wait
+    occupied_after = N * G * 128 + admitted          # slots the decode step touches
+    bytes_advance = occupied_after * 16 + N * G * 16  # kv, rem read + written; L, n read + written
+    bytes_score = qn * 4 + qn * 4 + N * G * (8 + 4)   # s read, best_g written; L, n read, best_i written
+    bytes_assign = qn * (4 + 4 + 4 + 4 + 4) + admitted * 8 + N * G * 16 + N * 16 * 8
+    ops_assign = 4.0 * admitted * (Q)               # per admission: one score (4 int ops) per waiting slot
+    per_kernel = {}
+    for k, (ms, c) in kern.items():
+        if c == 0:
+            continue
+        avg = ms / c
+        e = dict(avg_ms=avg, launches=c)
+        if k == "advance":
+            e.update(bound="hbm", achieved_GBs=bytes_advance / (avg * 1e-3) / 1e9, frac=bytes_advance / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS)
+        elif k == "score":
+            e.update(bound="hbm", achieved_GBs=bytes_score / (avg * 1e-3) / 1e9, frac=bytes_score / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS)
+        elif k == "assign":
+            e.update(bound="alu", achieved_Tops=ops_assign / (avg * 1e-3) / 1e12,
+                     frac=ops_assign / (avg * 1e-3) / 1e12 / ALU_INT_PEAK_TOPS,
+                     hbm_GBs=bytes_assign / (avg * 1e-3) / 1e9)
+        per_kernel[k] = e
+    dom = max((k for k in per_kernel if k != "init"), key=lambda k: per_kernel[k]["avg_ms"])
+    d = per_kernel[dom]
+    if d["bound"] == "hbm":
+        roofline = dict(bound="hbm", kernel=dom, achieved=d["achieved_GBs"], peak=HBM_PEAK_GBS, unit="GB/s",
+                        frac=d["frac"])
+    else:
+        roofline = dict(bound="alu", kernel=dom, achieved=d["achieved_Tops"], peak=ALU_INT_PEAK_TOPS, unit="TOP/s",
+                        frac=d["frac"])
+    roofline["traffic"] = None if args.traffic_kib is None else args.traffic_kib * 1024.0
+    roofline["avg_launch_ms"] = d["avg_ms"]
+    step_bytes = bytes_advance + bytes_score + bytes_assign
+    ms_per_step = elapsed / K * 1e3
+
+    res = dict(metric="F-score pairs/sec (batched route step + decode step); decisions/sec and single-instance "
+                      "route-step latency alongside",
+               value=pairs_per_step * K / elapsed, unit="pairs/s", n_gpus=1, steps=K, warmup=W,
+               ms_per_step=ms_per_step, higher_is_better=True, scaling="weak", vs_baseline=None,
+               dtype="int32", data="synthetic",
+               config=dict(workload="c4: 4096 independent BR-0 instances, G=16, B=144, 256 waiting + 128 active "
+                                    "per worker, one route step + one decode step",
+                           n_inst=N, G=G, B=B, max_wait=Q, H=0, R_max=cfg.R_max, S_greedy=cfg.s_greedy,
+                           parallelism="1 gpu"),
+               decisions_per_s=admitted * K / elapsed,
+               step_hbm_GBs=step_bytes / (ms_per_step * 1e-3) / 1e9,
+               step_hbm_frac=step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+               roofline=roofline, kernels=per_kernel)
+    if args.latency_steps > 0:
+        res["latency"] = latency_run(args.latency_steps, device)
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(cfg, init, arr)
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()
