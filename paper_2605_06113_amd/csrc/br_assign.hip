@@ -2,20 +2,36 @@
 // one wavefront per cluster.
 //
 // The round is a dependent chain: every admission changes L_g, possibly the envelope M and
-// with it every margin.  The chain therefore stays inside one wave, with no barrier and no
-// LDS round trip on its critical path:
+// with it every margin.  The chain therefore stays inside one wave, with no block barrier and
+// no HBM access on its critical path:
 //   - lane g holds worker g's state (free slots, projected loads L_g(k+h), request count);
 //   - the waiting set, ordered by prefill length (largest first, arrival order among equals),
-//     lives in registers, E requests per lane, sorted position = j*64 + lane;
-//   - "pick a worker" and "pick a request" are DPP reductions on int32 keys; Stage-2 subsets
-//     are enumerated one subset mask per lane.
+//     lives in registers, E requests per lane, sorted position = j*64 + lane, with a copy of the
+//     sorted keys in LDS for uniform look-ups;
+//   - "pick a worker" and "pick a request" are DPP reductions on packed int32 keys; Stage-2
+//     subsets are enumerated one subset mask per lane.
+//
+// Stage 1 is taken a whole capacity level at a time where that is provably the same as the
+// one-by-one loop: the workers that share the largest free-slot count are picked once each in
+// order of load, and as long as the largest waiting request still fits the next worker's
+// (horizon-min) margin its score is the largest one (score = const * s in the safe regime of
+// eq. (br0-Fscore) / eq. (brh-Fscore)), the envelope does not move, and the k-th lightest worker
+// takes the k-th largest waiting request.  The first worker for which this fails falls back to
+// the full single-request search.
+//
 // Ties: Stage 1 worker (most free slots, then lightest, then lowest index); Stage 2 worker
 // (most free slots, then largest horizon-min margin, then lowest index); equal request scores
 // resolve to the lowest sorted position; equal subset scores to the lowest mask.
 #include "br_device.h"
 #include "br_launch.h"
+#include "br_sort.h"
 
 #define BR_STAT(o, inst, k) (o).stats[(int64_t)(inst) * 16 + (k)]
+
+template <int E>
+struct Log2E {
+  static constexpr int v = E == 4 ? 2 : E == 8 ? 3 : E == 16 ? 4 : 5;
+};
 
 template <int E, bool BRH>
 __global__ __launch_bounds__(64) void br_k_assign(BrParams p, BrArr a, BrOut o) {
@@ -23,9 +39,15 @@ __global__ __launch_bounds__(64) void br_k_assign(BrParams p, BrArr a, BrOut o) 
   constexpr int NP = E * BR_WAVE;
   constexpr int NH = BRH ? BR_HP + 1 : 1;
   constexpr int IDX_MASK = (1 << BR_IDX_BITS) - 1;
-  int *skey = lds;          // [NP] sort buffer, then the sorted keys (s << 11 | 2047 - arrival position)
-  int *adm = lds + NP;      // [NP] by sorted position: worker << 16 | slot, or -1
-  int *who = lds + 2 * NP;  // [NP] by arrival position: worker, or -1
+  constexpr int PB = 6 + Log2E<E>::v;          // bits of a sorted position
+  constexpr bool PACK1 = !BRH && E <= 16;      // (score, position) of one request fits 32 bits
+  constexpr int BIAS1 = 1 << 21;               // single request: score in (-2^21, 2^15]
+  constexpr int BIAS2 = 1 << 24;               // subset of <= 8 requests: score in (-2^24, 2^18]
+  int *skey = lds;            // [NP] sort buffer, then the sorted keys (s << 11 | 2047 - arrival position)
+  int *adm = lds + NP;        // [NP] by sorted position: worker << 16 | slot, or -1
+  int *who = lds + 2 * NP;    // [NP] by arrival position: worker, or -1
+  int *slots = lds + 3 * NP;  // [64] k-th alive request of a Stage-1 level: s << 11 | sorted position
+  int *win = slots + BR_WAVE; // [8]  Stage-2 candidate window, same packing (16-byte aligned)
 
   const int inst = blockIdx.x, lane = br_lane();
   const int G = p.G;
@@ -51,78 +73,97 @@ __global__ __launch_bounds__(64) void br_k_assign(BrParams p, BrArr a, BrOut o) 
   for (int h = 0; h < NH; ++h) Mh[h] = br_wave_max(Lh[h]);
   int S_tot = br_wave_sum(cap);
 
-  long long sumL = 0;
-  for (int g = 0; g < G; ++g) sumL += __builtin_amdgcn_readlane(Lh[0], g);
-  const long long I_before = (long long)G * Mh[0] - sumL;
+  // sum of loads in two 16-bit halves (each partial sum fits int32 for loads below 2^25)
+  auto sum_loads = [&]() -> long long {
+    const int L0 = act ? Lh[0] : 0;
+    return ((long long)br_wave_sum(L0 >> 16) << 16) + br_wave_sum(L0 & 0xffff);
+  };
+  const long long I_before = o.stats ? (long long)G * Mh[0] - sum_loads() : 0;
 
-  // ---- waiting set: keys into LDS, bitonic sort (descending), back into registers
+  // ---- waiting set: keys (s << 11 | 2047 - arrival position) sorted in registers, descending;
+  //      a copy goes to LDS for uniform look-ups
+  unsigned xk[E];
 #pragma unroll
   for (int j = 0; j < E; ++j) {
     const int i = j * BR_WAVE + lane;
-    int key = 0;
+    unsigned key = 0;
     if (i < qn) {
       int s = i < q0 ? p.qs[qrow + i] : a.s[arow + (i - q0)];
       s = min(max(s, 1), BR_MAX_S_DEV);
-      key = (s << BR_IDX_BITS) | (IDX_MASK - i);
+      key = ((unsigned)s << BR_IDX_BITS) | (unsigned)(IDX_MASK - i);
     }
-    skey[i] = key;
+    xk[j] = key;
     adm[i] = -1;
     who[i] = -1;
   }
-  __syncthreads();
   const bool run = S_tot > 0 && qn > 0;
   if (run) {
     int N2 = BR_WAVE;
     while (N2 < qn) N2 <<= 1;
-    for (int k = 2; k <= N2; k <<= 1)
-      for (int jj = k >> 1; jj > 0; jj >>= 1) {
-        for (int t = lane; t < (N2 >> 1); t += BR_WAVE) {
-          const int i = ((t & ~(jj - 1)) << 1) | (t & (jj - 1));
-          const int l = i | jj;
-          const int x = skey[i], y = skey[l];
-          const bool desc = (i & k) == 0;
-          if ((x < y) == desc) {
-            skey[i] = y;
-            skey[l] = x;
-          }
-        }
-        __syncthreads();
-      }
+    br_sort_desc<E>(xk, lane, N2);
   }
   int sv[E];
   unsigned alive = 0;
 #pragma unroll
   for (int j = 0; j < E; ++j) {
     const int pos = j * BR_WAVE + lane;
-    sv[j] = skey[pos] >> BR_IDX_BITS;
+    skey[pos] = (int)xk[j];
+    sv[j] = (int)(xk[j] >> BR_IDX_BITS);
     if (pos < qn) alive |= 1u << j;
   }
+  __syncthreads();
 
   int n_alive = qn;
+  int jhead = 0;  // blocks below jhead hold no alive request any more
   int stage1 = 0, pops = 0, guard = 0, wdrop = 0, admitted = 0;
 
-  // argmax_i F_g({i}) over alive, admissible requests (lowest sorted position on ties)
-  auto pick_single = [&](const int(&mg)[BR_HP + 1], int room, int &pos, int &swin) -> int {
-    int bk = BR_KEY_NONE, bp = INT32_MAX, bs = 0;
+  auto advance_head = [&]() {
+    while (jhead < E - 1 && br_ballot((alive >> jhead) & 1u) == 0ull) ++jhead;
+  };
+
+  // argmax_i F_g({i}) over alive, admissible requests (lowest sorted position on ties).
+  // Returns false when no request is admissible.
+  auto pick_single = [&](const int(&mg)[BR_HP + 1], int room, int &pos, int &swin) -> bool {
+    if constexpr (PACK1) {
+      unsigned bk = 0;
 #pragma unroll
-    for (int j = 0; j < E; ++j) {
-      if (j * BR_WAVE < qn) {
-        const int s = sv[j];
-        const bool ok = ((alive >> j) & 1u) && s <= room;
-        int key = br_score_key<BRH>(p, mg, s);
-        key = ok ? key : BR_KEY_NONE;
-        if (key > bk) {
-          bk = key;
-          bp = j * BR_WAVE + lane;
-          bs = s;
+      for (int j = 0; j < E; ++j) {
+        if (j >= jhead && j * BR_WAVE < qn) {
+          const int s = sv[j];
+          const int F = s - __mul24(G, max(s - mg[0], 0));
+          const unsigned key = ((unsigned)(F + BIAS1) << PB) | (unsigned)(NP - 1 - (j * BR_WAVE + lane));
+          const bool ok = ((alive >> j) & 1u) && s <= room;
+          bk = max(bk, ok ? key : 0u);
         }
       }
+      const unsigned km = br_wave_umax(bk);
+      if (km == 0u) return false;
+      pos = NP - 1 - (int)(km & (unsigned)(NP - 1));
+    } else {
+      int bk = BR_KEY_NONE, bp = INT32_MAX;
+#pragma unroll
+      for (int j = 0; j < E; ++j) {
+        if (j >= jhead && j * BR_WAVE < qn) {
+          const int s = sv[j];
+          const bool ok = ((alive >> j) & 1u) && s <= room;
+          int key = br_score_key<BRH>(p, mg, s);
+          key = ok ? key : BR_KEY_NONE;
+          if (key > bk) {
+            bk = key;
+            bp = j * BR_WAVE + lane;
+          }
+        }
+      }
+      const int km = br_wave_max(bk);
+      if (km == BR_KEY_NONE) return false;
+      const unsigned long long tie = br_ballot(bk == km);
+      if ((tie & (tie - 1)) == 0ull)
+        pos = __builtin_amdgcn_readlane(bp, (int)__builtin_ctzll(tie));
+      else
+        pos = br_wave_min(bk == km ? bp : INT32_MAX);
     }
-    const int km = br_wave_max(bk);
-    if (km == BR_KEY_NONE) return BR_KEY_NONE;
-    pos = br_wave_min(bk == km ? bp : INT32_MAX);
-    swin = __builtin_amdgcn_readlane(bs, pos & 63);
-    return km;
+    swin = br_uniform(skey[pos] >> BR_IDX_BITS);
+    return true;
   };
 
   // margins of worker g against the current envelope
@@ -134,6 +175,14 @@ __global__ __launch_bounds__(64) void br_k_assign(BrParams p, BrArr a, BrOut o) 
       Lg[h] = __builtin_amdgcn_readlane(Lh[h], g);
       mg[h] = max(Mh[h] - Lg[h], 0);
     }
+  };
+
+  // horizon-min margin of the worker each lane holds
+  auto lane_minm = [&]() {
+    int mn = INT32_MAX;
+#pragma unroll
+    for (int h = 0; h < NH; ++h) mn = min(mn, max(Mh[h] - Lh[h], 0));
+    return mn;
   };
 
   // sticky binding of the request at sorted position pos to worker g
@@ -171,96 +220,178 @@ __global__ __launch_bounds__(64) void br_k_assign(BrParams p, BrArr a, BrOut o) 
       if (!(S_tot > p.S_greedy && n_alive > 0)) break;
       const int capmax = br_wave_max(cap);
       if (capmax <= 0) break;
-      const int Lc = (cap == capmax) ? Lh[0] : INT32_MAX;
-      const int Lmin = br_wave_min(Lc);
-      const int g = (int)__builtin_ctzll(br_ballot(Lc == Lmin));
-      int Lg[NH], mg[BR_HP + 1];
-      margins_of(g, Lg, mg);
-      const int room = p.W > 0 ? p.W - Lg[0] : INT32_MAX;
-      int pos = 0, swin = 0;
-      const int key = pick_single(mg, room, pos, swin);
-      if (key == BR_KEY_NONE) {
-        drop_worker(g, capmax);
-        continue;
+      // the level: workers sharing the largest free-slot count, ranked by (load, index)
+      const bool member = cap == capmax;
+      const int wkey = member ? (int)(((unsigned)Lh[0] << 6) | (unsigned)lane) : INT32_MAX;
+      int rank = 0;
+      for (int g0 = 0; g0 < G; g0 += 4) {  // lanes beyond G hold INT32_MAX and never count
+#pragma unroll
+        for (int u = 0; u < 4; ++u) rank += (__builtin_amdgcn_readlane(wkey, g0 + u) < wkey) ? 1 : 0;
       }
-      bind(pos, g, __builtin_amdgcn_readlane(nn, g));
-      add_load(g, Lg, swin, 1);
-      ++stage1;
+      const int level = __builtin_popcountll(br_ballot(member));
+      const int kmaxp = min(level, min(S_tot - p.S_greedy, n_alive));
+      // the first kmaxp alive requests, by rank, through LDS
+      advance_head();
+      {
+        int base = 0;
+#pragma unroll
+        for (int j = 0; j < E; ++j) {
+          if (j >= jhead && base < kmaxp && j * BR_WAVE < qn) {
+            const bool al = (alive >> j) & 1u;
+            const unsigned long long bal = br_ballot(al);
+            const int ar = base + br_rank_below(bal);
+            if (al && ar < kmaxp) slots[ar] = (sv[j] << BR_IDX_BITS) | (j * BR_WAVE + lane);
+            base += __builtin_popcountll(bal);
+          }
+        }
+      }
+      __syncthreads();
+      const bool cand = member && rank < kmaxp;
+      const int mine = cand ? slots[rank] : 0;
+      const int s_k = mine >> BR_IDX_BITS, pos_k = mine & IDX_MASK;
+      int lim = lane_minm();
+      if (p.W > 0) lim = min(lim, p.W - Lh[0]);
+      const int k0 = br_wave_min((cand && s_k > lim) ? rank : kmaxp);
+      if (k0 > 0) {  // ranks 0..k0-1 are in the safe regime: k-th lightest worker takes k-th largest request
+        const bool take = cand && rank < k0;
+        if (take) adm[pos_k] = (lane << 16) | nn;
+#pragma unroll
+        for (int h = 0; h < NH; ++h) Lh[h] += take ? s_k : 0;
+        nn += take ? 1 : 0;
+        cap -= take ? 1 : 0;
+        const int pstar = br_uniform(slots[k0 - 1] & IDX_MASK);  // last position taken; everything alive before it went too
+        const int jf = pstar >> 6, lf = pstar & 63;
+        const unsigned clear = ((1u << jf) - 1u) | ((lane <= lf) ? (1u << jf) : 0u);
+        alive &= ~clear;
+        S_tot -= k0;
+        n_alive -= k0;
+        admitted += k0;
+        stage1 += k0;
+      }
+      __syncthreads();
+      if (k0 < kmaxp) {  // next worker in order: full single-request search
+        const int g = (int)__builtin_ctzll(br_ballot(member && rank == k0));
+        int Lg[NH], mg[BR_HP + 1];
+        margins_of(g, Lg, mg);
+        const int room = p.W > 0 ? p.W - Lg[0] : INT32_MAX;
+        int pos = 0, swin = 0;
+        if (!pick_single(mg, room, pos, swin)) {
+          drop_worker(g, capmax);
+          continue;
+        }
+        bind(pos, g, __builtin_amdgcn_readlane(nn, g));
+        add_load(g, Lg, swin, 1);
+        ++stage1;
+      }
     }
 
     // ---- Stage 2: refined allocation over the workers that still have free slots
+    // lane-constant pieces of the subset enumeration: lane l of pass c stands for mask c*64 + l
+    int lbit[6];
+#pragma unroll
+    for (int b = 0; b < 6; ++b) lbit[b] = (lane >> b) & 1;
+    const int lpop = __builtin_popcount(lane);
     for (int it = 0; it < bound; ++it) {
       if (n_alive <= 0) break;
       const int capmax = br_wave_max(cap);
       if (capmax <= 0) break;
-      int minm = INT32_MAX;
-#pragma unroll
-      for (int h = 0; h < NH; ++h) minm = min(minm, max(Mh[h] - Lh[h], 0));
-      const int kc = (cap == capmax) ? minm : -1;
-      const int kmaxm = br_wave_max(kc);
-      const int g = (int)__builtin_ctzll(br_ballot(kc == kmaxm));
+      // priority (free slots, horizon-min margin), lowest index on ties
+      const int kc = (cap == capmax) ? (int)(((unsigned)lane_minm() << 6) | (unsigned)(63 - lane)) : -1;
+      const int g = 63 - (br_wave_max(kc) & 63);
       ++pops;
       int Lg[NH], mg[BR_HP + 1];
       margins_of(g, Lg, mg);
       const int room = p.W > 0 ? p.W - Lg[0] : INT32_MAX;
 
-      // candidate window: the first min(R_max, |R_wait|) alive requests in sorted order
+      // candidate window: the first min(R_max, |R_wait|) alive requests in sorted order, ranked
+      // by ballots and passed through LDS so that every lane holds all of them
       const int w = min(p.R_max, n_alive);
-      int wpos[8], ws[8];
-      unsigned wk = alive;
+      advance_head();
+      {
+        int base = 0;
 #pragma unroll
-      for (int b = 0; b < 8; ++b) {
-        wpos[b] = 0;
-        ws[b] = 0;
-        if (b < w) {
-          const int lp = wk ? (__builtin_ctz(wk) * BR_WAVE + lane) : INT32_MAX;
-          const int pb = min(br_wave_min(lp), NP - 1);
-          wk = (lane == (pb & 63)) ? (wk & ~(1u << (pb >> 6))) : wk;
-          wpos[b] = pb;
-          ws[b] = skey[pb] >> BR_IDX_BITS;
+        for (int j = 0; j < E; ++j) {
+          if (j >= jhead && base < w && j * BR_WAVE < qn) {
+            const bool al = (alive >> j) & 1u;
+            const unsigned long long bal = br_ballot(al);
+            const int ar = base + br_rank_below(bal);
+            if (al && ar < w) win[ar] = (sv[j] << BR_IDX_BITS) | (j * BR_WAVE + lane);
+            base += __builtin_popcountll(bal);
+          }
         }
       }
+      __syncthreads();
+      int wv[8];
+      {
+        const int4 lo = *reinterpret_cast<const int4 *>(win);
+        const int4 hi = *reinterpret_cast<const int4 *>(win + 4);
+        wv[0] = lo.x, wv[1] = lo.y, wv[2] = lo.z, wv[3] = lo.w;
+        wv[4] = hi.x, wv[5] = hi.y, wv[6] = hi.z, wv[7] = hi.w;
+      }
+      int ws[8];
+#pragma unroll
+      for (int b = 0; b < 8; ++b) ws[b] = b < w ? (wv[b] >> BR_IDX_BITS) : 0;
 
       // exhaustive subset search, one subset mask per lane (ascending masks, strict improvement)
       const int kmax = min(capmax, p.R_max);
       const int nmask = 1 << w;
       int bestmask = 0, bestkey = BR_KEY_NONE;
-      for (int c = 0; c * BR_WAVE + 1 < nmask; ++c) {
-        const int mask = c * BR_WAVE + lane + 1;
-        int delta = 0;
+      for (int c = 0; c * BR_WAVE < nmask; ++c) {
+        int delta = (c & 1) * ws[6] + (c >> 1) * ws[7];
 #pragma unroll
-        for (int b = 0; b < 8; ++b) delta += ((mask >> b) & 1) ? ws[b] : 0;
-        const bool ok = mask < nmask && __builtin_popcount(mask) <= kmax && delta <= room;
-        int key = br_score_key<BRH>(p, mg, delta);
-        key = ok ? key : BR_KEY_NONE;
-        const int km = br_wave_max(key);
-        if (km > bestkey) {
-          bestkey = km;
-          bestmask = c * BR_WAVE + (int)__builtin_ctzll(br_ballot(key == km)) + 1;
+        for (int b = 0; b < 6; ++b)
+          if (b < w) delta += lbit[b] * ws[b];
+        const int mask = c * BR_WAVE + lane;
+        const bool ok = mask != 0 && mask < nmask && lpop + __builtin_popcount(c) <= kmax && delta <= room;
+        if constexpr (!BRH) {
+          const int F = delta - __mul24(G, max(delta - mg[0], 0));
+          const unsigned key = ok ? (((unsigned)(F + BIAS2) << 6) | (unsigned)(63 - lane)) : 0u;
+          const unsigned km = br_wave_umax(key);
+          if (km != 0u) {
+            const int Fm = (int)(km >> 6) - BIAS2;
+            if (Fm > bestkey) {
+              bestkey = Fm;
+              bestmask = c * BR_WAVE + (63 - (int)(km & 63u));
+            }
+          }
+        } else {
+          int key = br_score_key<BRH>(p, mg, delta);
+          key = ok ? key : BR_KEY_NONE;
+          const int km = br_wave_max(key);
+          if (km > bestkey) {
+            bestkey = km;
+            bestmask = c * BR_WAVE + (int)__builtin_ctzll(br_ballot(key == km));
+          }
         }
       }
 
       if (bestmask == 0 || bestkey <= 0) {  // starvation guard: the single best request anyway
         ++guard;
         int pos = 0, swin = 0;
-        const int key = pick_single(mg, room, pos, swin);
-        if (key == BR_KEY_NONE) {
+        if (!pick_single(mg, room, pos, swin)) {
           drop_worker(g, capmax);
           continue;
         }
         bind(pos, g, __builtin_amdgcn_readlane(nn, g));
         add_load(g, Lg, swin, 1);
       } else {
-        int slot = __builtin_amdgcn_readlane(nn, g);
-        int delta = 0, k = 0;
+        // lane b binds window entry b if chosen; slots follow the order of the window
+        const int slot = __builtin_amdgcn_readlane(nn, g);
+        const bool mine = lane < 8 && ((bestmask >> lane) & 1);
+        if (mine) {
+          const int me = lane == 0 ? wv[0] : lane == 1 ? wv[1] : lane == 2 ? wv[2] : lane == 3 ? wv[3]
+                       : lane == 4 ? wv[4] : lane == 5 ? wv[5] : lane == 6 ? wv[6] : wv[7];
+          adm[me & IDX_MASK] = (g << 16) | (slot + __builtin_popcount(bestmask & ((1 << lane) - 1)));
+        }
+        int delta = 0;
 #pragma unroll
         for (int b = 0; b < 8; ++b)
           if ((bestmask >> b) & 1) {
-            bind(wpos[b], g, slot + k);
+            const int pb = wv[b] & IDX_MASK;
+            alive = (lane == (pb & 63)) ? (alive & ~(1u << (pb >> 6))) : alive;
             delta += ws[b];
-            ++k;
           }
-        add_load(g, Lg, delta, k);
+        add_load(g, Lg, br_uniform(delta), __builtin_popcount(bestmask));
       }
     }
   }
@@ -334,8 +465,7 @@ __global__ __launch_bounds__(64) void br_k_assign(BrParams p, BrArr a, BrOut o) 
   const int Lmax = br_wave_max(Lact);
   const int Lmin = br_wave_min(act ? Lact : INT32_MAX);
   const int over = __builtin_popcountll(br_ballot(act && p.C > 0 && Lact > p.C));
-  sumL = 0;
-  for (int g = 0; g < G; ++g) sumL += __builtin_amdgcn_readlane(Lact, g);
+  const long long sumL = o.stats ? sum_loads() : 0;
   if (lane == 0) {
     p.qlen[inst] = kept;
     if (o.stats) {
@@ -356,17 +486,22 @@ __global__ __launch_bounds__(64) void br_k_assign(BrParams p, BrArr a, BrOut o) 
   }
 }
 
+template <int E, bool BRH>
+static void launch_one(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st) {
+  const size_t lds = (3 * E * BR_WAVE + BR_WAVE + 8) * sizeof(int);  // skey, adm, who, slots, win
+  hipLaunchKernelGGL((br_k_assign<E, BRH>), dim3((unsigned)p.N), dim3(BR_WAVE), lds, st, p, a, o);
+}
+
 template <bool BRH>
 static void launch_e(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st) {
-  const dim3 grid((unsigned)p.N), block(BR_WAVE);
   if (p.Q <= 256)
-    hipLaunchKernelGGL((br_k_assign<4, BRH>), grid, block, 3 * 4 * 64 * 4, st, p, a, o);
+    launch_one<4, BRH>(p, a, o, st);
   else if (p.Q <= 512)
-    hipLaunchKernelGGL((br_k_assign<8, BRH>), grid, block, 3 * 8 * 64 * 4, st, p, a, o);
+    launch_one<8, BRH>(p, a, o, st);
   else if (p.Q <= 1024)
-    hipLaunchKernelGGL((br_k_assign<16, BRH>), grid, block, 3 * 16 * 64 * 4, st, p, a, o);
+    launch_one<16, BRH>(p, a, o, st);
   else
-    hipLaunchKernelGGL((br_k_assign<32, BRH>), grid, block, 3 * 32 * 64 * 4, st, p, a, o);
+    launch_one<32, BRH>(p, a, o, st);
 }
 
 void br_launch_assign(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st) {

@@ -43,36 +43,48 @@ struct BrOut {
 // within half rows, mirror within rows of 16, then carry lane 15 of each row into the
 // next row and lane 31 into the upper half; lane 63 ends up with the full reduction.
 
-template <int CTRL, int ROW_MASK = 0xF>
+// `old` is what a lane keeps when its source is masked off; passing the identity of the
+// combining operation lets the compiler fold the move into the ALU instruction itself.
+template <int CTRL, int ROW_MASK = 0xF, bool BOUND = false>
 __device__ __forceinline__ int br_dpp(int old, int src) {
-  return __builtin_amdgcn_update_dpp(old, src, CTRL, ROW_MASK, 0xF, false);
+  return __builtin_amdgcn_update_dpp(old, src, CTRL, ROW_MASK, 0xF, BOUND);
 }
 
 __device__ __forceinline__ int br_wave_max(int x) {
-  x = max(x, br_dpp<0xB1>(x, x));         // quad_perm [1,0,3,2]
-  x = max(x, br_dpp<0x4E>(x, x));         // quad_perm [2,3,0,1]
-  x = max(x, br_dpp<0x141>(x, x));        // row_half_mirror
-  x = max(x, br_dpp<0x140>(x, x));        // row_mirror
-  x = max(x, br_dpp<0x142, 0xA>(x, x));   // row_bcast:15 into rows 1 and 3
-  x = max(x, br_dpp<0x143, 0xC>(x, x));   // row_bcast:31 into rows 2 and 3
+  x = max(x, br_dpp<0xB1, 0xF, true>(0, x));          // quad_perm [1,0,3,2]
+  x = max(x, br_dpp<0x4E, 0xF, true>(0, x));          // quad_perm [2,3,0,1]
+  x = max(x, br_dpp<0x141, 0xF, true>(0, x));         // row_half_mirror
+  x = max(x, br_dpp<0x140, 0xF, true>(0, x));         // row_mirror
+  x = max(x, br_dpp<0x142, 0xA>(INT32_MIN, x));       // row_bcast:15 into rows 1 and 3
+  x = max(x, br_dpp<0x143, 0xC>(INT32_MIN, x));       // row_bcast:31 into rows 2 and 3
   return __builtin_amdgcn_readlane(x, 63);
 }
 
+__device__ __forceinline__ unsigned br_wave_umax(unsigned x) {
+  x = max(x, (unsigned)br_dpp<0xB1, 0xF, true>(0, (int)x));
+  x = max(x, (unsigned)br_dpp<0x4E, 0xF, true>(0, (int)x));
+  x = max(x, (unsigned)br_dpp<0x141, 0xF, true>(0, (int)x));
+  x = max(x, (unsigned)br_dpp<0x140, 0xF, true>(0, (int)x));
+  x = max(x, (unsigned)br_dpp<0x142, 0xA>(0, (int)x));
+  x = max(x, (unsigned)br_dpp<0x143, 0xC>(0, (int)x));
+  return (unsigned)__builtin_amdgcn_readlane((int)x, 63);
+}
+
 __device__ __forceinline__ int br_wave_min(int x) {
-  x = min(x, br_dpp<0xB1>(x, x));
-  x = min(x, br_dpp<0x4E>(x, x));
-  x = min(x, br_dpp<0x141>(x, x));
-  x = min(x, br_dpp<0x140>(x, x));
-  x = min(x, br_dpp<0x142, 0xA>(x, x));
-  x = min(x, br_dpp<0x143, 0xC>(x, x));
+  x = min(x, br_dpp<0xB1, 0xF, true>(0, x));
+  x = min(x, br_dpp<0x4E, 0xF, true>(0, x));
+  x = min(x, br_dpp<0x141, 0xF, true>(0, x));
+  x = min(x, br_dpp<0x140, 0xF, true>(0, x));
+  x = min(x, br_dpp<0x142, 0xA>(INT32_MAX, x));
+  x = min(x, br_dpp<0x143, 0xC>(INT32_MAX, x));
   return __builtin_amdgcn_readlane(x, 63);
 }
 
 __device__ __forceinline__ int br_wave_sum(int x) {
-  x += br_dpp<0xB1>(0, x);
-  x += br_dpp<0x4E>(0, x);
-  x += br_dpp<0x141>(0, x);
-  x += br_dpp<0x140>(0, x);
+  x += br_dpp<0xB1, 0xF, true>(0, x);
+  x += br_dpp<0x4E, 0xF, true>(0, x);
+  x += br_dpp<0x141, 0xF, true>(0, x);
+  x += br_dpp<0x140, 0xF, true>(0, x);
   x += br_dpp<0x142, 0xA>(0, x);
   x += br_dpp<0x143, 0xC>(0, x);
   return __builtin_amdgcn_readlane(x, 63);
