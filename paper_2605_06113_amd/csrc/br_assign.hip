@@ -34,8 +34,8 @@ struct Log2E {
 };
 
 template <int E, bool BRH>
-__global__ __launch_bounds__(64) void br_k_assign(BrParams p, BrArr a, BrOut o) {
-  extern __shared__ int lds[];
+__global__ __launch_bounds__(256) void br_k_assign(BrParams p, BrArr a, BrOut o) {
+  extern __shared__ int lds_all[];
   constexpr int NP = E * BR_WAVE;
   constexpr int NH = BRH ? BR_HP + 1 : 1;
   constexpr int IDX_MASK = (1 << BR_IDX_BITS) - 1;
@@ -43,13 +43,17 @@ __global__ __launch_bounds__(64) void br_k_assign(BrParams p, BrArr a, BrOut o) 
   constexpr bool PACK1 = !BRH && E <= 16;      // (score, position) of one request fits 32 bits
   constexpr int BIAS1 = 1 << 21;               // single request: score in (-2^21, 2^15]
   constexpr int BIAS2 = 1 << 24;               // subset of <= 8 requests: score in (-2^24, 2^18]
+  // every wave of the block owns one cluster and its own slice of LDS; waves never meet at a barrier
+  const int inst = (int)(blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6));
+  if (inst >= p.N) return;
+  int *lds = lds_all + (threadIdx.x >> 6) * (3 * NP + BR_WAVE + 8);
   int *skey = lds;            // [NP] sort buffer, then the sorted keys (s << 11 | 2047 - arrival position)
   int *adm = lds + NP;        // [NP] by sorted position: worker << 16 | slot, or -1
   int *who = lds + 2 * NP;    // [NP] by arrival position: worker, or -1
   int *slots = lds + 3 * NP;  // [64] k-th alive request of a Stage-1 level: s << 11 | sorted position
   int *win = slots + BR_WAVE; // [8]  Stage-2 candidate window, same packing (16-byte aligned)
 
-  const int inst = blockIdx.x, lane = br_lane();
+  const int lane = br_lane();
   const int G = p.G;
   const int q0 = br_uniform(min(max(p.qlen[inst], 0), p.Q));
   int cnt = a.count ? a.count[inst] : 0;
@@ -111,7 +115,7 @@ __global__ __launch_bounds__(64) void br_k_assign(BrParams p, BrArr a, BrOut o) 
     sv[j] = (int)(xk[j] >> BR_IDX_BITS);
     if (pos < qn) alive |= 1u << j;
   }
-  __syncthreads();
+  br_wave_sync();
 
   int n_alive = qn;
   int jhead = 0;  // blocks below jhead hold no alive request any more
@@ -220,7 +224,8 @@ __global__ __launch_bounds__(64) void br_k_assign(BrParams p, BrArr a, BrOut o) 
       if (!(S_tot > p.S_greedy && n_alive > 0)) break;
       const int capmax = br_wave_max(cap);
       if (capmax <= 0) break;
-      // the level: workers sharing the largest free-slot count, ranked by (load, index)
+      // the level: workers sharing the largest free-slot count, ranked by (load, index); each is
+      // picked exactly once, in rank order, before any other worker can reach this free-slot count
       const bool member = cap == capmax;
       const int wkey = member ? (int)(((unsigned)Lh[0] << 6) | (unsigned)lane) : INT32_MAX;
       int rank = 0;
@@ -245,7 +250,7 @@ __global__ __launch_bounds__(64) void br_k_assign(BrParams p, BrArr a, BrOut o) 
           }
         }
       }
-      __syncthreads();
+      br_wave_sync();
       const bool cand = member && rank < kmaxp;
       const int mine = cand ? slots[rank] : 0;
       const int s_k = mine >> BR_IDX_BITS, pos_k = mine & IDX_MASK;
@@ -268,9 +273,11 @@ __global__ __launch_bounds__(64) void br_k_assign(BrParams p, BrArr a, BrOut o) 
         admitted += k0;
         stage1 += k0;
       }
-      __syncthreads();
-      if (k0 < kmaxp) {  // next worker in order: full single-request search
-        const int g = (int)__builtin_ctzll(br_ballot(member && rank == k0));
+      br_wave_sync();
+      // the rest of the level one worker at a time, in rank order
+      for (int r = k0; r < level; ++r) {
+        if (!(S_tot > p.S_greedy && n_alive > 0)) break;
+        const int g = (int)__builtin_ctzll(br_ballot(member && rank == r));
         int Lg[NH], mg[BR_HP + 1];
         margins_of(g, Lg, mg);
         const int room = p.W > 0 ? p.W - Lg[0] : INT32_MAX;
@@ -320,7 +327,7 @@ __global__ __launch_bounds__(64) void br_k_assign(BrParams p, BrArr a, BrOut o) 
           }
         }
       }
-      __syncthreads();
+      br_wave_sync();
       int wv[8];
       {
         const int4 lo = *reinterpret_cast<const int4 *>(win);
@@ -395,7 +402,7 @@ __global__ __launch_bounds__(64) void br_k_assign(BrParams p, BrArr a, BrOut o) 
       }
     }
   }
-  __syncthreads();
+  br_wave_sync();
 
   // ---- commit the admitted requests into their workers' dense lists
   if (admitted > 0) {
@@ -421,7 +428,7 @@ __global__ __launch_bounds__(64) void br_k_assign(BrParams p, BrArr a, BrOut o) 
       }
     }
   }
-  __syncthreads();
+  br_wave_sync();
 
   // ---- outputs in arrival order; the queue keeps the deferred requests, order preserved
   int kept = 0;
@@ -488,8 +495,10 @@ __global__ __launch_bounds__(64) void br_k_assign(BrParams p, BrArr a, BrOut o) 
 
 template <int E, bool BRH>
 static void launch_one(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st) {
-  const size_t lds = (3 * E * BR_WAVE + BR_WAVE + 8) * sizeof(int);  // skey, adm, who, slots, win
-  hipLaunchKernelGGL((br_k_assign<E, BRH>), dim3((unsigned)p.N), dim3(BR_WAVE), lds, st, p, a, o);
+  // several single-wave clusters share a block so that the chip's per-CU block slots do not cap residency
+  const int wpb = E <= 8 ? 4 : 1;
+  const size_t lds = (size_t)wpb * (3 * E * BR_WAVE + BR_WAVE + 8) * sizeof(int);  // skey, adm, who, slots, win per wave
+  hipLaunchKernelGGL((br_k_assign<E, BRH>), dim3((unsigned)((p.N + wpb - 1) / wpb)), dim3(BR_WAVE * wpb), lds, st, p, a, o);
 }
 
 template <bool BRH>
