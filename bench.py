@@ -27,6 +27,10 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 # integer vector peak: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz, one int32 op per lane per clock
 ALU_INT_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
+# HBM KiB per launch on this workload from rocprofv3 --pmc (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, see
+# profiles/bench_c4_kernels.md); an entry is None when its kernel changed after the counters were taken
+TRAFFIC_KIB = {"assign": 2.0 * 6706.1 + 17485.9, "advance": 2.0 * 37453.2 + 74704.8,
+               "score": 2.0 * 2857.9 + 4352.0}
 
 
 def cpu_baseline(cfg, init, arr, min_seconds=10.0):
@@ -96,6 +100,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--latency-steps", type=int, default=1000)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 256 MiB device copy (reference for scaling rocprofv3 byte counters)")
     ap.add_argument("--traffic-kib", type=float, default=None,
                     help="HBM KiB per launch of the dominant kernel from rocprofv3 --pmc runs, if known")
     args = ap.parse_args()
@@ -112,6 +118,14 @@ def main():
         sys.exit(1)
     device = "cuda:0"
     binding.load()
+
+    if args.calibrate_copy:
+        src = torch.ones(64 * 1024 * 1024, dtype=torch.int32, device=device)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     cfg = wl.config("c4")
     init, arr = wl.initial_state(cfg), wl.initial_waiting(cfg)
@@ -179,7 +193,8 @@ def main():
     else:
         roofline = dict(bound="alu", kernel=dom, achieved=d["achieved_Tops"], peak=ALU_INT_PEAK_TOPS, unit="TOP/s",
                         frac=d["frac"])
-    roofline["traffic"] = None if args.traffic_kib is None else args.traffic_kib * 1024.0
+    kib = args.traffic_kib if args.traffic_kib is not None else TRAFFIC_KIB.get(dom)
+    roofline["traffic"] = None if kib is None else kib * 1024.0
     roofline["avg_launch_ms"] = d["avg_ms"]
     step_bytes = bytes_advance + bytes_score + bytes_assign
     ms_per_step = elapsed / K * 1e3

@@ -46,35 +46,58 @@ __global__ __launch_bounds__(256) void br_k_load_init(BrParams p, const int32_t 
 // footprint goes with it.  t steps are applied in closed form: a request with rem <= t
 // leaves (net load change -kv), the others gain t tokens.  One wave owns one worker's dense
 // list and compacts it in place, order preserved (writes never run ahead of reads).
+template <int NC, int RW>
 __global__ __launch_bounds__(256) void br_k_advance(BrParams p, int t) {
-  const int64_t row = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
-  if (row >= (int64_t)p.N * p.G) return;
+  // each wave owns RW consecutive worker lists; everything it will touch is requested before the
+  // first result is needed, so that enough bytes are in flight to cover the HBM latency, and the
+  // in-place compaction cannot overtake its own reads
+  const int64_t row0 = ((int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6)) * RW;
+  const int64_t rows = (int64_t)p.N * p.G;
+  if (row0 >= rows) return;
   const int lane = br_lane();
-  const int n_g = p.n[row];
-  const int64_t base = row * p.Bs;
-  int kept = 0;  // uniform
-  int dL = 0;
-  for (int c = 0; c < n_g; c += BR_WAVE) {
-    const int j = c + lane;
-    const bool used = j < n_g;
-    const int kv = used ? p.kv[base + j] : 0;
-    const int rem = used ? p.rem[base + j] : 0;
-    const bool stay = used && rem > t;
-    dL += used ? (stay ? t : -kv) : 0;
-    const unsigned long long bal = br_ballot(stay);
-    const int nj = kept + br_rank_below(bal);
-    if (stay) {
-      p.kv[base + nj] = kv + t;
-      p.rem[base + nj] = rem - t;
-      if (p.P && nj != j)
-        for (int q = 0; q < p.P; ++q) p.pred[(base + nj) * p.P + q] = p.pred[(base + j) * p.P + q];
+  int n_g[RW], kv[RW][NC], rem[RW][NC];
+#pragma unroll
+  for (int r = 0; r < RW; ++r) n_g[r] = row0 + r < rows ? p.n[row0 + r] : 0;
+#pragma unroll
+  for (int r = 0; r < RW; ++r) {
+    const int64_t base = (row0 + r) * p.Bs;
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+      const int j = c * BR_WAVE + lane;
+      const bool used = j < n_g[r];
+      kv[r][c] = used ? p.kv[base + j] : 0;
+      rem[r][c] = used ? p.rem[base + j] : 0;
     }
-    kept += __builtin_popcountll(bal);
   }
-  const int tot = br_wave_sum(dL);
-  if (lane == 0) {
-    p.L[row] += tot;
-    p.n[row] = kept;
+#pragma unroll
+  for (int r = 0; r < RW; ++r) {
+    if (row0 + r >= rows) break;
+    const int64_t base = (row0 + r) * p.Bs;
+    int kept = 0;  // uniform
+    int dL = 0;
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+      if (c * BR_WAVE < n_g[r]) {
+        const int j = c * BR_WAVE + lane;
+        const bool used = j < n_g[r];
+        const bool stay = used && rem[r][c] > t;
+        dL += used ? (stay ? t : -kv[r][c]) : 0;
+        const unsigned long long bal = br_ballot(stay);
+        const int nj = kept + br_rank_below(bal);
+        if (stay) {
+          p.kv[base + nj] = kv[r][c] + t;
+          p.rem[base + nj] = rem[r][c] - t;
+          if (p.P && nj != j)
+            for (int q = 0; q < p.P; ++q) p.pred[(base + nj) * p.P + q] = p.pred[(base + j) * p.P + q];
+        }
+        kept += __builtin_popcountll(bal);
+      }
+    }
+    const int tot = br_wave_sum(dL);
+    if (lane == 0) {
+      p.L[row0 + r] += tot;
+      p.n[row0 + r] = kept;
+    }
   }
 }
 
@@ -270,9 +293,25 @@ void br_launch_load_init(const BrParams &p, const int32_t *n, const int32_t *kv,
   hipLaunchKernelGGL(br_k_load_init, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, p, n, kv, rem, pred);
 }
 
+template <int NC, int RW>
+static void launch_advance(const BrParams &p, int t, hipStream_t st) {
+  const int64_t waves = ((int64_t)p.N * p.G + RW - 1) / RW;
+  hipLaunchKernelGGL((br_k_advance<NC, RW>), dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, st, p, t);
+}
+
 void br_launch_advance(const BrParams &p, int t, hipStream_t st) {
-  const int64_t rows = (int64_t)p.N * p.G;
-  hipLaunchKernelGGL(br_k_advance, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, p, t);
+  if (p.B <= 64)
+    launch_advance<1, 4>(p, t, st);
+  else if (p.B <= 128)
+    launch_advance<2, 4>(p, t, st);
+  else if (p.B <= 192)
+    launch_advance<3, 4>(p, t, st);
+  else if (p.B <= 256)
+    launch_advance<4, 2>(p, t, st);
+  else if (p.B <= 512)
+    launch_advance<8, 1>(p, t, st);
+  else
+    launch_advance<16, 1>(p, t, st);
 }
 
 void br_launch_project(const BrParams &p, hipStream_t st) {
@@ -281,7 +320,7 @@ void br_launch_project(const BrParams &p, hipStream_t st) {
 }
 
 void br_launch_score(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st) {
-  int waves = (p.Q + 255) / 256;
+  int waves = (p.Q + 63) / 64;  // one wave per tile of 64 requests, at most 8 waves
   waves = waves < 1 ? 1 : (waves > 8 ? 8 : waves);
   const int want_tile = o.F != nullptr;
   auto lds_words = [&](int w) {
