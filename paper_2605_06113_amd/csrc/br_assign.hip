@@ -25,8 +25,7 @@
 #include "br_device.h"
 #include "br_launch.h"
 #include "br_sort.h"
-
-#define BR_STAT(o, inst, k) (o).stats[(int64_t)(inst) * 16 + (k)]
+#include "br_assign_common.h"
 
 template <int E>
 struct Log2E {
@@ -134,7 +133,7 @@ __global__ __launch_bounds__(256) void br_k_assign(BrParams p, BrArr a, BrOut o)
       for (int j = 0; j < E; ++j) {
         if (j >= jhead && j * BR_WAVE < qn) {
           const int s = sv[j];
-          const int F = s - __mul24(G, max(s - mg[0], 0));
+          const int F = s - (int)((unsigned)(max(s - mg[0], 0) & 0xffff) * (unsigned)(G & 0x7f));
           const unsigned key = ((unsigned)(F + BIAS1) << PB) | (unsigned)(NP - 1 - (j * BR_WAVE + lane));
           const bool ok = ((alive >> j) & 1u) && s <= room;
           bk = max(bk, ok ? key : 0u);
@@ -351,7 +350,7 @@ __global__ __launch_bounds__(256) void br_k_assign(BrParams p, BrArr a, BrOut o)
         const int mask = c * BR_WAVE + lane;
         const bool ok = mask != 0 && mask < nmask && lpop + __builtin_popcount(c) <= kmax && delta <= room;
         if constexpr (!BRH) {
-          const int F = delta - __mul24(G, max(delta - mg[0], 0));
+          const int F = delta - (int)((unsigned)(max(delta - mg[0], 0) & 0x7ffff) * (unsigned)(G & 0x7f));
           const unsigned key = ok ? (((unsigned)(F + BIAS2) << 6) | (unsigned)(63 - lane)) : 0u;
           const unsigned km = br_wave_umax(key);
           if (km != 0u) {
@@ -404,93 +403,14 @@ __global__ __launch_bounds__(256) void br_k_assign(BrParams p, BrArr a, BrOut o)
   }
   br_wave_sync();
 
-  // ---- commit the admitted requests into their workers' dense lists
-  if (admitted > 0) {
-#pragma unroll
-    for (int j = 0; j < E; ++j) {
-      const int pos = j * BR_WAVE + lane;
-      if (pos < qn) {
-        const int ad = adm[pos];
-        if (ad >= 0) {
-          const int key = skey[pos];
-          const int idx = IDX_MASK - (key & IDX_MASK);
-          const int g = ad >> 16, slot = ad & 0xffff;
-          if (g < G && slot < p.B && idx < qn) {
-            const int64_t row = ((int64_t)inst * G + g) * p.Bs + slot;
-            const bool old = idx < q0;
-            p.kv[row] = key >> BR_IDX_BITS;
-            p.rem[row] = old ? p.qo[qrow + idx] : max(a.o[arow + (idx - q0)], 1);
-            for (int q = 0; q < p.P; ++q)
-              p.pred[row * p.P + q] = old ? p.qpred[(qrow + idx) * p.P + q] : a.pred[(arow + (idx - q0)) * p.P + q];
-            who[idx] = g;
-          }
-        }
-      }
-    }
-  }
-  br_wave_sync();
-
-  // ---- outputs in arrival order; the queue keeps the deferred requests, order preserved
-  int kept = 0;
-#pragma unroll
-  for (int j = 0; j < E; ++j) {
-    const int i = j * BR_WAVE + lane;
-    if (j * BR_WAVE < p.Q) {
-      const bool in = i < qn;
-      const int wg = in ? who[i] : -1;
-      const bool old = i < q0;
-      int id = -1;
-      if (in) id = old ? p.qid[qrow + i] : (a.id ? a.id[arow + (i - q0)] : i - q0);
-      if (i < p.Q) {
-        if (o.assign) o.assign[qrow + i] = wg;
-        if (o.assign_id) o.assign_id[qrow + i] = id;
-      }
-      const bool keep = in && wg < 0;
-      const unsigned long long bal = br_ballot(keep);
-      const int ni = kept + br_rank_below(bal);
-      if (keep && (ni != i || !old)) {
-        int s = old ? p.qs[qrow + i] : a.s[arow + (i - q0)];
-        s = min(max(s, 1), BR_MAX_S_DEV);
-        const int oo = old ? p.qo[qrow + i] : max(a.o[arow + (i - q0)], 1);
-        float pr[BR_HP];
-        for (int q = 0; q < p.P; ++q) pr[q] = old ? p.qpred[(qrow + i) * p.P + q] : a.pred[(arow + (i - q0)) * p.P + q];
-        p.qs[qrow + ni] = s;
-        p.qo[qrow + ni] = oo;
-        p.qid[qrow + ni] = id;
-        for (int q = 0; q < p.P; ++q) p.qpred[(qrow + ni) * p.P + q] = pr[q];
-      }
-      kept += __builtin_popcountll(bal);
-    }
-  }
-
-  // ---- state and statistics
-  if (act) {
-    p.L[wrow] = Lh[0];
-    p.n[wrow] = nn;
-  }
-  const int Lact = Lh[0];
-  const int Lmax = br_wave_max(Lact);
-  const int Lmin = br_wave_min(act ? Lact : INT32_MAX);
-  const int over = __builtin_popcountll(br_ballot(act && p.C > 0 && Lact > p.C));
-  const long long sumL = o.stats ? sum_loads() : 0;
-  if (lane == 0) {
-    p.qlen[inst] = kept;
-    if (o.stats) {
-      BR_STAT(o, inst, 0) = admitted;
-      BR_STAT(o, inst, 1) = kept;
-      BR_STAT(o, inst, 2) = cnt - (qn - q0);
-      BR_STAT(o, inst, 3) = stage1;
-      BR_STAT(o, inst, 4) = pops;
-      BR_STAT(o, inst, 5) = guard;
-      BR_STAT(o, inst, 6) = over;
-      BR_STAT(o, inst, 7) = I_before;
-      BR_STAT(o, inst, 8) = (long long)G * Lmax - sumL;
-      BR_STAT(o, inst, 9) = (long long)Lmax - Lmin;
-      BR_STAT(o, inst, 10) = qn;
-      BR_STAT(o, inst, 11) = wdrop;
-      for (int k = 12; k < 16; ++k) BR_STAT(o, inst, k) = 0;
-    }
-  }
+  BrRoundCounts rc;
+  rc.admitted = admitted;
+  rc.stage1 = stage1;
+  rc.pops = pops;
+  rc.guard = guard;
+  rc.wdrop = wdrop;
+  rc.I_before = I_before;
+  br_assign_epilogue<E>(inst, lane, q0, qn, cnt, skey, adm, who, Lh[0], nn, rc);
 }
 
 template <int E, bool BRH>

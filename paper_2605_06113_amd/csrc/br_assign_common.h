@@ -1,0 +1,155 @@
+// Shared tail of the assignment kernels: writes the admitted requests into their workers'
+// lists, emits the per-entry outputs in arrival order, compacts the waiting queue in place and
+// stores worker state and statistics.  Everything here is lane-parallel; `adm` (by sorted
+// position: worker << 16 | slot, or -1) and the sorted keys in `skey` come from the round.
+#pragma once
+
+#include "br_device.h"
+
+#define BR_STAT(o, inst, k) (o).stats[(int64_t)(inst) * 16 + (k)]
+
+struct BrRoundCounts {
+  int admitted, stage1, pops, guard, wdrop;
+  long long I_before;
+};
+
+// What the tail needs of the kernel arguments.  The assignment kernels take (BrParams, BrArr,
+// BrOut) by value; keeping all of that in scalar registers across the admission loops starves
+// them, so the tail reads its own copy from the kernel-argument segment when it starts.
+struct BrTailArgs {
+  int32_t *L, *n, *kv, *rem;
+  float *pred;
+  int32_t *qlen, *qs, *qo, *qid;
+  float *qpred;
+  const int32_t *as, *ao, *aid;
+  const float *apred;
+  int32_t *assign, *assign_id;
+  long long *stats;
+  int32_t G, B, Bs, Q, P, C, arr_cap;
+};
+
+static_assert(sizeof(BrParams) == 208 && sizeof(BrArr) == 48 && sizeof(BrOut) == 48, "kernel argument layout");
+
+__device__ __forceinline__ BrTailArgs br_tail_args() {
+  typedef __attribute__((address_space(4))) const char kchar_t;
+  typedef __attribute__((address_space(4))) const BrParams kparams_t;
+  typedef __attribute__((address_space(4))) const BrArr karr_t;
+  typedef __attribute__((address_space(4))) const BrOut kout_t;
+  kchar_t *ka = (kchar_t *)__builtin_amdgcn_kernarg_segment_ptr();
+  asm volatile("" : "+s"(ka));  // the loads below may not move above this point
+  kparams_t *kp = (kparams_t *)ka;
+  karr_t *kaa = (karr_t *)(ka + sizeof(BrParams));
+  kout_t *ko = (kout_t *)(ka + sizeof(BrParams) + sizeof(BrArr));
+  BrTailArgs t;
+  t.L = kp->L, t.n = kp->n, t.kv = kp->kv, t.rem = kp->rem, t.pred = kp->pred;
+  t.qlen = kp->qlen, t.qs = kp->qs, t.qo = kp->qo, t.qid = kp->qid, t.qpred = kp->qpred;
+  t.as = kaa->s, t.ao = kaa->o, t.aid = kaa->id, t.apred = kaa->pred;
+  t.assign = ko->assign, t.assign_id = ko->assign_id, t.stats = ko->stats;
+  t.G = kp->G, t.B = kp->B, t.Bs = kp->Bs, t.Q = kp->Q, t.P = kp->P, t.C = kp->C;
+  t.arr_cap = kaa->arr_cap;
+  return t;
+}
+
+template <int E>
+__device__ __forceinline__ void br_assign_epilogue(int inst, int lane, int q0, int qn, int cnt, const int *skey,
+                                                   const int *adm, int *who, int Lcur, int nn,
+                                                   const BrRoundCounts &rc) {
+  constexpr int IDX_MASK = (1 << BR_IDX_BITS) - 1;
+  const BrTailArgs t = br_tail_args();
+  const int G = t.G;
+  const bool act = lane < G;
+  const int64_t wrow = (int64_t)inst * G + lane;
+  const int64_t qrow = (int64_t)inst * t.Q, arow = (int64_t)inst * t.arr_cap;
+  const int admitted = rc.admitted;
+  // ---- commit the admitted requests into their workers' dense lists
+  if (admitted > 0) {
+#pragma unroll
+    for (int j = 0; j < E; ++j) {
+      const int pos = j * BR_WAVE + lane;
+      if (pos < qn) {
+        const int ad = adm[pos];
+        if (ad >= 0) {
+          const int key = skey[pos];
+          const int idx = IDX_MASK - (key & IDX_MASK);
+          const int g = ad >> 16, slot = ad & 0xffff;
+          if (g < G && slot < t.B && idx < qn) {
+            const int64_t row = ((int64_t)inst * G + g) * t.Bs + slot;
+            const bool old = idx < q0;
+            t.kv[row] = key >> BR_IDX_BITS;
+            t.rem[row] = old ? t.qo[qrow + idx] : max(t.ao[arow + (idx - q0)], 1);
+            for (int q = 0; q < t.P; ++q)
+              t.pred[row * t.P + q] = old ? t.qpred[(qrow + idx) * t.P + q] : t.apred[(arow + (idx - q0)) * t.P + q];
+            who[idx] = g;
+          }
+        }
+      }
+    }
+  }
+  br_wave_sync();
+
+  // ---- outputs in arrival order; the queue keeps the deferred requests, order preserved
+  int kept = 0;
+#pragma unroll
+  for (int j = 0; j < E; ++j) {
+    const int i = j * BR_WAVE + lane;
+    if (j * BR_WAVE < t.Q) {
+      const bool in = i < qn;
+      const int wg = in ? who[i] : -1;
+      const bool old = i < q0;
+      int id = -1;
+      if (in) id = old ? t.qid[qrow + i] : (t.aid ? t.aid[arow + (i - q0)] : i - q0);
+      if (i < t.Q) {
+        if (t.assign) t.assign[qrow + i] = wg;
+        if (t.assign_id) t.assign_id[qrow + i] = id;
+      }
+      const bool keep = in && wg < 0;
+      const unsigned long long bal = br_ballot(keep);
+      const int ni = kept + br_rank_below(bal);
+      if (keep && (ni != i || !old)) {
+        int s = old ? t.qs[qrow + i] : t.as[arow + (i - q0)];
+        s = min(max(s, 1), BR_MAX_S_DEV);
+        const int oo = old ? t.qo[qrow + i] : max(t.ao[arow + (i - q0)], 1);
+        float pr[BR_HP];
+        for (int q = 0; q < t.P; ++q) pr[q] = old ? t.qpred[(qrow + i) * t.P + q] : t.apred[(arow + (i - q0)) * t.P + q];
+        t.qs[qrow + ni] = s;
+        t.qo[qrow + ni] = oo;
+        t.qid[qrow + ni] = id;
+        for (int q = 0; q < t.P; ++q) t.qpred[(qrow + ni) * t.P + q] = pr[q];
+      }
+      kept += __builtin_popcountll(bal);
+    }
+  }
+
+  // ---- state and statistics
+  if (act) {
+    t.L[wrow] = Lcur;
+    t.n[wrow] = nn;
+  }
+  const int Lact = Lcur;
+  const int Lmax = br_wave_max(Lact);
+  const int Lmin = br_wave_min(act ? Lact : INT32_MAX);
+  const int over = __builtin_popcountll(br_ballot(act && t.C > 0 && Lact > t.C));
+  long long sumL = 0;
+  if (t.stats) {
+    const int L0 = act ? Lcur : 0;
+    sumL = ((long long)br_wave_sum(L0 >> 16) << 16) + br_wave_sum(L0 & 0xffff);
+  }
+  if (lane == 0) {
+    t.qlen[inst] = kept;
+    if (t.stats) {
+      BR_STAT(t, inst, 0) = admitted;
+      BR_STAT(t, inst, 1) = kept;
+      BR_STAT(t, inst, 2) = cnt - (qn - q0);
+      BR_STAT(t, inst, 3) = rc.stage1;
+      BR_STAT(t, inst, 4) = rc.pops;
+      BR_STAT(t, inst, 5) = rc.guard;
+      BR_STAT(t, inst, 6) = over;
+      BR_STAT(t, inst, 7) = rc.I_before;
+      BR_STAT(t, inst, 8) = (long long)G * Lmax - sumL;
+      BR_STAT(t, inst, 9) = (long long)Lmax - Lmin;
+      BR_STAT(t, inst, 10) = qn;
+      BR_STAT(t, inst, 11) = rc.wdrop;
+      for (int k = 12; k < 16; ++k) BR_STAT(t, inst, k) = 0;
+    }
+  }
+}
