@@ -93,6 +93,58 @@ def latency_run(steps, device):
     return res
 
 
+def brh_run(device, steps=6, warmup=2):
+    """Batched BR-H round (horizon projection + scores + assignment) and decode step:
+    1024 clusters of the c3 shape (G=32, B=96, H=4), 76 active requests per worker, 256 waiting."""
+    import torch
+    from paper_2605_06113_amd import binding, workloads as wl
+    cfg = wl.config("c3", n_inst=1024, gate_pfin=0.0, token_watermark=0, token_cap=0, init_active_per_worker=76, init_kv_lo=256, init_kv_hi=8192,
+                    init_rem_lo=1, init_rem_hi=1024, init_waiting=256)
+    init, arr = wl.initial_state(cfg), wl.initial_waiting(cfg)
+    routers = [binding.Router(cfg, init, device=device) for _ in range(steps + warmup)]
+    darr = binding.DeviceArrivals(arr, device, routers[0].P)
+    out = routers[0].alloc_outputs(scores=True, matrix=False)
+    torch.cuda.synchronize()
+    for r in routers[:warmup]:
+        r.route_step_device(darr, out)
+        r.advance(1)
+    torch.cuda.synchronize()
+    for r in routers[warmup:]:
+        r.profile(True)
+    t0 = time.perf_counter()
+    for r in routers[warmup:]:
+        r.route_step_device(darr, out)
+        r.advance(1)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    stats = out["stats"].cpu().numpy()
+    admitted = int(stats[:, binding.ST["admitted"]].sum())
+    qn = int(stats[:, binding.ST["qlen"]].sum())
+    kern = {k: [0.0, 0] for k in binding.KERNEL_NAMES}
+    for r in routers[warmup:]:
+        for k, (ms, c) in r.profile_read().items():
+            kern[k][0] += ms
+            kern[k][1] += c
+    for r in routers:
+        r.close()
+    N, G, H, P = cfg.n_inst, cfg.G, cfg.H, cfg.H
+    active = N * G * 76
+    bytes_k = dict(project=active * (4 + 4 * P) + N * G * 4 + N * (H + 1) * 4 * (2 * G + 1) + N * G * 4,
+                   advance=(active + admitted) * 16 + N * G * 16)
+    res = dict(workload="1024 clusters of the c3 shape: BR-H H=4, G=32, B=96, 76 active per worker, 256 waiting",
+               ms_per_step=elapsed / steps * 1e3, pairs_per_s=qn * G * steps / elapsed,
+               decisions_per_s=admitted * steps / elapsed, kernels={})
+    for k, (ms, c) in kern.items():
+        if c == 0 or k == "init":
+            continue
+        e = dict(avg_ms=ms / c, launches=c)
+        if k in bytes_k:
+            gbs = bytes_k[k] / (ms / c * 1e-3) / 1e9
+            e.update(bound="hbm", achieved_GBs=gbs, frac=gbs / HBM_PEAK_GBS)
+        res["kernels"][k] = e
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -100,6 +152,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--latency-steps", type=int, default=1000)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-brh", action="store_true", help="skip the batched BR-H side measurement")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (reference for scaling rocprofv3 byte counters)")
     ap.add_argument("--traffic-kib", type=float, default=None,
@@ -212,6 +265,8 @@ def main():
                step_hbm_GBs=step_bytes / (ms_per_step * 1e-3) / 1e9,
                step_hbm_frac=step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
                roofline=roofline, kernels=per_kernel)
+    if not args.no_brh:
+        res["brh_batched"] = brh_run(device)
     if args.latency_steps > 0:
         res["latency"] = latency_run(args.latency_steps, device)
     if not args.no_cpu_baseline:

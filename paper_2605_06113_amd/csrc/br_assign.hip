@@ -124,6 +124,11 @@ __global__ __launch_bounds__(256) void br_k_assign(BrParams p, BrArr a, BrOut o)
     while (jhead < E - 1 && br_ballot((alive >> jhead) & 1u) == 0ull) ++jhead;
   };
 
+  // lane-constant part of a packed (score, position) key: bias << PB | (NP-1 - position)
+  unsigned ckey[E];
+#pragma unroll
+  for (int j = 0; j < E; ++j) ckey[j] = ((unsigned)BIAS1 << PB) + (unsigned)(NP - 1 - (j * BR_WAVE + lane));
+
   // argmax_i F_g({i}) over alive, admissible requests (lowest sorted position on ties).
   // Returns false when no request is admissible.
   auto pick_single = [&](const int(&mg)[BR_HP + 1], int room, int &pos, int &swin) -> bool {
@@ -131,11 +136,12 @@ __global__ __launch_bounds__(256) void br_k_assign(BrParams p, BrArr a, BrOut o)
       unsigned bk = 0;
 #pragma unroll
       for (int j = 0; j < E; ++j) {
-        if (j >= jhead && j * BR_WAVE < qn) {
+        if (E <= 8 || (j >= jhead && j * BR_WAVE < qn)) {  // few registers: cheaper to score all than to branch
           const int s = sv[j];
           const int F = s - (int)((unsigned)(max(s - mg[0], 0) & 0xffff) * (unsigned)(G & 0x7f));
-          const unsigned key = ((unsigned)(F + BIAS1) << PB) | (unsigned)(NP - 1 - (j * BR_WAVE + lane));
-          const bool ok = ((alive >> j) & 1u) && s <= room;
+          const unsigned key = ((unsigned)F << PB) + ckey[j];
+          bool ok = (alive >> j) & 1u;
+          if (p.W > 0) ok = ok && s <= room;
           bk = max(bk, ok ? key : 0u);
         }
       }

@@ -102,57 +102,84 @@ __global__ __launch_bounds__(256) void br_k_advance(BrParams p, int t) {
 }
 
 // ------------------------------------------------------------------ horizon projection
-// Preparation step of Alg. BR-H: per worker and offset h = 0..H the projected load
-// L_g(k+h) = sum over active requests of (kv + h) while h <= c_hat (eq. (wprofile-new)); then the
-// envelope M_h = max_g L_g(k+h), margins m_{g,h} = (M_h - L_g(k+h))_+ and min_h m_{g,h}.
-// One block per cluster; each wave walks whole worker lists.
-__global__ __launch_bounds__(1024) void br_k_project(BrParams p) {
-  __shared__ int sLh[BR_MAX_G_DEV * (BR_HP + 1)];
-  __shared__ int sMh[BR_HP + 1];
-  const int inst = blockIdx.x;
+// Preparation step of Alg. BR-H, part 1: per worker and offset h = 0..H the projected load
+// L_g(k+h) = sum over active requests of (kv + h) while h <= c_hat (eq. (wprofile-new)).
+// A pure stream over the active lists: one wave owns RW consecutive worker lists and requests
+// everything it will read (kv and the prediction inputs, as 16-byte loads when P is 4 or 8)
+// before the first use; per list it then forms c_hat per request, H+1 integer partial sums per
+// lane, and H+1 DPP wave sums.
+template <int NC, int RW>
+__global__ __launch_bounds__(256) void br_k_project_rows(BrParams p) {
+  const int64_t row0 = ((int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6)) * RW;
+  const int64_t rows = (int64_t)p.N * p.G;
+  if (row0 >= rows) return;
   const int lane = br_lane();
-  const int wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
   const int H1 = p.H + 1;
-  for (int g = wave; g < p.G; g += nw) {
-    const int64_t row = (int64_t)inst * p.G + g;
-    const int n_g = p.n[row];
-    const int64_t base = row * p.Bs;
+  int n_g[RW], kv[RW][NC];
+  float pr[RW][NC][BR_HP];
+#pragma unroll
+  for (int r = 0; r < RW; ++r) n_g[r] = row0 + r < rows ? p.n[row0 + r] : 0;
+#pragma unroll
+  for (int r = 0; r < RW; ++r) {
+    const int64_t base = (row0 + r) * p.Bs;
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+      const int j = c * BR_WAVE + lane;
+      const bool used = j < n_g[r];
+      kv[r][c] = used ? p.kv[base + j] : 0;
+      if (used) {
+        br_load_pred(p, p.pred + (base + j) * p.P, pr[r][c]);
+      } else {
+#pragma unroll
+        for (int q = 0; q < BR_HP; ++q) pr[r][c][q] = 0.0f;
+      }
+    }
+  }
+#pragma unroll
+  for (int r = 0; r < RW; ++r) {
+    if (row0 + r >= rows) break;
     int acc[BR_HP + 1];
 #pragma unroll
     for (int h = 0; h <= BR_HP; ++h) acc[h] = 0;
-    for (int j = lane; j < n_g; j += BR_WAVE) {
-      const int kv = p.kv[base + j];
-      const float c = br_chat(p, p.pred + (base + j) * p.P);
 #pragma unroll
-      for (int h = 0; h <= BR_HP; ++h)
-        if (h <= p.H && (float)h <= c) acc[h] += kv + h;
+    for (int c = 0; c < NC; ++c) {
+      const int j = c * BR_WAVE + lane;
+      if (j < n_g[r]) {
+        const float ch = br_chat_vals(p, pr[r][c]);
+#pragma unroll
+        for (int h = 0; h <= BR_HP; ++h)
+          if (h <= p.H && (float)h <= ch) acc[h] += kv[r][c] + h;
+      }
     }
 #pragma unroll
     for (int h = 0; h <= BR_HP; ++h) {
-      const int v = br_wave_sum(acc[h]);
-      if (lane == 0) sLh[g * (BR_HP + 1) + h] = v;
+      if (h <= p.H) {
+        const int v = br_wave_sum(acc[h]);
+        if (lane == 0) p.Lh[(row0 + r) * H1 + h] = v;
+      }
     }
   }
-  __syncthreads();
-  if ((int)threadIdx.x < H1) {
-    int M = sLh[threadIdx.x];
-    for (int g = 1; g < p.G; ++g) M = max(M, sLh[g * (BR_HP + 1) + threadIdx.x]);
-    sMh[threadIdx.x] = M;
-    p.Mh[(int64_t)inst * H1 + threadIdx.x] = M;
+}
+
+// Part 2: envelope M_h = max_g L_g(k+h), margins m_{g,h} = (M_h - L_g(k+h))_+ and min_h m_{g,h};
+// one wave per cluster, lane g holds worker g.
+__global__ __launch_bounds__(256) void br_k_envelope(BrParams p) {
+  const int inst = (int)(blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6));
+  if (inst >= p.N) return;
+  const int lane = br_lane();
+  const bool act = lane < p.G;
+  const int H1 = p.H + 1;
+  const int64_t wrow = (int64_t)inst * p.G + lane;
+  int mn = INT32_MAX;
+  for (int h = 0; h < H1; ++h) {
+    const int lh = act ? p.Lh[wrow * H1 + h] : BR_LOW;
+    const int M = br_wave_max(lh);
+    const int m = max(M - lh, 0);
+    mn = min(mn, m);
+    if (act) p.mh[wrow * H1 + h] = m;
+    if (lane == 0) p.Mh[(int64_t)inst * H1 + h] = M;
   }
-  __syncthreads();
-  for (int e = threadIdx.x; e < p.G * H1; e += blockDim.x) {
-    const int g = e / H1, h = e - g * H1;
-    const int lh = sLh[g * (BR_HP + 1) + h];
-    p.Lh[((int64_t)inst * p.G + g) * H1 + h] = lh;
-    p.mh[((int64_t)inst * p.G + g) * H1 + h] = max(sMh[h] - lh, 0);
-  }
-  if ((int)threadIdx.x < p.G) {
-    const int g = threadIdx.x;
-    int mn = INT32_MAX;
-    for (int h = 0; h < H1; ++h) mn = min(mn, max(sMh[h] - sLh[g * (BR_HP + 1) + h], 0));
-    p.minm[(int64_t)inst * p.G + g] = mn;
-  }
+  if (act) p.minm[wrow] = mn;
 }
 
 // ------------------------------------------------------------------ F-score matrix + reductions
@@ -314,9 +341,26 @@ void br_launch_advance(const BrParams &p, int t, hipStream_t st) {
     launch_advance<16, 1>(p, t, st);
 }
 
+template <int NC, int RW>
+static void launch_project_rows(const BrParams &p, hipStream_t st) {
+  const int64_t waves = ((int64_t)p.N * p.G + RW - 1) / RW;
+  hipLaunchKernelGGL((br_k_project_rows<NC, RW>), dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, st, p);
+}
+
 void br_launch_project(const BrParams &p, hipStream_t st) {
-  const int waves = p.G < 16 ? p.G : 16;
-  hipLaunchKernelGGL(br_k_project, dim3((unsigned)p.N), dim3(64 * waves), 0, st, p);
+  if (p.B <= 64)
+    launch_project_rows<1, 4>(p, st);
+  else if (p.B <= 128)
+    launch_project_rows<2, 4>(p, st);
+  else if (p.B <= 192)
+    launch_project_rows<3, 2>(p, st);
+  else if (p.B <= 256)
+    launch_project_rows<4, 2>(p, st);
+  else if (p.B <= 512)
+    launch_project_rows<8, 1>(p, st);
+  else
+    launch_project_rows<16, 1>(p, st);
+  hipLaunchKernelGGL(br_k_envelope, dim3((unsigned)((p.N + 3) / 4)), dim3(256), 0, st, p);
 }
 
 void br_launch_score(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st) {

@@ -161,6 +161,51 @@ def test_c4_full_size_bench_configuration():
     r.close()
 
 
+@pytest.mark.parametrize("name,over", [("c2", {}), ("c3", dict(gate_pfin=0.5)), ("c5", dict(gate_pfin=0.0))])
+def test_replay_full_length(name, over):
+    """The replay workloads at their full length (2000 / 1000 / 10000 decode steps): assignments and
+    statistics of every step, the whole state every 250 steps."""
+    cfg = wl.config(name, **over)
+    _say(f"full replay {name} {cfg.steps} steps")
+    tr = wl.arrival_trace(cfg)
+    oc, r = br_oracle.OracleCluster(cfg), binding.Router(cfg)
+    out = r.alloc_outputs(scores=False)
+    for k in range(cfg.steps):
+        a = tr.step(k)
+        ref = oc.route_step(a, want_scores=False)
+        darr = binding.DeviceArrivals(a, r.device, r.P)
+        r.route_step_device(darr, out)
+        r.advance(1)
+        r.stream.synchronize()
+        got = {kk: out[kk].cpu().numpy() for kk in ("assign", "assign_id", "stats")}
+        compare_outputs(ref, got, cfg, f"{name} step {k}")
+        oc.advance(1)
+        if k % 250 == 0 or k == cfg.steps - 1:
+            compare_state(oc, r.state(), cfg, f"{name} step {k}")
+        if k % 1000 == 0:
+            _say(f"  step {k}")
+    r.close()
+
+
+def test_brh_batched_bench_configuration():
+    """The batched BR-H side workload of bench.py at full size (1024 clusters), every instance."""
+    cfg = wl.config("c3", n_inst=1024, gate_pfin=0.0, token_watermark=0, token_cap=0, init_active_per_worker=76,
+                    init_kv_lo=256, init_kv_hi=8192, init_rem_lo=1, init_rem_hi=1024, init_waiting=256)
+    _say("brh batched full size")
+    init, arr = wl.initial_state(cfg), wl.initial_waiting(cfg)
+    oc, r = br_oracle.OracleCluster(cfg, init), binding.Router(cfg, init)
+    ref = oc.route_step(arr, want_prep=True)
+    out = r.route_step(arr, matrix=False)
+    from tests.parity import compare_prep
+    compare_prep(ref, r.state(), "brh batch")
+    compare_outputs(ref, out, cfg, "brh batch")
+    assert (ref["stats"][:, br_oracle.ST["admitted"]] > 0).all()
+    oc.advance(1)
+    r.advance(1)
+    compare_state(oc, r.state(), cfg, "brh batch")
+    r.close()
+
+
 def test_determinism():
     cfg, init, arr = wl.random_case(31, N=16, G=16, B=24, max_wait=256, H=4, gate_pfin=0.0, tie_heavy=True)
     outs = []
