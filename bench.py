@@ -145,6 +145,38 @@ def brh_run(device, steps=6, warmup=2):
     return res
 
 
+def bypass_run(device, cfg, init, arr, steps=6, warmup=2):
+    """Pool-bypass dispatch (BR-0) of the same batch: 256 arrivals per cluster placed one by one."""
+    import torch
+    from paper_2605_06113_amd import binding
+    routers = [binding.Router(cfg, init, device=device) for _ in range(steps + warmup)]
+    darr = binding.DeviceArrivals(arr, device, 0)
+    out = dict(assign=torch.empty((cfg.n_inst, darr.arr_cap), dtype=torch.int32, device=device),
+               stats=torch.empty((cfg.n_inst, binding.NSTATS), dtype=torch.int64, device=device))
+    for r in routers[:warmup]:
+        r.route_bypass_device(darr, out)
+    torch.cuda.synchronize()
+    for r in routers[warmup:]:
+        r.profile(True)
+    t0 = time.perf_counter()
+    for r in routers[warmup:]:
+        r.route_bypass_device(darr, out)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    st = out["stats"].cpu().numpy()
+    placed = int(st[:, binding.ST["admitted"]].sum())
+    ms = cnt = 0
+    for r in routers[warmup:]:
+        m, c = r.profile_read()["bypass"]
+        ms += m
+        cnt += c
+    for r in routers:
+        r.close()
+    return dict(workload="c4 state, 256 arrivals per cluster dispatched one at a time (argmax_g over 16 workers each)",
+                ms_per_call=elapsed / steps * 1e3, kernel_avg_ms=ms / max(cnt, 1), decisions_per_s=placed * steps / elapsed,
+                pairs_per_s=int(st[:, binding.ST["qlen"]].sum()) * cfg.G * steps / elapsed)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -267,6 +299,7 @@ def main():
                roofline=roofline, kernels=per_kernel)
     if not args.no_brh:
         res["brh_batched"] = brh_run(device)
+        res["bypass"] = bypass_run(device, cfg, init, arr)
     if args.latency_steps > 0:
         res["latency"] = latency_run(args.latency_steps, device)
     if not args.no_cpu_baseline:

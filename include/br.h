@@ -39,7 +39,7 @@ extern "C" {
 #define BR_MAX_RMAX 8
 #define BR_MAX_S 32768
 #define BR_NSTATS 16
-#define BR_NKERNELS 5
+#define BR_NKERNELS 6
 
 enum {
   BR_OK = 0,
@@ -70,7 +70,8 @@ enum {
   BR_K_SCORE = 1,   /* F-score matrix + stage-one reductions */
   BR_K_ASSIGN = 2,  /* sequential two-stage assignment */
   BR_K_ADVANCE = 3, /* decode step */
-  BR_K_INIT = 4
+  BR_K_INIT = 4,
+  BR_K_BYPASS = 5   /* pool-bypass dispatch */
 };
 
 typedef struct br_ctx br_ctx; /* opaque; host object owned by the library */
@@ -190,6 +191,21 @@ int32_t br_route_step(br_ctx *ctx, const br_arrivals *in, const br_step_out *out
  * slot.  n_steps >= 0.
  */
 int32_t br_advance_decode(br_ctx *ctx, int32_t n_steps);
+
+/*
+ * Pool-bypass dispatch for BR-0 (Appendix "Pool-bypass deployment path for BR-0"): instead of
+ * waiting in the pool for a scheduling round, each arrival is placed at once, in order, on
+ * argmax_g F_g(s) with F_g(s) = s - G (s - m_g)_+ (eq. (br0-Fscore)) over the workers that have a
+ * free slot (and pass the token watermark), against the virtual load: everything already
+ * dispatched to a worker counts.  The per-worker inflight cap is the slot limit B.  Equal scores
+ * go to the lowest worker index.  An arrival no worker can take joins the waiting queue (a later
+ * br_route_step serves it); if that is full it is dropped and counted.
+ * Requires H == 0 and in->arr_cap <= BR_MAX_WAIT (else BR_EINVAL).
+ * out->assign is [n_inst][in->arr_cap], per ARRIVAL: worker, -1 = queued, -2 = dropped; entries
+ * at or beyond count[i] are left untouched.  out->stats as in br_route_step (BR_ST_QLEN = arrivals
+ * considered; stage counters zero).  Other outputs are ignored.
+ */
+int32_t br_route_bypass(br_ctx *ctx, const br_arrivals *in, const br_step_out *out);
 
 /* Destroy the context (host memory only; the workspace stays the caller's). NULL is allowed. */
 void br_free(br_ctx *ctx);

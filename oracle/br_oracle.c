@@ -586,3 +586,74 @@ int32_t orc_advance(const orc_params *P, orc_io *io, int32_t n_steps) {
   }
   return 0;
 }
+
+/* ------------------------------------------------------------- pool bypass */
+
+/* Appendix "Pool-bypass deployment path for BR-0": every request that finishes prefill is scored
+ * at once with the single-step score F_g(s) = s - G (s - m_g)_+ over all decode workers, against
+ * the virtual load (everything already dispatched to the worker counts), and forwarded to the best
+ * worker; the per-worker inflight cap is the slot limit B.  BR-0 only.  Equal scores resolve to the
+ * lowest worker index (the paper is silent).  A request no worker can take joins the waiting queue. */
+int32_t orc_route_bypass(const orc_params *P, orc_io *io) {
+  int G = P->G, a, g;
+  int64_t st[ORC_NSTATS];
+  int32_t qlen = *io->qlen;
+  int32_t pw = pred_width(P);
+  int64_t L0[ORC_MAX_G];
+  if (G < 1 || G > ORC_MAX_G || P->H != 0 || pw != 0) return -1;
+  memset(st, 0, sizeof st);
+  for (g = 0; g < G; ++g) L0[g] = io->L[g];
+  st[ORC_ST_I_BEFORE] = imbalance(L0, G);
+  st[ORC_ST_QLEN] = io->a_count;
+  for (a = 0; a < io->a_count; ++a) {
+    int64_t s = clamp_s(io->a_s[a]);
+    int64_t M = io->L[0];
+    int best = -1;
+    int64_t bf = 0;
+    for (g = 1; g < G; ++g)
+      if (io->L[g] > M) M = io->L[g];
+    for (g = 0; g < G; ++g) {
+      int64_t f;
+      if (io->n[g] >= P->B) continue;
+      if (P->token_watermark > 0 && io->L[g] + s > P->token_watermark) continue;
+      f = orc_score_br0(G, M - io->L[g], s);
+      if (best < 0 || f > bf) {
+        best = g;
+        bf = f;
+      }
+    }
+    if (best >= 0) {
+      int64_t slot = (int64_t)best * P->B + io->n[best];
+      io->kv[slot] = (int32_t)s;
+      io->rem[slot] = io->a_o[a] < 1 ? 1 : io->a_o[a];
+      io->n[best] += 1;
+      io->L[best] += s;
+      st[ORC_ST_ADMITTED] += 1;
+      if (io->assign) io->assign[a] = best;
+    } else if (qlen < P->max_wait) {
+      io->qs[qlen] = (int32_t)s;
+      io->qo[qlen] = io->a_o[a] < 1 ? 1 : io->a_o[a];
+      io->qid[qlen] = io->a_id ? io->a_id[a] : a;
+      ++qlen;
+      if (io->assign) io->assign[a] = -1;
+    } else {
+      st[ORC_ST_DROPPED] += 1;
+      if (io->assign) io->assign[a] = -2;
+    }
+  }
+  *io->qlen = qlen;
+  st[ORC_ST_DEFERRED] = qlen;
+  for (g = 0; g < G; ++g) L0[g] = io->L[g];
+  st[ORC_ST_I_AFTER] = imbalance(L0, G);
+  {
+    int64_t mx = L0[0], mn = L0[0];
+    for (g = 0; g < G; ++g) {
+      if (L0[g] > mx) mx = L0[g];
+      if (L0[g] < mn) mn = L0[g];
+      if (P->token_cap > 0 && L0[g] > P->token_cap) st[ORC_ST_OVERCAP] += 1;
+    }
+    st[ORC_ST_SPREAD] = mx - mn;
+  }
+  if (io->stats) memcpy(io->stats, st, sizeof st);
+  return 0;
+}

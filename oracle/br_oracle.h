@@ -17,6 +17,7 @@
  *     interface", eqs. (two-stage), (composite), (wprofile-new); gate and floor from
  *     Appendix "Refresh logic"
  *   - exhaustive subset search of Stage 2:     Appendix "Bit-set subset selection"
+ *   - pool-bypass dispatch:                    Appendix "Pool-bypass deployment path for BR-0"
  *
  * BR-0/BR-H are heuristics without an exactness claim, so the oracle is the
  * algorithm itself, step by step.  Integer quantities are int64; BR-H scores are
@@ -129,6 +130,10 @@ int32_t orc_best_subset(const orc_params *P, const int64_t *m_g, int64_t L_g, in
 int32_t orc_project(const orc_params *P, orc_io *io);
 int32_t orc_route_step(const orc_params *P, orc_io *io);
 int32_t orc_advance(const orc_params *P, orc_io *io, int32_t n_steps);
+/* Pool-bypass dispatch (Appendix "Pool-bypass deployment path for BR-0"): arrivals are placed one
+ * at a time, in order, on argmax_g F_g(s) over the workers with a free slot; io->assign[a] gets the
+ * worker of arrival a, -1 if it had to join the waiting queue, -2 if that was full too. */
+int32_t orc_route_bypass(const orc_params *P, orc_io *io);
 
 #ifdef __cplusplus
 }

@@ -76,7 +76,7 @@ def lib():
         _lib.orc_best_subset.restype = C.c_int32
         _lib.orc_best_subset.argtypes = [C.POINTER(Params), _P, C.c_int64, C.c_int32, _P, C.c_int32,
                                          C.POINTER(C.c_double)]
-        for f in (_lib.orc_project, _lib.orc_route_step):
+        for f in (_lib.orc_project, _lib.orc_route_step, _lib.orc_route_bypass):
             f.restype = C.c_int32
             f.argtypes = [C.POINTER(Params), C.POINTER(IO)]
         _lib.orc_advance.restype = C.c_int32
@@ -219,6 +219,23 @@ class OracleCluster:
             if want_events:
                 io.events, io.n_events = _ptr(out["events"][i]), _ptr(out["n_events"][i:i + 1])
             rc = lib().orc_route_step(C.byref(self.params), C.byref(io))
+            assert rc == 0, rc
+        return out
+
+    def route_bypass(self, arr):
+        """Pool-bypass dispatch of one batch of arrivals (BR-0 only); assign is per arrival."""
+        N = self.N
+        cap = int(arr.s.shape[-1])
+        out = dict(assign=np.full((N, cap), -3, np.int32), stats=np.zeros((N, NSTATS), np.int64))
+        a_s = np.ascontiguousarray(arr.s, np.int32)
+        a_o = np.ascontiguousarray(arr.o, np.int32)
+        a_id = np.ascontiguousarray(arr.id, np.int32)
+        for i in range(N):
+            io = self._io(i)
+            io.a_count = int(min(max(arr.count[i], 0), cap))
+            io.a_s, io.a_o, io.a_id = _ptr(a_s[i]), _ptr(a_o[i]), _ptr(a_id[i])
+            io.assign, io.stats = _ptr(out["assign"][i]), _ptr(out["stats"][i])
+            rc = lib().orc_route_bypass(C.byref(self.params), C.byref(io))
             assert rc == 0, rc
         return out
 

@@ -17,13 +17,13 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libbr_hip.so")
 
 NSTATS = 16
-NKERNELS = 5
-KERNEL_NAMES = ("project", "score", "assign", "advance", "init")
+NKERNELS = 6
+KERNEL_NAMES = ("project", "score", "assign", "advance", "init", "bypass")
 ST = dict(admitted=0, deferred=1, dropped=2, stage1=3, stage2_pops=4, guard=5, overcap=6,
           I_before=7, I_after=8, spread=9, qlen=10, workers_dropped=11)
 BR_OK, BR_EINVAL, BR_ENOMEM, BR_EHIP = 0, -1, -2, -3
 
-EXPORTS = ("br_workspace_bytes", "br_init", "br_route_step", "br_advance_decode", "br_free",
+EXPORTS = ("br_workspace_bytes", "br_init", "br_route_step", "br_route_bypass", "br_advance_decode", "br_free",
            "br_last_hip_error", "br_get_layout", "br_profile_enable", "br_profile_read")
 
 _P = C.c_void_p
@@ -75,6 +75,8 @@ def load():
     lib.br_init.argtypes = [C.POINTER(Config), C.POINTER(InitState), C.POINTER(_P)]
     lib.br_route_step.restype = C.c_int32
     lib.br_route_step.argtypes = [_P, C.POINTER(Arrivals), C.POINTER(StepOut)]
+    lib.br_route_bypass.restype = C.c_int32
+    lib.br_route_bypass.argtypes = [_P, C.POINTER(Arrivals), C.POINTER(StepOut)]
     lib.br_advance_decode.restype = C.c_int32
     lib.br_advance_decode.argtypes = [_P, C.c_int32]
     lib.br_free.restype = None
@@ -204,6 +206,22 @@ class Router:
         darr = DeviceArrivals(arr, self.device, self.P) if arr is not None else None
         out = self.alloc_outputs(scores, matrix)
         self.route_step_device(darr, out)
+        self.stream.synchronize()
+        return {k: v.cpu().numpy() for k, v in out.items()}
+
+    def route_bypass_device(self, darr: DeviceArrivals, out) -> None:
+        """Enqueue the pool-bypass dispatch of one batch of arrivals (BR-0); no synchronisation."""
+        a = darr.struct()
+        o = self.out_struct(out)
+        _check(self.lib.br_route_bypass(self.ctx, C.byref(a), C.byref(o)), "br_route_bypass", self.ctx)
+
+    def route_bypass(self, arr):
+        """Convenience for tests: host arrays in, numpy out (synchronises)."""
+        torch = self.torch
+        darr = DeviceArrivals(arr, self.device, 0)
+        out = dict(assign=torch.full((self.N, darr.arr_cap), -3, dtype=torch.int32, device=self.device),
+                   stats=torch.zeros((self.N, NSTATS), dtype=torch.int64, device=self.device))
+        self.route_bypass_device(darr, out)
         self.stream.synchronize()
         return {k: v.cpu().numpy() for k, v in out.items()}
 

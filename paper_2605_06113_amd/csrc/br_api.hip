@@ -228,6 +228,25 @@ int32_t br_route_step(br_ctx *ctx, const br_arrivals *in, const br_step_out *out
   return rc;
 }
 
+int32_t br_route_bypass(br_ctx *ctx, const br_arrivals *in, const br_step_out *out) {
+  if (!ctx || ctx->p.H != 0) return BR_EINVAL;
+  if (!in || !in->count || in->arr_cap <= 0) return BR_OK;  // nothing to place
+  if (in->arr_cap > BR_MAX_WAIT || !in->s || !in->o) return BR_EINVAL;
+  BrArr a{};
+  a.count = in->count;
+  a.s = in->s;
+  a.o = in->o;
+  a.id = in->id;
+  a.pred = nullptr;
+  a.arr_cap = in->arr_cap;
+  BrOut o{};
+  if (out) {
+    o.assign = out->assign;
+    o.stats = (long long *)out->stats;
+  }
+  return enqueue(ctx, BR_K_BYPASS, [&] { br_launch_bypass(ctx->p, a, o, ctx->st); });
+}
+
 int32_t br_advance_decode(br_ctx *ctx, int32_t n_steps) {
   if (!ctx || n_steps < 0) return BR_EINVAL;
   if (n_steps == 0) return BR_OK;

@@ -206,6 +206,31 @@ def test_brh_batched_bench_configuration():
     r.close()
 
 
+def test_pool_bypass():
+    """br_route_bypass against the oracle: placements, loads, slot tables, queue fallback, drops."""
+    for seed, (G, B, Q, cap, fill, wm) in enumerate([(4, 8, 16, 40, 0.5, 0), (16, 144, 256, 256, 0.85, 0),
+                                                      (64, 12, 64, 900, 0.3, 0), (1, 5, 8, 20, 0.2, 0),
+                                                      (16, 20, 32, 128, 0.6, 30000), (7, 9, 300, 2048, 0.1, 0)]):
+        _say(f"bypass G={G} B={B} Q={Q} arrivals<={cap}")
+        cfg, init, _ = wl.random_case(100 + seed, N=5, G=G, B=B, max_wait=Q, H=0, fill=fill, token_watermark=wm)
+        _, _, arr = wl.random_case(200 + seed, N=5, G=G, B=B, max_wait=cap, H=0, s_hi=[4096, 16384, 32768][seed % 3])
+        oc, r = br_oracle.OracleCluster(cfg, init), binding.Router(cfg, init)
+        for rnd in range(2):
+            ref, out = oc.route_bypass(arr), r.route_bypass(arr)
+            for i in range(cfg.n_inst):
+                c = int(arr.count[i])
+                assert np.array_equal(out["assign"][i, :c], ref["assign"][i, :c]), (seed, rnd, i)
+            assert np.array_equal(out["stats"], ref["stats"]), (seed, rnd, out["stats"][:2], ref["stats"][:2])
+            compare_state(oc, r.state(), cfg, f"bypass {seed}/{rnd}")
+            oc.advance(3)
+            r.advance(3)
+        # what was queued is served by an ordinary round afterwards
+        ref, out = oc.route_step(None), r.route_step(None)
+        compare_outputs(ref, out, cfg, f"bypass {seed} then round")
+        compare_state(oc, r.state(), cfg, f"bypass {seed} then round")
+        r.close()
+
+
 def test_determinism():
     cfg, init, arr = wl.random_case(31, N=16, G=16, B=24, max_wait=256, H=4, gate_pfin=0.0, tie_heavy=True)
     outs = []
