@@ -24,6 +24,8 @@
 // resolve to the lowest sorted position; equal subset scores to the lowest mask.
 #include "br_device.h"
 #include "br_launch.h"
+#include <type_traits>
+
 #include "br_sort.h"
 #include "br_assign_common.h"
 
@@ -134,20 +136,38 @@ __global__ __launch_bounds__(256) void br_k_assign(BrParams p, BrArr a, BrOut o)
   auto pick_single = [&](const int(&mg)[BR_HP + 1], int room, int &pos, int &swin) -> bool {
     if constexpr (PACK1) {
       unsigned bk = 0;
+      const int negG = -(G & 0x7f);
+      auto scan = [&](auto wm) {
 #pragma unroll
-      for (int j = 0; j < E; ++j) {
-        if (E <= 8 || (j >= jhead && j * BR_WAVE < qn)) {  // few registers: cheaper to score all than to branch
-          const int s = sv[j];
-          const int F = s - (int)((unsigned)(max(s - mg[0], 0) & 0xffff) * (unsigned)(G & 0x7f));
-          const unsigned key = ((unsigned)F << PB) + ckey[j];
-          bool ok = (alive >> j) & 1u;
-          if (p.W > 0) ok = ok && s <= room;
-          bk = max(bk, ok ? key : 0u);
+        for (int j = 0; j < E; ++j) {
+          if (E <= 8 || (j >= jhead && j * BR_WAVE < qn)) {  // few registers: cheaper to score all than to branch
+            const int s = sv[j];
+            const int F = s + (max(s - mg[0], 0) & 0xffff) * negG;       // one 24-bit multiply-add
+            unsigned key = ((unsigned)F << PB) + ckey[j];
+            key &= (unsigned)(((int)(alive << (31 - j))) >> 31);         // all ones if still waiting
+            if constexpr (decltype(wm)::value) key = s <= room ? key : 0u;
+            bk = max(bk, key);
+          }
         }
-      }
+      };
+      if (p.W > 0)
+        scan(std::true_type{});
+      else
+        scan(std::false_type{});
       const unsigned km = br_wave_umax(bk);
       if (km == 0u) return false;
       pos = NP - 1 - (int)(km & (unsigned)(NP - 1));
+      if constexpr (E <= 8) {  // the winner's length straight from its register, no LDS round trip
+        const int lw = pos & 63, jw = pos >> 6;
+        int sw = __builtin_amdgcn_readlane(sv[0], lw);
+#pragma unroll
+        for (int j = 1; j < E; ++j) {
+          const int sj = __builtin_amdgcn_readlane(sv[j], lw);
+          sw = jw == j ? sj : sw;
+        }
+        swin = sw;
+        return true;
+      }
     } else {
       int bk = BR_KEY_NONE, bp = INT32_MAX;
 #pragma unroll
@@ -196,7 +216,7 @@ __global__ __launch_bounds__(256) void br_k_assign(BrParams p, BrArr a, BrOut o)
 
   // sticky binding of the request at sorted position pos to worker g
   auto bind = [&](int pos, int g, int slot) {
-    if (lane == 0) adm[pos] = (g << 16) | slot;
+    adm[pos] = (g << 16) | slot;  // every lane stores the same word: no lane masking needed
     const int jw = pos >> 6, lw = pos & 63;
     alive = (lane == lw) ? (alive & ~(1u << jw)) : alive;
   };
