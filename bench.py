@@ -102,7 +102,7 @@ def brh_run(device, steps=6, warmup=2):
                     init_rem_lo=1, init_rem_hi=1024, init_waiting=256)
     init, arr = wl.initial_state(cfg), wl.initial_waiting(cfg)
     routers = [binding.Router(cfg, init, device=device) for _ in range(steps + warmup)]
-    darr = binding.DeviceArrivals(arr, device, routers[0].P)
+    darr = binding.DeviceArrivals(arr, device, routers[0].Pq)
     out = routers[0].alloc_outputs(scores=True, matrix=False)
     torch.cuda.synchronize()
     for r in routers[:warmup]:

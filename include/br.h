@@ -90,19 +90,30 @@ typedef struct {
   int32_t token_watermark; /* 0 = off; else a request is admissible on g only if L_g + s <= watermark */
   int32_t token_cap;       /* 0 = off; reporting only (BR_ST_OVERCAP) */
   int32_t pred_mode;       /* H > 0: 0 = per-step termination hazards p[1..H] per request,
-                              1 = one float per request holding c_hat directly */
+                              1 = one float per request holding c_hat directly,
+                              2 = c_hat maintained by the library with the empirical-survival
+                                  estimator and the refresh rules of Appendix "Refresh logic"
+                                  (arrivals carry no prediction inputs; needs hist below) */
   float alpha, beta, gamma; /* horizon score parameters, eq. (brh-Fscore); ignored when H == 0
                                (BR-0 is (1, G)); alpha > 0, beta >= 0, 0 < gamma <= 1 */
   float gate_pfin;          /* confidence gate on p_fin (Appendix "Refresh logic"); <= 0 disables */
   void *stream;             /* hipStream_t, borrowed for the life of the context (NULL = default) */
   void *workspace;          /* device memory, >= br_workspace_bytes() bytes, 256-byte aligned, borrowed */
   uint64_t workspace_bytes;
+  /* pred_mode 2 only (Appendix "Estimator realizations", empirical-survival): the output lengths of
+   * a training corpus, sorted ascending, and their prefix sums (hist_sum[k] = sum of the first k
+   * lengths, hist_n + 1 entries); device memory, borrowed until br_free.  hist_n in [1, 2^20]. */
+  const int32_t *hist;
+  const int64_t *hist_sum;
+  int32_t hist_n;
+  int32_t refresh_period;   /* Delta T: generated tokens between two queries of the estimator, >= 1 */
 } br_config;
 
 /*
  * Optional active sets at step 0.  Dense lists: slots [0, n[i][g]) of worker g are used.
- * n [n_inst][G]; kv, rem [n_inst][G][B]; pred [n_inst][G][B][P] with P = H (pred_mode 0)
- * or 1 (pred_mode 1), NULL when H == 0.  kv = current KV length (s_i + a_i), rem = decode
+ * n [n_inst][G]; kv, rem [n_inst][G][B]; pred [n_inst][G][B][P] with P = H (pred_mode 0),
+ * 1 (pred_mode 1) or 3 (pred_mode 2: c_hat, tokens generated so far, tokens since the last
+ * estimator query), NULL when H == 0.  kv = current KV length (s_i + a_i), rem = decode
  * steps still to run (>= 1).  Copied into the workspace by br_init.
  */
 typedef struct {
@@ -114,7 +125,8 @@ typedef struct {
 
 /*
  * Requests that finished prefill since the previous round (they join R_wait in this order).
- * count [n_inst]; s, o, id [n_inst][arr_cap]; pred [n_inst][arr_cap][P].
+ * count [n_inst]; s, o, id [n_inst][arr_cap]; pred [n_inst][arr_cap][Pq] with Pq = H (pred_mode 0),
+ * 1 (pred_mode 1) or 0 (pred_mode 2 and BR-0: pred is ignored).
  * s = prefill length s_i; o = output length o_i (never read by the routing decision, only
  * stored for br_advance_decode; values < 1 count as 1); id = caller's request handle
  * (NULL: the position within this batch is used).
@@ -156,13 +168,13 @@ typedef struct {
  * Where the state lives inside the workspace (byte offsets), for inspection by tests and
  * tools.  All arrays are int32 except pred/qpred (float).
  *  L, n [n_inst][G];  kv, rem [n_inst][G][B_stride];  pred [n_inst][G][B_stride][P]
- *  qlen [n_inst];  qs, qo, qid [n_inst][max_wait];  qpred [n_inst][max_wait][P]
+ *  qlen [n_inst];  qs, qo, qid [n_inst][max_wait];  qpred [n_inst][max_wait][Pq]
  *  Lh, mh [n_inst][G][H+1];  Mh [n_inst][H+1];  minm [n_inst][G]   (written when H > 0)
  */
 typedef struct {
   uint64_t L, n, kv, rem, pred, qlen, qs, qo, qid, qpred, Lh, Mh, mh, minm;
   uint64_t total_bytes;
-  int32_t B_stride, P;
+  int32_t B_stride, P, Pq, pad;
 } br_layout;
 
 /* Bytes of workspace a configuration needs (0 if the configuration is invalid). Host only. */

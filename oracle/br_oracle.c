@@ -82,7 +82,7 @@ float orc_chat(int32_t H, int32_t pred_mode, float gate_pfin, const float *p) {
   float c;
   float Hf = (float)H;
   if (H == 0) return 0.0f;
-  if (pred_mode == 1) {
+  if (pred_mode >= 1) {
     c = p[0];
   } else {
     float S = 1.0f, pfin;
@@ -100,9 +100,45 @@ float orc_chat(int32_t H, int32_t pred_mode, float gate_pfin, const float *p) {
   return c;
 }
 
+/* floats kept per active request / per waiting request */
 static int32_t pred_width(const orc_params *P) {
   if (P->H == 0) return 0;
-  return P->pred_mode == 1 ? 1 : P->H;
+  return P->pred_mode == 2 ? 3 : (P->pred_mode == 1 ? 1 : P->H);
+}
+
+static int32_t queue_pred_width(const orc_params *P) { return P->pred_mode == 2 ? 0 : pred_width(P); }
+
+/* number of history entries <= x */
+static int64_t hist_rank(const orc_params *P, int64_t x) {
+  int64_t lo = 0, hi = P->hist_n;
+  while (lo < hi) {
+    int64_t mid = (lo + hi) / 2;
+    if (P->hist[mid] <= x)
+      lo = mid + 1;
+    else
+      hi = mid;
+  }
+  return lo;
+}
+
+/* Appendix "Estimator realizations", empirical-survival: with F the empirical CDF of the output-length
+ * history, p_fin = (F(a+H) - F(a)) / (1 - F(a)) and mu_rem = mean of (o_j - a) over a < o_j <= a+H;
+ * composite, gate, floor and clip as in eq. (composite) and "Refresh logic".  A request that has
+ * outlived the whole history, or with nothing in the window, gets the conservative anchor H. */
+float orc_survival(const orc_params *P, int64_t age) {
+  float Hf = (float)P->H, p = 0.0f, mu = 0.0f, c;
+  int64_t lo = hist_rank(P, age), hi = hist_rank(P, age + P->H);
+  int64_t surv = P->hist_n - lo, cnt = hi - lo;
+  if (surv > 0 && cnt > 0) {
+    int64_t rem_sum = (P->hist_sum[hi] - P->hist_sum[lo]) - cnt * age;
+    p = (float)cnt / (float)surv;
+    mu = (float)rem_sum / (float)cnt;
+  }
+  c = (1.0f - p) * Hf + p * mu;
+  if (P->gate_pfin > 0.0f && p < P->gate_pfin) c = Hf;
+  if (c < 1.0f) c = 1.0f;
+  if (c > Hf) c = Hf;
+  return c;
 }
 
 /* ------------------------------------------------------------ route state */
@@ -260,12 +296,17 @@ typedef struct {
 static void bind(round_t *T, int pos, int g) {
   const orc_params *P = T->R->P;
   orc_io *io = T->io;
-  int32_t pw = pred_width(P);
+  int32_t pw = queue_pred_width(P);
   int32_t idx = T->ord[pos].idx;
   int64_t slot = (int64_t)g * P->B + io->n[g];
   io->kv[slot] = T->ord[pos].s;
   io->rem[slot] = io->qo[idx];
   if (pw) memcpy(io->pred + slot * pw, io->qpred + (int64_t)idx * pw, sizeof(float) * (size_t)pw);
+  if (P->H > 0 && P->pred_mode == 2) { /* first query of the estimator, at age 0 */
+    io->pred[slot * 3 + 0] = orc_survival(P, 0);
+    io->pred[slot * 3 + 1] = 0.0f;
+    io->pred[slot * 3 + 2] = 0.0f;
+  }
   io->n[g] += 1;
   T->R->cap[g] -= 1;
   T->S_tot -= 1;
@@ -341,7 +382,7 @@ static int64_t imbalance(const int64_t *L, int G) {
 int32_t orc_route_step(const orc_params *P, orc_io *io) {
   rstate R;
   round_t T;
-  int32_t pw = pred_width(P);
+  int32_t pw = queue_pred_width(P);
   int g, i, pos, G = P->G;
   int32_t qlen, space, acc;
   int64_t st[ORC_NSTATS];
@@ -579,6 +620,25 @@ int32_t orc_advance(const orc_params *P, orc_io *io, int32_t n_steps) {
         io->L[g] += 1;
         if (pw && k != j)
           memmove(io->pred + (base + k) * pw, io->pred + (base + j) * pw, sizeof(float) * (size_t)pw);
+        if (P->H > 0 && P->pred_mode == 2) {
+          /* Appendix "Refresh logic": one more token generated; re-query every `refresh` tokens, in
+           * between one step less of in-window contribution; falling below the floor re-queries at once */
+          float *q = io->pred + (base + k) * 3;
+          float age = q[1] + 1.0f, since = q[2] + 1.0f, c = q[0];
+          if ((int64_t)since >= P->refresh) {
+            c = orc_survival(P, (int64_t)age);
+            since = 0.0f;
+          } else {
+            c = c - 1.0f;
+            if (c < 1.0f) {
+              c = orc_survival(P, (int64_t)age);
+              since = 0.0f;
+            }
+          }
+          q[0] = c;
+          q[1] = age;
+          q[2] = since;
+        }
         ++k;
       }
       io->n[g] = k;

@@ -18,6 +18,7 @@
  *     Appendix "Refresh logic"
  *   - exhaustive subset search of Stage 2:     Appendix "Bit-set subset selection"
  *   - pool-bypass dispatch:                    Appendix "Pool-bypass deployment path for BR-0"
+ *   - empirical-survival estimator, refresh:   Appendix "Estimator realizations", "Refresh logic"
  *
  * BR-0/BR-H are heuristics without an exactness claim, so the oracle is the
  * algorithm itself, step by step.  Integer quantities are int64; BR-H scores are
@@ -69,9 +70,16 @@ typedef struct {
   int32_t G, B, max_wait, H;
   int32_t R_max, S_greedy;
   int32_t token_watermark, token_cap;
-  int32_t pred_mode; /* 0: per-step hazards p[1..H]; 1: direct c_hat (one float) */
+  int32_t pred_mode; /* 0: per-step hazards p[1..H]; 1: direct c_hat (one float);
+                        2: empirical-survival estimator maintained per request (c_hat, age, since-refresh) */
   int32_t force_float; /* evaluate the horizon score in fp32 even when H == 0 (reduction check) */
   float alpha, beta, gamma, gate_pfin;
+  /* pred_mode 2: sorted history of output lengths, its prefix sums (hist_sum[k] = sum of the first k),
+   * and the refresh period Delta T in generated tokens */
+  const int32_t *hist;
+  const int64_t *hist_sum;
+  int32_t hist_n;
+  int32_t refresh;
 } orc_params;
 
 /* One admission event (a single request in Stage 1, a subset in Stage 2). */
@@ -123,6 +131,8 @@ int64_t orc_score_br0(int64_t G, int64_t m, int64_t delta);
 float orc_score_brh(int32_t H, float alpha, float beta, float gamma, const int64_t *m, int64_t delta);
 /* in-window contribution from the prediction inputs of one request */
 float orc_chat(int32_t H, int32_t pred_mode, float gate_pfin, const float *p);
+/* empirical-survival estimate of the in-window contribution at age a (pred_mode 2) */
+float orc_survival(const orc_params *P, int64_t age);
 /* Stage-2 subset search on an explicit window; returns the chosen mask (0 = none feasible) */
 int32_t orc_best_subset(const orc_params *P, const int64_t *m_g, int64_t L_g, int32_t cap_g,
                         const int32_t *win_s, int32_t w, double *best_score);

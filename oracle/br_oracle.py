@@ -39,7 +39,8 @@ class Params(C.Structure):
                 ("token_watermark", C.c_int32), ("token_cap", C.c_int32),
                 ("pred_mode", C.c_int32), ("force_float", C.c_int32),
                 ("alpha", C.c_float), ("beta", C.c_float), ("gamma", C.c_float),
-                ("gate_pfin", C.c_float)]
+                ("gate_pfin", C.c_float),
+                ("hist", C.c_void_p), ("hist_sum", C.c_void_p), ("hist_n", C.c_int32), ("refresh", C.c_int32)]
 
 
 class Event(C.Structure):
@@ -103,12 +104,27 @@ def chat(H: int, pred_mode: int, gate_pfin: float, p) -> float:
     return float(lib().orc_chat(H, pred_mode, gate_pfin, _ptr(pp)))
 
 
-def params_from(cfg, force_float: bool = False) -> Params:
-    """cfg: any object with the RouteConfig fields."""
-    return Params(G=cfg.G, B=cfg.B, max_wait=cfg.max_wait, H=cfg.H, R_max=cfg.R_max,
-                  S_greedy=cfg.s_greedy, token_watermark=cfg.token_watermark,
-                  token_cap=cfg.token_cap, pred_mode=cfg.pred_mode, force_float=int(force_float),
-                  alpha=cfg.alpha, beta=cfg.beta_eff, gamma=cfg.gamma, gate_pfin=cfg.gate_pfin)
+def params_from(cfg, force_float: bool = False, hist=None) -> Params:
+    """cfg: any object with the RouteConfig fields; hist: sorted output-length history (pred_mode 2).
+    The returned struct keeps the history arrays alive in `_keep`."""
+    P = Params(G=cfg.G, B=cfg.B, max_wait=cfg.max_wait, H=cfg.H, R_max=cfg.R_max,
+               S_greedy=cfg.s_greedy, token_watermark=cfg.token_watermark,
+               token_cap=cfg.token_cap, pred_mode=cfg.pred_mode, force_float=int(force_float),
+               alpha=cfg.alpha, beta=cfg.beta_eff, gamma=cfg.gamma, gate_pfin=cfg.gate_pfin,
+               hist=None, hist_sum=None, hist_n=0, refresh=int(getattr(cfg, "refresh_eff", 1)))
+    if hist is not None:
+        h = np.ascontiguousarray(hist, np.int32)
+        assert (np.diff(h) >= 0).all(), "history must be sorted"
+        hs = np.concatenate([[0], np.cumsum(h, dtype=np.int64)]).astype(np.int64)
+        P._keep = (h, hs)
+        P.hist, P.hist_sum, P.hist_n = h.ctypes.data, hs.ctypes.data, len(h)
+    return P
+
+
+def survival(params: Params, age: int) -> float:
+    lib().orc_survival.restype = C.c_float
+    lib().orc_survival.argtypes = [C.POINTER(Params), C.c_int64]
+    return float(lib().orc_survival(C.byref(params), int(age)))
 
 
 def best_subset(params: Params, m_g, L_g: int, cap_g: int, win_s):
@@ -123,12 +139,13 @@ def best_subset(params: Params, m_g, L_g: int, cap_g: int, win_s):
 class OracleCluster:
     """N independent instances held as numpy arrays; every call loops over them in C."""
 
-    def __init__(self, cfg, init=None, force_float: bool = False):
+    def __init__(self, cfg, init=None, force_float: bool = False, hist=None):
         self.cfg = cfg
-        self.params = params_from(cfg, force_float)
+        self.params = params_from(cfg, force_float, hist)
         N, G, B, Q, H = cfg.n_inst, cfg.G, cfg.B, cfg.max_wait, cfg.H
         self.N, self.G, self.B, self.Q, self.H = N, G, B, Q, H
-        self.P = 0 if H == 0 else (1 if cfg.pred_mode == 1 else H)
+        self.P = 0 if H == 0 else (3 if cfg.pred_mode == 2 else (1 if cfg.pred_mode == 1 else H))
+        self.Pq = 0 if cfg.pred_mode == 2 else self.P
         self.use_float = H > 0 or force_float
         self.L = np.zeros((N, G), np.int64)
         self.n = np.zeros((N, G), np.int32)
@@ -139,7 +156,7 @@ class OracleCluster:
         self.qs = np.zeros((N, Q), np.int32)
         self.qo = np.zeros((N, Q), np.int32)
         self.qid = np.zeros((N, Q), np.int32)
-        self.qpred = np.zeros((N, Q, self.P), np.float32) if self.P else None
+        self.qpred = np.zeros((N, Q, self.Pq), np.float32) if self.Pq else None
         if init is not None:
             self.n[...] = init.n
             self.kv[...] = init.kv
@@ -158,7 +175,7 @@ class OracleCluster:
         io.pred = _ptr(self.pred[i]) if self.P else None
         io.qlen = _ptr(self.qlen[i:i + 1])
         io.qs, io.qo, io.qid = _ptr(self.qs[i]), _ptr(self.qo[i]), _ptr(self.qid[i])
-        io.qpred = _ptr(self.qpred[i]) if self.P else None
+        io.qpred = _ptr(self.qpred[i]) if self.Pq else None
         return io
 
     def project(self):
@@ -198,13 +215,13 @@ class OracleCluster:
             a_s = np.ascontiguousarray(arr.s, np.int32)
             a_o = np.ascontiguousarray(arr.o, np.int32)
             a_id = np.ascontiguousarray(arr.id, np.int32)
-            a_pred = np.ascontiguousarray(arr.pred, np.float32) if self.P else None
+            a_pred = np.ascontiguousarray(arr.pred, np.float32) if self.Pq else None
         for i in range(N):
             io = self._io(i)
             if arr is not None:
                 io.a_count = int(arr.count[i])
                 io.a_s, io.a_o, io.a_id = _ptr(a_s[i]), _ptr(a_o[i]), _ptr(a_id[i])
-                io.a_pred = _ptr(a_pred[i]) if self.P else None
+                io.a_pred = _ptr(a_pred[i]) if self.Pq else None
             io.assign, io.assign_id, io.stats = (_ptr(out["assign"][i]), _ptr(out["assign_id"][i]),
                                                  _ptr(out["stats"][i]))
             if want_scores:

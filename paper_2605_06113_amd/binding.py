@@ -34,7 +34,8 @@ class Config(C.Structure):
                 ("H", C.c_int32), ("S_greedy", C.c_int32), ("R_max", C.c_int32),
                 ("token_watermark", C.c_int32), ("token_cap", C.c_int32), ("pred_mode", C.c_int32),
                 ("alpha", C.c_float), ("beta", C.c_float), ("gamma", C.c_float), ("gate_pfin", C.c_float),
-                ("stream", _P), ("workspace", _P), ("workspace_bytes", C.c_uint64)]
+                ("stream", _P), ("workspace", _P), ("workspace_bytes", C.c_uint64),
+                ("hist", _P), ("hist_sum", _P), ("hist_n", C.c_int32), ("refresh_period", C.c_int32)]
 
 
 class InitState(C.Structure):
@@ -53,7 +54,7 @@ class StepOut(C.Structure):
 class Layout(C.Structure):
     _fields_ = [(k, C.c_uint64) for k in ("L", "n", "kv", "rem", "pred", "qlen", "qs", "qo", "qid", "qpred",
                                           "Lh", "Mh", "mh", "minm", "total_bytes")] + \
-               [("B_stride", C.c_int32), ("P", C.c_int32)]
+               [("B_stride", C.c_int32), ("P", C.c_int32), ("Pq", C.c_int32), ("pad", C.c_int32)]
 
 
 _lib = None
@@ -93,17 +94,19 @@ def load():
     return lib
 
 
-def make_config(cfg, stream=0, workspace=0, workspace_bytes=0) -> Config:
-    """cfg: any object with the workloads.RouteConfig fields."""
-    return Config(n_inst=cfg.n_inst, G=cfg.G, B=cfg.B, max_wait=cfg.max_wait, H=cfg.H,
+def make_config(cfg, stream=0, workspace=0, workspace_bytes=0, hist=0, hist_sum=0, hist_n=0) -> Config:
+    """cfg: any object with the workloads.RouteConfig fields; hist*: device pointers (pred_mode 2)."""
+    return Config(hist=hist, hist_sum=hist_sum, hist_n=hist_n, refresh_period=int(getattr(cfg, "refresh_eff", 1)),
+                  n_inst=cfg.n_inst, G=cfg.G, B=cfg.B, max_wait=cfg.max_wait, H=cfg.H,
                   S_greedy=cfg.s_greedy, R_max=cfg.R_max, token_watermark=cfg.token_watermark,
                   token_cap=cfg.token_cap, pred_mode=cfg.pred_mode, alpha=cfg.alpha, beta=cfg.beta_eff,
                   gamma=cfg.gamma, gate_pfin=cfg.gate_pfin, stream=stream, workspace=workspace,
                   workspace_bytes=workspace_bytes)
 
 
-def workspace_bytes(cfg) -> int:
-    c = make_config(cfg)
+def workspace_bytes(cfg, hist_n: int = 0) -> int:
+    # the size does not depend on the history's contents; any non-null address passes validation
+    c = make_config(cfg, hist=256 if hist_n else 0, hist_sum=256 if hist_n else 0, hist_n=hist_n)
     return int(load().br_workspace_bytes(C.byref(c)))
 
 
@@ -138,22 +141,30 @@ class DeviceArrivals:
 class Router:
     """Owns a workspace tensor and a br_ctx; all methods only marshal arguments."""
 
-    def __init__(self, cfg, init=None, device="cuda:0", stream=None):
+    def __init__(self, cfg, init=None, device="cuda:0", stream=None, hist=None):
         import torch
         self.torch = torch
         self.lib = load()
         self.cfg = cfg
         self.device = torch.device(device)
         self.N, self.G, self.B, self.Q, self.H = cfg.n_inst, cfg.G, cfg.B, cfg.max_wait, cfg.H
-        self.P = 0 if cfg.H == 0 else (1 if cfg.pred_mode == 1 else cfg.H)
-        nbytes = workspace_bytes(cfg)
+        self.P = 0 if cfg.H == 0 else (3 if cfg.pred_mode == 2 else (1 if cfg.pred_mode == 1 else cfg.H))
+        self.Pq = 0 if cfg.pred_mode == 2 else self.P
+        self._hist = None
+        hargs = {}
+        if hist is not None:   # sorted output-length history and its prefix sums, resident on the device
+            h = np.ascontiguousarray(hist, np.int32)
+            hs = np.concatenate([[0], np.cumsum(h, dtype=np.int64)]).astype(np.int64)
+            self._hist = (torch.as_tensor(h, device=self.device), torch.as_tensor(hs, device=self.device))
+            hargs = dict(hist=self._hist[0].data_ptr(), hist_sum=self._hist[1].data_ptr(), hist_n=len(h))
+        nbytes = workspace_bytes(cfg, hist_n=len(hist) if hist is not None else 0)
         if nbytes == 0:
             raise BrError("invalid configuration")
         self.ws = torch.empty(nbytes // 4 + 64, dtype=torch.int32, device=self.device)
         assert self.ws.data_ptr() % 256 == 0
         self.stream = stream if stream is not None else torch.cuda.current_stream(self.device)
         c = make_config(cfg, stream=self.stream.cuda_stream, workspace=self.ws.data_ptr(),
-                        workspace_bytes=self.ws.numel() * 4)
+                        workspace_bytes=self.ws.numel() * 4, **hargs)
         ini = None
         self._keep = []
         if init is not None:
@@ -203,7 +214,7 @@ class Router:
 
     def route_step(self, arr=None, scores: bool = True, matrix: bool = True):
         """Convenience for tests: host arrays in, numpy out (synchronises)."""
-        darr = DeviceArrivals(arr, self.device, self.P) if arr is not None else None
+        darr = DeviceArrivals(arr, self.device, self.Pq) if arr is not None else None
         out = self.alloc_outputs(scores, matrix)
         self.route_step_device(darr, out)
         self.stream.synchronize()
@@ -249,7 +260,7 @@ class Router:
     def state(self):
         """Host copies of the snapshot, in the oracle's array shapes (slots beyond n zeroed)."""
         self.stream.synchronize()
-        N, G, B, Bs, Q, P, H = self.N, self.G, self.B, self.Bs, self.Q, self.P, self.H
+        N, G, B, Bs, Q, P, Pq, H = self.N, self.G, self.B, self.Bs, self.Q, self.P, self.Pq, self.H
         lay = self.layout
         st = dict(L=self._view(lay.L, (N, G)).cpu().numpy().astype(np.int64),
                   n=self._view(lay.n, (N, G)).cpu().numpy(),
@@ -260,7 +271,8 @@ class Router:
                   qid=self._view(lay.qid, (N, Q)).cpu().numpy())
         if P:
             st["pred"] = self._view(lay.pred, (N, G, Bs, P), "f32")[:, :, :B].cpu().numpy()
-            st["qpred"] = self._view(lay.qpred, (N, Q, P), "f32").cpu().numpy()
+            if Pq:
+                st["qpred"] = self._view(lay.qpred, (N, Q, Pq), "f32").cpu().numpy()
         if H > 0:
             st["Lh"] = self._view(lay.Lh, (N, G, H + 1)).cpu().numpy().astype(np.int64)
             st["Mh"] = self._view(lay.Mh, (N, H + 1)).cpu().numpy().astype(np.int64)

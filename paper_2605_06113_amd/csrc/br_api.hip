@@ -18,7 +18,9 @@ struct EvPair {
 
 uint64_t align_up(uint64_t x) { return (x + 255u) & ~(uint64_t)255u; }
 
-int pred_width(const br_config &c) { return c.H == 0 ? 0 : (c.pred_mode == 1 ? 1 : c.H); }
+int pred_width(const br_config &c) { return c.H == 0 ? 0 : (c.pred_mode == 2 ? 3 : (c.pred_mode == 1 ? 1 : c.H)); }
+
+int queue_pred_width(const br_config &c) { return c.pred_mode == 2 ? 0 : pred_width(c); }
 
 bool config_ok(const br_config *c) {
   if (!c) return false;
@@ -26,7 +28,11 @@ bool config_ok(const br_config *c) {
   if (c->max_wait < 1 || c->max_wait > BR_MAX_WAIT || c->H < 0 || c->H > BR_MAX_H) return false;
   if (c->R_max < 1 || c->R_max > BR_MAX_RMAX || c->S_greedy < 0) return false;
   if (c->token_watermark < 0 || c->token_cap < 0) return false;
-  if (c->pred_mode != 0 && c->pred_mode != 1) return false;
+  if (c->pred_mode < 0 || c->pred_mode > 2) return false;
+  if (c->pred_mode == 2) {
+    if (c->H == 0 || !c->hist || !c->hist_sum || c->hist_n < 1 || c->hist_n > (1 << 20) || c->refresh_period < 1)
+      return false;
+  }
   if (c->H > 0) {
     if (!(c->alpha > 0.0f) || !(c->beta >= 0.0f) || !(c->gamma > 0.0f) || !(c->gamma <= 1.0f)) return false;
   }
@@ -35,7 +41,7 @@ bool config_ok(const br_config *c) {
 
 void make_layout(const br_config &c, br_layout *l) {
   const uint64_t N = (uint64_t)c.n_inst, G = (uint64_t)c.G, Q = (uint64_t)c.max_wait, H1 = (uint64_t)c.H + 1;
-  const uint64_t P = (uint64_t)pred_width(c);
+  const uint64_t P = (uint64_t)pred_width(c), Pq = (uint64_t)queue_pred_width(c);
   const uint64_t Bs = ((uint64_t)c.B + 3u) & ~(uint64_t)3u;
   uint64_t off = 0;
   auto take = [&](uint64_t words) {
@@ -52,7 +58,7 @@ void make_layout(const br_config &c, br_layout *l) {
   l->qs = take(N * Q);
   l->qo = take(N * Q);
   l->qid = take(N * Q);
-  l->qpred = take(N * Q * P);
+  l->qpred = take(N * Q * Pq);
   l->Lh = take(N * G * H1);
   l->Mh = take(N * H1);
   l->mh = take(N * G * H1);
@@ -60,6 +66,8 @@ void make_layout(const br_config &c, br_layout *l) {
   l->total_bytes = off;
   l->B_stride = (int32_t)Bs;
   l->P = (int32_t)P;
+  l->Pq = (int32_t)Pq;
+  l->pad = 0;
 }
 
 }  // namespace
@@ -152,6 +160,12 @@ int32_t br_init(const br_config *cfg, const br_init_state *init, br_ctx **out) {
   p.Q = cfg->max_wait;
   p.H = cfg->H;
   p.P = P;
+  p.Pq = queue_pred_width(*cfg);
+  p.hist_n = cfg->pred_mode == 2 ? cfg->hist_n : 0;
+  p.refresh = cfg->pred_mode == 2 ? cfg->refresh_period : 1;
+  p.pad0 = 0;
+  p.hist = cfg->pred_mode == 2 ? cfg->hist : nullptr;
+  p.hsum = cfg->pred_mode == 2 ? (const long long *)cfg->hist_sum : nullptr;
   p.R_max = cfg->R_max;
   p.S_greedy = cfg->S_greedy;
   p.W = cfg->token_watermark;
@@ -202,7 +216,7 @@ int32_t br_route_step(br_ctx *ctx, const br_arrivals *in, const br_step_out *out
   if (!ctx) return BR_EINVAL;
   BrArr a{};
   if (in && in->count && in->arr_cap > 0) {
-    if (!in->s || !in->o || (ctx->p.P > 0 && !in->pred)) return BR_EINVAL;
+    if (!in->s || !in->o || (ctx->p.Pq > 0 && !in->pred)) return BR_EINVAL;
     a.count = in->count;
     a.s = in->s;
     a.o = in->o;

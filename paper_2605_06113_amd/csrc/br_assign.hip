@@ -62,6 +62,12 @@ __global__ __launch_bounds__(256) void br_k_assign(BrParams p, BrArr a, BrOut o)
   const int qn = q0 + min(cnt, p.Q - q0);
   const int64_t qrow = (int64_t)inst * p.Q, arow = (int64_t)inst * a.arr_cap;
 
+  // first estimate of a newly admitted request when the library maintains c_hat (age 0)
+  float c0 = 0.0f;
+  if constexpr (BRH) {
+    if (p.pred_mode == 2) c0 = br_survival(p, 0);
+  }
+
   // ---- worker state, one worker per lane
   const bool act = lane < G;
   const int64_t wrow = (int64_t)inst * G + lane;
@@ -436,7 +442,7 @@ __global__ __launch_bounds__(256) void br_k_assign(BrParams p, BrArr a, BrOut o)
   rc.guard = guard;
   rc.wdrop = wdrop;
   rc.I_before = I_before;
-  br_assign_epilogue<E>(inst, lane, q0, qn, cnt, skey, adm, who, Lh[0], nn, rc);
+  br_assign_epilogue<E>(inst, lane, q0, qn, cnt, skey, adm, who, Lh[0], nn, rc, c0);
 }
 
 template <int E, bool BRH>

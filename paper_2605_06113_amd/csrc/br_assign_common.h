@@ -25,10 +25,10 @@ struct BrTailArgs {
   const float *apred;
   int32_t *assign, *assign_id;
   long long *stats;
-  int32_t G, B, Bs, Q, P, C, arr_cap;
+  int32_t G, B, Bs, Q, P, Pq, C, arr_cap;
 };
 
-static_assert(sizeof(BrParams) == 208 && sizeof(BrArr) == 48 && sizeof(BrOut) == 48, "kernel argument layout");
+static_assert(sizeof(BrParams) == 240 && sizeof(BrArr) == 48 && sizeof(BrOut) == 48, "kernel argument layout");
 
 __device__ __forceinline__ BrTailArgs br_tail_args() {
   typedef __attribute__((address_space(4))) const char kchar_t;
@@ -45,7 +45,7 @@ __device__ __forceinline__ BrTailArgs br_tail_args() {
   t.qlen = kp->qlen, t.qs = kp->qs, t.qo = kp->qo, t.qid = kp->qid, t.qpred = kp->qpred;
   t.as = kaa->s, t.ao = kaa->o, t.aid = kaa->id, t.apred = kaa->pred;
   t.assign = ko->assign, t.assign_id = ko->assign_id, t.stats = ko->stats;
-  t.G = kp->G, t.B = kp->B, t.Bs = kp->Bs, t.Q = kp->Q, t.P = kp->P, t.C = kp->C;
+  t.G = kp->G, t.B = kp->B, t.Bs = kp->Bs, t.Q = kp->Q, t.P = kp->P, t.Pq = kp->Pq, t.C = kp->C;
   t.arr_cap = kaa->arr_cap;
   return t;
 }
@@ -53,7 +53,7 @@ __device__ __forceinline__ BrTailArgs br_tail_args() {
 template <int E>
 __device__ __forceinline__ void br_assign_epilogue(int inst, int lane, int q0, int qn, int cnt, const int *skey,
                                                    const int *adm, int *who, int Lcur, int nn,
-                                                   const BrRoundCounts &rc) {
+                                                   const BrRoundCounts &rc, float c0) {
   constexpr int IDX_MASK = (1 << BR_IDX_BITS) - 1;
   const BrTailArgs t = br_tail_args();
   const int G = t.G;
@@ -77,8 +77,13 @@ __device__ __forceinline__ void br_assign_epilogue(int inst, int lane, int q0, i
             const bool old = idx < q0;
             t.kv[row] = key >> BR_IDX_BITS;
             t.rem[row] = old ? t.qo[qrow + idx] : max(t.ao[arow + (idx - q0)], 1);
-            for (int q = 0; q < t.P; ++q)
-              t.pred[row * t.P + q] = old ? t.qpred[(qrow + idx) * t.P + q] : t.apred[(arow + (idx - q0)) * t.P + q];
+            for (int q = 0; q < t.Pq; ++q)
+              t.pred[row * t.P + q] = old ? t.qpred[(qrow + idx) * t.Pq + q] : t.apred[(arow + (idx - q0)) * t.Pq + q];
+            if (t.P == 3 && t.Pq == 0) {  // maintained estimate: first query at age 0, nothing generated yet
+              t.pred[row * 3] = c0;
+              t.pred[row * 3 + 1] = 0.0f;
+              t.pred[row * 3 + 2] = 0.0f;
+            }
             who[idx] = g;
           }
         }
@@ -110,11 +115,11 @@ __device__ __forceinline__ void br_assign_epilogue(int inst, int lane, int q0, i
         s = min(max(s, 1), BR_MAX_S_DEV);
         const int oo = old ? t.qo[qrow + i] : max(t.ao[arow + (i - q0)], 1);
         float pr[BR_HP];
-        for (int q = 0; q < t.P; ++q) pr[q] = old ? t.qpred[(qrow + i) * t.P + q] : t.apred[(arow + (i - q0)) * t.P + q];
+        for (int q = 0; q < t.Pq; ++q) pr[q] = old ? t.qpred[(qrow + i) * t.Pq + q] : t.apred[(arow + (i - q0)) * t.Pq + q];
         t.qs[qrow + ni] = s;
         t.qo[qrow + ni] = oo;
         t.qid[qrow + ni] = id;
-        for (int q = 0; q < t.P; ++q) t.qpred[(qrow + ni) * t.P + q] = pr[q];
+        for (int q = 0; q < t.Pq; ++q) t.qpred[(qrow + ni) * t.Pq + q] = pr[q];
       }
       kept += __builtin_popcountll(bal);
     }

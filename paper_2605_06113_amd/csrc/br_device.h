@@ -14,6 +14,7 @@
 
 struct BrParams {
   int32_t N, G, B, Bs, Q, H, P, R_max, S_greedy, W, C, pred_mode;
+  int32_t Pq, hist_n, refresh, pad0;  // queue prediction width; survival-estimator history size and period
   float aD, beta, gate;
   float d[BR_HP + 1];  // discount vector, zero beyond H
   // workspace arrays
@@ -22,6 +23,8 @@ struct BrParams {
   int32_t *qlen, *qs, *qo, *qid;
   float *qpred;
   int32_t *Lh, *Mh, *mh, *minm;
+  const int32_t *hist;      // sorted output lengths (pred_mode 2)
+  const long long *hsum;    // their prefix sums
 };
 
 struct BrArr {  // arrivals of one round (device pointers, may be null when none)
@@ -147,7 +150,7 @@ __device__ __forceinline__ int br_score_key(const BrParams &p, const int (&m)[BR
 __device__ __forceinline__ float br_chat_vals(const BrParams &p, const float (&pr)[BR_HP]) {
   const float Hf = (float)p.H;
   float c;
-  if (p.pred_mode == 1) {
+  if (p.pred_mode >= 1) {
     c = pr[0];
   } else {
     float S = 1.0f;
@@ -182,4 +185,38 @@ __device__ __forceinline__ void br_load_pred(const BrParams &p, const float *src
     for (int j = 0; j < BR_HP; ++j)
       if (j < p.P) pr[j] = src[j];
   }
+}
+
+// Empirical-survival estimate of the in-window contribution at age a (Appendix "Estimator
+// realizations"): with F the empirical CDF of the sorted output-length history,
+// p_fin = (F(a+H) - F(a)) / (1 - F(a)), mu_rem = mean of (o_j - a) over a < o_j <= a+H, then the
+// composite, gate, floor and clip of eq. (composite) / "Refresh logic".  All counts and the sum of
+// remainders are exact integers below 2^24, so each quotient is one correctly rounded division.
+__device__ __forceinline__ int br_hist_rank(const BrParams &p, int x) {
+  int lo = 0, hi = p.hist_n;
+  while (lo < hi) {
+    const int mid = (lo + hi) >> 1;
+    if (p.hist[mid] <= x)
+      lo = mid + 1;
+    else
+      hi = mid;
+  }
+  return lo;
+}
+
+__device__ __forceinline__ float br_survival(const BrParams &p, int age) {
+  const float Hf = (float)p.H;
+  const int lo = br_hist_rank(p, age), hi = br_hist_rank(p, age + p.H);
+  const int surv = p.hist_n - lo, cnt = hi - lo;
+  float pf = 0.0f, mu = 0.0f;
+  if (surv > 0 && cnt > 0) {
+    const long long rem_sum = (p.hsum[hi] - p.hsum[lo]) - (long long)cnt * age;
+    pf = __fdiv_rn((float)cnt, (float)surv);
+    mu = __fdiv_rn((float)(int)rem_sum, (float)cnt);
+  }
+  float c = __fadd_rn(__fmul_rn(__fsub_rn(1.0f, pf), Hf), __fmul_rn(pf, mu));
+  if (p.gate > 0.0f && pf < p.gate) c = Hf;
+  c = c < 1.0f ? 1.0f : c;
+  c = c > Hf ? Hf : c;
+  return c;
 }

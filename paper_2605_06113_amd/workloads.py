@@ -44,7 +44,8 @@ class RouteConfig:
     beta: float = -1.0          # -1 => float(G)
     gamma: float = 0.9
     gate_pfin: float = 0.5
-    pred_mode: int = 0          # 0 hazards p[1..H], 1 direct c_hat
+    pred_mode: int = 0          # 0 hazards p[1..H], 1 direct c_hat, 2 empirical-survival estimator
+    refresh_period: int = 0     # pred_mode 2: tokens between predictor refreshes (0 => max(H // 2, 1))
     steps: int = 1
     seed: int = 0
     # generator knobs
@@ -72,6 +73,10 @@ class RouteConfig:
     @property
     def s_greedy(self) -> int:
         return self.G * self.R_max if self.S_greedy < 0 else self.S_greedy
+
+    @property
+    def refresh_eff(self) -> int:
+        return self.refresh_period if self.refresh_period > 0 else max(self.H // 2, 1)
 
     @property
     def beta_eff(self) -> float:
@@ -186,10 +191,16 @@ def _instance_rngs(cfg: RouteConfig):
 
 
 def pred_width(cfg: RouteConfig) -> int:
-    """Floats stored per request for the prediction interface."""
-    if cfg.H == 0:
+    """Floats a waiting request / an arrival carries for the prediction interface."""
+    if cfg.H == 0 or cfg.pred_mode == 2:
         return 0
     return 1 if cfg.pred_mode == 1 else cfg.H
+
+
+def output_history(cfg: RouteConfig, n: int = 4096) -> np.ndarray:
+    """Sorted output lengths of a synthetic training corpus (same length mix as the arrivals)."""
+    rng = np.random.Generator(np.random.PCG64([cfg.seed, 3]))
+    return np.sort(outputs(rng, cfg, n)).astype(np.int32)
 
 
 def initial_state(cfg: RouteConfig) -> InitState:

@@ -36,6 +36,7 @@ def compare_state(oc, st, cfg, tag=""):
         assert np.array_equal(st[k][inq], getattr(oc, k)[inq]), f"{tag} {k}"
     if oc.P:
         assert np.array_equal(st["pred"][used], oc.pred[used]), f"{tag} pred"
+    if oc.Pq:
         assert np.array_equal(st["qpred"][inq], oc.qpred[inq]), f"{tag} qpred"
 
 

@@ -21,10 +21,10 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_struct_sizes_match_header():
-    assert C.sizeof(binding.Config) == 14 * 4 + 3 * 8
+    assert C.sizeof(binding.Config) == 14 * 4 + 3 * 8 + 2 * 8 + 2 * 4
     assert C.sizeof(binding.Arrivals) == 5 * 8 + 8
     assert C.sizeof(binding.StepOut) == 6 * 8
-    assert C.sizeof(binding.Layout) == 15 * 8 + 8
+    assert C.sizeof(binding.Layout) == 15 * 8 + 16
 
 
 def test_workspace_bytes_scale():

@@ -8,7 +8,7 @@ import pytest
 
 from oracle import br_oracle
 from paper_2605_06113_amd import binding, workloads as wl
-from tests.parity import compare_outputs, compare_state, run_pair
+from tests.parity import compare_outputs, compare_prep, compare_state, run_pair
 
 pytestmark = pytest.mark.gpu
 
@@ -173,7 +173,7 @@ def test_replay_full_length(name, over):
     for k in range(cfg.steps):
         a = tr.step(k)
         ref = oc.route_step(a, want_scores=False)
-        darr = binding.DeviceArrivals(a, r.device, r.P)
+        darr = binding.DeviceArrivals(a, r.device, r.Pq)
         r.route_step_device(darr, out)
         r.advance(1)
         r.stream.synchronize()
@@ -229,6 +229,34 @@ def test_pool_bypass():
         compare_outputs(ref, out, cfg, f"bypass {seed} then round")
         compare_state(oc, r.state(), cfg, f"bypass {seed} then round")
         r.close()
+
+
+@pytest.mark.parametrize("H,refresh,gate", [(4, 0, 0.0), (8, 3, 0.5), (8, 1, 0.0)])
+def test_maintained_estimate_replay(H, refresh, gate):
+    """pred_mode 2: c_hat kept by the library (empirical-survival estimator, periodic refresh, decrement,
+    floor): replay with short outputs so that the estimate moves; slot tables incl. (c_hat, age, since)."""
+    cfg = wl.config("c3", G=8, B=24, max_wait=128, H=H, pred_mode=2, refresh_period=refresh, gate_pfin=gate,
+                    token_watermark=0, arrival_rate=14.0, out_mu=float(np.log(3.0 * H)), out_sigma=0.9, out_hi=400,
+                    seed=70 + H + refresh)
+    hist = wl.output_history(cfg, 3000)
+    _say(f"maintained estimate H={H} refresh={cfg.refresh_eff} gate={gate}")
+    steps = 300
+    tr = wl.arrival_trace(cfg, steps)
+    oc, r = br_oracle.OracleCluster(cfg, hist=hist), binding.Router(cfg, hist=hist)
+    for k in range(steps):
+        a = tr.step(k)
+        ref = oc.route_step(a, want_scores=(k % 20 == 0), want_prep=True)
+        out = r.route_step(a, scores=(k % 20 == 0))
+        if k % 10 == 0:
+            compare_prep(ref, r.state(), f"mode2 step {k}")
+        compare_outputs(ref, out, cfg, f"mode2 step {k}")
+        t = 1 if k % 7 else 3
+        oc.advance(t)
+        r.advance(t)
+        if k % 10 == 0 or k == steps - 1:
+            compare_state(oc, r.state(), cfg, f"mode2 step {k}")
+    assert (oc.pred[..., 0][np.arange(cfg.B)[None, None, :] < oc.n[:, :, None]] < H).any()   # estimates did move
+    r.close()
 
 
 def test_determinism():

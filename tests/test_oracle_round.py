@@ -13,7 +13,7 @@ from paper_2605_06113_amd import workloads as wl
 
 
 def _mk(orc, cfg, init=None, **kw):
-    return orc.OracleCluster(cfg, init, **kw)
+    return orc.OracleCluster(cfg, init, **kw)  # kw: force_float, hist
 
 
 def _arr(s, o=None, ids=None, pred=None):
