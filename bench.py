@@ -184,6 +184,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--latency-steps", type=int, default=1000)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--two-calls", action="store_true",
+                    help="time br_route_step + br_advance_decode instead of the fused br_route_advance")
+    ap.add_argument("--no-two-calls-leg", action="store_true", help="skip the side measurement of the two-call step")
     ap.add_argument("--no-brh", action="store_true", help="skip the batched BR-H side measurement")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (reference for scaling rocprofv3 byte counters)")
@@ -215,38 +218,47 @@ def main():
     cfg = wl.config("c4")
     init, arr = wl.initial_state(cfg), wl.initial_waiting(cfg)
     K, W = args.steps, args.warmup
-    routers = [binding.Router(cfg, init, device=device) for _ in range(K + W)]
     darr = binding.DeviceArrivals(arr, device, 0)
-    out = routers[0].alloc_outputs(scores=True, matrix=False)
-    torch.cuda.synchronize()
 
-    def step(r):
-        r.route_step_device(darr, out)
-        r.advance(1)
+    def timed(fused):
+        """W + K steps, each on its own copy of the cluster state; per-kernel HIP-event times of the K."""
+        routers = [binding.Router(cfg, init, device=device) for _ in range(K + W)]
+        out = routers[0].alloc_outputs(scores=True, matrix=False)
+        torch.cuda.synchronize()
 
-    for r in routers[:W]:
-        step(r)
-    torch.cuda.synchronize()
-    for r in routers[W:]:
-        r.profile(True)
-    t0 = time.perf_counter()
-    for r in routers[W:]:
-        step(r)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    elapsed = t1 - t0
+        def step(r):
+            if fused:
+                r.route_advance_device(darr, out, 1)
+            else:
+                r.route_step_device(darr, out)
+                r.advance(1)
 
-    stats = out["stats"].cpu().numpy()
+        for r in routers[:W]:
+            step(r)
+        torch.cuda.synchronize()
+        for r in routers[W:]:
+            r.profile(True)
+        t0 = time.perf_counter()
+        for r in routers[W:]:
+            step(r)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        stats = out["stats"].cpu().numpy()
+        kern = {k: [0.0, 0] for k in binding.KERNEL_NAMES}
+        for r in routers[W:]:
+            for k, (ms, c) in r.profile_read().items():
+                kern[k][0] += ms
+                kern[k][1] += c
+        for r in routers:
+            r.close()
+        del routers, out
+        return t1 - t0, stats, kern
+
+    fused = not args.two_calls
+    elapsed, stats, kern = timed(fused)
     admitted = int(stats[:, binding.ST["admitted"]].sum())
     qn = int(stats[:, binding.ST["qlen"]].sum())
     pairs_per_step = qn * cfg.G
-    kern = {k: [0.0, 0] for k in binding.KERNEL_NAMES}
-    for r in routers[W:]:
-        for k, (ms, c) in r.profile_read().items():
-            kern[k][0] += ms
-            kern[k][1] += c
-    for r in routers:
-        r.close()
 
     # algorithmic work per launch of each kernel (stated in DESIGN.md)
     N, G, B, Q = cfg.n_inst, cfg.G, cfg.B, cfg.max_wait
@@ -255,21 +267,29 @@ def main():
     bytes_score = qn * 4 + qn * 4 + N * G * (8 + 4)   # s read, best_g written; L, n read, best_i written
     bytes_assign = qn * (4 + 4 + 4 + 4 + 4) + admitted * 8 + N * G * 16 + N * 16 * 8
     ops_assign = 4.0 * admitted * (Q)               # per admission: one score (4 int ops) per waiting slot
-    per_kernel = {}
-    for k, (ms, c) in kern.items():
-        if c == 0:
-            continue
-        avg = ms / c
-        e = dict(avg_ms=avg, launches=c)
-        if k == "advance":
-            e.update(bound="hbm", achieved_GBs=bytes_advance / (avg * 1e-3) / 1e9, frac=bytes_advance / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS)
-        elif k == "score":
-            e.update(bound="hbm", achieved_GBs=bytes_score / (avg * 1e-3) / 1e9, frac=bytes_score / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS)
-        elif k == "assign":
-            e.update(bound="alu", achieved_Tops=ops_assign / (avg * 1e-3) / 1e12,
-                     frac=ops_assign / (avg * 1e-3) / 1e12 / ALU_INT_PEAK_TOPS,
-                     hbm_GBs=bytes_assign / (avg * 1e-3) / 1e9)
-        per_kernel[k] = e
+
+    def kernel_table(kern, fused):
+        tab = {}
+        for k, (ms, c) in kern.items():
+            if c == 0:
+                continue
+            avg = ms / c
+            e = dict(avg_ms=avg, launches=c)
+            b_assign = bytes_assign + (bytes_advance if fused else 0)   # the fused launch also streams the lists
+            if k == "advance":
+                e.update(bound="hbm", achieved_GBs=bytes_advance / (avg * 1e-3) / 1e9,
+                         frac=bytes_advance / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS)
+            elif k == "score":
+                e.update(bound="hbm", achieved_GBs=bytes_score / (avg * 1e-3) / 1e9,
+                         frac=bytes_score / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS)
+            elif k == "assign":
+                e.update(bound="alu", achieved_Tops=ops_assign / (avg * 1e-3) / 1e12,
+                         frac=ops_assign / (avg * 1e-3) / 1e12 / ALU_INT_PEAK_TOPS,
+                         hbm_GBs=b_assign / (avg * 1e-3) / 1e9, includes_decode_step=bool(fused))
+            tab[k] = e
+        return tab
+
+    per_kernel = kernel_table(kern, fused)
     dom = max((k for k in per_kernel if k != "init"), key=lambda k: per_kernel[k]["avg_ms"])
     d = per_kernel[dom]
     if d["bound"] == "hbm":
@@ -278,7 +298,7 @@ def main():
     else:
         roofline = dict(bound="alu", kernel=dom, achieved=d["achieved_Tops"], peak=ALU_INT_PEAK_TOPS, unit="TOP/s",
                         frac=d["frac"])
-    kib = args.traffic_kib if args.traffic_kib is not None else TRAFFIC_KIB.get(dom)
+    kib = args.traffic_kib if args.traffic_kib is not None else TRAFFIC_KIB.get(dom + ("+advance" if fused else ""))
     roofline["traffic"] = None if kib is None else kib * 1024.0
     roofline["avg_launch_ms"] = d["avg_ms"]
     step_bytes = bytes_advance + bytes_score + bytes_assign
@@ -296,7 +316,12 @@ def main():
                decisions_per_s=admitted * K / elapsed,
                step_hbm_GBs=step_bytes / (ms_per_step * 1e-3) / 1e9,
                step_hbm_frac=step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+               entry="br_route_advance" if fused else "br_route_step + br_advance_decode",
                roofline=roofline, kernels=per_kernel)
+    if fused and not args.no_two_calls_leg:
+        e2, _, k2 = timed(False)
+        res["two_calls"] = dict(entry="br_route_step + br_advance_decode", ms_per_step=e2 / K * 1e3,
+                                pairs_per_s=pairs_per_step * K / e2, kernels=kernel_table(k2, False))
     if not args.no_brh:
         res["brh_batched"] = brh_run(device)
         res["bypass"] = bypass_run(device, cfg, init, arr)

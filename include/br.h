@@ -205,6 +205,18 @@ int32_t br_route_step(br_ctx *ctx, const br_arrivals *in, const br_step_out *out
 int32_t br_advance_decode(br_ctx *ctx, int32_t n_steps);
 
 /*
+ * One decode step of the serving loop in a single launch: the round of br_route_step followed by
+ * n_steps decode steps of br_advance_decode (Sec. 2.2; Alg. BR-0 / Alg. BR-H), with exactly their
+ * results: same outputs (written as br_route_step writes them, statistics describe the state
+ * right after the round) and same workspace contents afterwards as the two calls in sequence.
+ * The wave that has routed a cluster applies the decode steps to that cluster's lists, so clusters
+ * that finish their round early stream their lists while others are still routing.
+ * Arguments, ownership and errors as for br_route_step; n_steps >= 0 (0: identical to
+ * br_route_step), BR_EINVAL otherwise.
+ */
+int32_t br_route_advance(br_ctx *ctx, const br_arrivals *in, const br_step_out *out, int32_t n_steps);
+
+/*
  * Pool-bypass dispatch for BR-0 (Appendix "Pool-bypass deployment path for BR-0"): instead of
  * waiting in the pool for a scheduling round, each arrival is placed at once, in order, on
  * argmax_g F_g(s) with F_g(s) = s - G (s - m_g)_+ (eq. (br0-Fscore)) over the workers that have a

@@ -23,7 +23,7 @@ ST = dict(admitted=0, deferred=1, dropped=2, stage1=3, stage2_pops=4, guard=5, o
           I_before=7, I_after=8, spread=9, qlen=10, workers_dropped=11)
 BR_OK, BR_EINVAL, BR_ENOMEM, BR_EHIP = 0, -1, -2, -3
 
-EXPORTS = ("br_workspace_bytes", "br_init", "br_route_step", "br_route_bypass", "br_advance_decode", "br_free",
+EXPORTS = ("br_workspace_bytes", "br_init", "br_route_step", "br_route_advance", "br_route_bypass", "br_advance_decode", "br_free",
            "br_last_hip_error", "br_get_layout", "br_profile_enable", "br_profile_read")
 
 _P = C.c_void_p
@@ -76,6 +76,8 @@ def load():
     lib.br_init.argtypes = [C.POINTER(Config), C.POINTER(InitState), C.POINTER(_P)]
     lib.br_route_step.restype = C.c_int32
     lib.br_route_step.argtypes = [_P, C.POINTER(Arrivals), C.POINTER(StepOut)]
+    lib.br_route_advance.restype = C.c_int32
+    lib.br_route_advance.argtypes = [_P, C.POINTER(Arrivals), C.POINTER(StepOut), C.c_int32]
     lib.br_route_bypass.restype = C.c_int32
     lib.br_route_bypass.argtypes = [_P, C.POINTER(Arrivals), C.POINTER(StepOut)]
     lib.br_advance_decode.restype = C.c_int32
@@ -212,11 +214,22 @@ class Router:
         _check(self.lib.br_route_step(self.ctx, C.byref(a) if a is not None else None, C.byref(o)),
                "br_route_step", self.ctx)
 
-    def route_step(self, arr=None, scores: bool = True, matrix: bool = True):
-        """Convenience for tests: host arrays in, numpy out (synchronises)."""
+    def route_advance_device(self, darr: Optional[DeviceArrivals], out, n_steps: int = 1) -> None:
+        """Enqueue one round and n_steps decode steps as one launch; no synchronisation."""
+        a = darr.struct() if darr is not None else None
+        o = self.out_struct(out)
+        _check(self.lib.br_route_advance(self.ctx, C.byref(a) if a is not None else None, C.byref(o), int(n_steps)),
+               "br_route_advance", self.ctx)
+
+    def route_step(self, arr=None, scores: bool = True, matrix: bool = True, advance: int = 0):
+        """Convenience for tests: host arrays in, numpy out (synchronises).  advance > 0 takes the
+        fused entry point (round + that many decode steps)."""
         darr = DeviceArrivals(arr, self.device, self.Pq) if arr is not None else None
         out = self.alloc_outputs(scores, matrix)
-        self.route_step_device(darr, out)
+        if advance > 0:
+            self.route_advance_device(darr, out, advance)
+        else:
+            self.route_step_device(darr, out)
         self.stream.synchronize()
         return {k: v.cpu().numpy() for k, v in out.items()}
 

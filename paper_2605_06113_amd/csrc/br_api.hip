@@ -163,7 +163,7 @@ int32_t br_init(const br_config *cfg, const br_init_state *init, br_ctx **out) {
   p.Pq = queue_pred_width(*cfg);
   p.hist_n = cfg->pred_mode == 2 ? cfg->hist_n : 0;
   p.refresh = cfg->pred_mode == 2 ? cfg->refresh_period : 1;
-  p.pad0 = 0;
+  p.adv_t = 0;
   p.hist = cfg->pred_mode == 2 ? cfg->hist : nullptr;
   p.hsum = cfg->pred_mode == 2 ? (const long long *)cfg->hist_sum : nullptr;
   p.R_max = cfg->R_max;
@@ -212,8 +212,9 @@ int32_t br_init(const br_config *cfg, const br_init_state *init, br_ctx **out) {
   return BR_OK;
 }
 
-int32_t br_route_step(br_ctx *ctx, const br_arrivals *in, const br_step_out *out) {
-  if (!ctx) return BR_EINVAL;
+// one round, optionally followed inside the assignment kernel by `adv_t` decode steps
+static int32_t route(br_ctx *ctx, const br_arrivals *in, const br_step_out *out, int32_t adv_t) {
+  if (!ctx || adv_t < 0) return BR_EINVAL;
   BrArr a{};
   if (in && in->count && in->arr_cap > 0) {
     if (!in->s || !in->o || (ctx->p.Pq > 0 && !in->pred)) return BR_EINVAL;
@@ -233,13 +234,20 @@ int32_t br_route_step(br_ctx *ctx, const br_arrivals *in, const br_step_out *out
     o.best_g = out->best_g;
     o.best_i = out->best_i;
   }
-  const BrParams &p = ctx->p;
+  BrParams p = ctx->p;
+  p.adv_t = adv_t;
   int32_t rc = BR_OK;
   if (p.H > 0) rc = enqueue(ctx, BR_K_PROJECT, [&] { br_launch_project(p, ctx->st); });
   if (rc == BR_OK && (o.F || o.best_g || o.best_i))
     rc = enqueue(ctx, BR_K_SCORE, [&] { br_launch_score(p, a, o, ctx->st); });
   if (rc == BR_OK) rc = enqueue(ctx, BR_K_ASSIGN, [&] { br_launch_assign(p, a, o, ctx->st); });
   return rc;
+}
+
+int32_t br_route_step(br_ctx *ctx, const br_arrivals *in, const br_step_out *out) { return route(ctx, in, out, 0); }
+
+int32_t br_route_advance(br_ctx *ctx, const br_arrivals *in, const br_step_out *out, int32_t n_steps) {
+  return route(ctx, in, out, n_steps);
 }
 
 int32_t br_route_bypass(br_ctx *ctx, const br_arrivals *in, const br_step_out *out) {

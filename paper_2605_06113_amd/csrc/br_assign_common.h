@@ -158,3 +158,93 @@ __device__ __forceinline__ void br_assign_epilogue(int inst, int lane, int q0, i
     }
   }
 }
+
+// Late copy of the whole parameter block from the kernel-argument segment (same reason as above).
+__device__ __forceinline__ BrParams br_late_params() {
+  typedef __attribute__((address_space(4))) const char kchar_t;
+  typedef __attribute__((address_space(4))) const BrParams kparams_t;
+  kchar_t *ka = (kchar_t *)__builtin_amdgcn_kernarg_segment_ptr();
+  asm volatile("" : "+s"(ka));
+  BrParams p;
+  __builtin_memcpy(&p, (kparams_t *)ka, sizeof(BrParams));
+  return p;
+}
+
+// Decode advance of one cluster by the wave that has just routed it: the arithmetic of the
+// stand-alone advance kernel (Sec. 2.2 load model: a request that stays gains t tokens, one whose
+// remaining output is used up leaves with its whole kv), applied to the cluster's G lists in
+// (list, 64-slot chunk) units.  UB units are requested before the first is used.  Chunks are taken
+// in order and a chunk's survivors move to positions at or below their own, all of which were read
+// by this or an earlier chunk, so the compaction is safe in place.  `Lcur`, `nn`: load and list
+// length of worker `lane` after the round.
+template <int UB, bool BRH>
+__device__ __forceinline__ void br_advance_cluster(int inst, int lane, int Lcur, int nn) {
+  const BrParams p = br_late_params();
+  const int t = p.adv_t;
+  if (t <= 0) return;
+  br_wave_sync();  // the round's own writes into the lists are read back below
+  const int G = p.G, NC = (p.Bs + BR_WAVE - 1) / BR_WAVE, U = G * NC;
+  const int64_t row0 = (int64_t)__builtin_amdgcn_readfirstlane(inst) * G;  // scalar: list bases stay in SGPRs
+  int dLw = 0, nw = nn;     // lane g: load change and new length of worker g
+  int kept = 0, dL = 0;     // running state of the list in progress
+  int gl = 0, cl = 0, gp = 0, cp = 0;  // (list, chunk) cursors of the load and the update pass
+  for (int u0 = 0; u0 < U; u0 += UB) {
+    int kv[UB], rem[UB];
+#pragma unroll
+    for (int k = 0; k < UB; ++k) {
+      kv[k] = 0, rem[k] = 0;
+      if (gl < G) {
+        const int ng = __builtin_amdgcn_readlane(nn, gl);
+        const int j = cl * BR_WAVE + lane;
+        if (j < ng) {
+          const int64_t at = (row0 + gl) * p.Bs + j;
+          kv[k] = p.kv[at];
+          rem[k] = p.rem[at];
+        }
+      }
+      if (++cl == NC) cl = 0, ++gl;
+    }
+#pragma unroll
+    for (int k = 0; k < UB; ++k) {
+      if (gp < G) {
+        const int ng = __builtin_amdgcn_readlane(nn, gp);
+        const int64_t base = (row0 + gp) * p.Bs;
+        if (cp * BR_WAVE < ng) {
+          // unused lanes hold kv = rem = 0: they neither stay nor change the load
+          const bool stay = rem[k] > t;
+          dL += stay ? t : -kv[k];
+          const unsigned long long bal = br_ballot(stay);
+          const unsigned nj = (unsigned)(kept + br_rank_below(bal));
+          int32_t *const kvl = p.kv + base, *const reml = p.rem + base;
+          if (stay) {
+            kvl[nj] = kv[k] + t;
+            reml[nj] = rem[k] - t;
+            if constexpr (BRH) {
+              const unsigned j = (unsigned)(cp * BR_WAVE + lane);
+              float *const pl = p.pred + base * p.P;
+              if (p.pred_mode == 2) {
+                float ch = pl[j * 3], age = pl[j * 3 + 1], since = pl[j * 3 + 2];
+                br_refresh_update(p, t, ch, age, since);
+                pl[nj * 3] = ch;
+                pl[nj * 3 + 1] = age;
+                pl[nj * 3 + 2] = since;
+              } else if (nj != j) {
+                for (int q = 0; q < p.P; ++q) pl[nj * p.P + q] = pl[j * p.P + q];
+              }
+            }
+          }
+          kept += __builtin_popcountll(bal);
+        }
+        if (++cp == NC) {
+          const int tot = ng > 0 ? br_wave_sum(dL) : 0;
+          if (lane == gp) dLw = tot, nw = kept;
+          kept = 0, dL = 0, cp = 0, ++gp;
+        }
+      }
+    }
+  }
+  if (lane < G) {
+    p.L[row0 + lane] = Lcur + dLw;
+    p.n[row0 + lane] = nw;
+  }
+}

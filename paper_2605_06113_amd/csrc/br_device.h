@@ -14,7 +14,8 @@
 
 struct BrParams {
   int32_t N, G, B, Bs, Q, H, P, R_max, S_greedy, W, C, pred_mode;
-  int32_t Pq, hist_n, refresh, pad0;  // queue prediction width; survival-estimator history size and period
+  int32_t Pq, hist_n, refresh, adv_t;  // queue prediction width; survival-estimator history size and period;
+                                       // decode steps the assignment kernel applies after the round (0: none)
   float aD, beta, gate;
   float d[BR_HP + 1];  // discount vector, zero beyond H
   // workspace arrays
@@ -219,4 +220,24 @@ __device__ __forceinline__ float br_survival(const BrParams &p, int age) {
   c = c < 1.0f ? 1.0f : c;
   c = c > Hf ? Hf : c;
   return c;
+}
+
+// Appendix "Refresh logic", for a request that stays active over t more generated tokens: per token
+// one step less of in-window contribution; the estimator is queried again every `refresh` tokens and
+// whenever c_hat would fall below its floor of one.
+__device__ __forceinline__ void br_refresh_update(const BrParams &p, int t, float &ch, float &age, float &since) {
+  for (int u = 0; u < t; ++u) {
+    age = __fadd_rn(age, 1.0f);
+    since = __fadd_rn(since, 1.0f);
+    if ((int)since >= p.refresh) {
+      ch = br_survival(p, (int)age);
+      since = 0.0f;
+    } else {
+      ch = __fsub_rn(ch, 1.0f);
+      if (ch < 1.0f) {
+        ch = br_survival(p, (int)age);
+        since = 0.0f;
+      }
+    }
+  }
 }

@@ -88,24 +88,8 @@ __global__ __launch_bounds__(256) void br_k_advance(BrParams p, int t) {
           p.kv[base + nj] = kv[r][c] + t;
           p.rem[base + nj] = rem[r][c] - t;
           if (p.pred_mode == 2) {
-            // Appendix "Refresh logic": per generated token one step less of in-window contribution;
-            // the estimator is queried again every `refresh` tokens and whenever c_hat would fall
-            // below its floor of one
             float ch = p.pred[(base + j) * 3], age = p.pred[(base + j) * 3 + 1], since = p.pred[(base + j) * 3 + 2];
-            for (int u = 0; u < t; ++u) {
-              age = __fadd_rn(age, 1.0f);
-              since = __fadd_rn(since, 1.0f);
-              if ((int)since >= p.refresh) {
-                ch = br_survival(p, (int)age);
-                since = 0.0f;
-              } else {
-                ch = __fsub_rn(ch, 1.0f);
-                if (ch < 1.0f) {
-                  ch = br_survival(p, (int)age);
-                  since = 0.0f;
-                }
-              }
-            }
+            br_refresh_update(p, t, ch, age, since);
             p.pred[(base + nj) * 3] = ch;
             p.pred[(base + nj) * 3 + 1] = age;
             p.pred[(base + nj) * 3 + 2] = since;

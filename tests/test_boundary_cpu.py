@@ -62,6 +62,7 @@ def test_init_argument_errors():
     assert lib.br_init(C.byref(c), None, C.byref(ctx)) == binding.BR_ENOMEM          # too small
     assert lib.br_route_step(None, None, None) == binding.BR_EINVAL
     assert lib.br_advance_decode(None, 1) == binding.BR_EINVAL
+    assert lib.br_route_advance(None, None, None, 1) == binding.BR_EINVAL
     lib.br_free(None)                                                                  # allowed
 
 

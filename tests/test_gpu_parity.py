@@ -63,10 +63,11 @@ def test_random_rounds(case):
             _, _, arr2 = wl.random_case(77 + 1000 * case + seed + rnd, N=6, G=G, B=B, max_wait=Q, H=H,
                                         n_wait=max(1, Q // 3), **kw)
             ref = oc.route_step(arr2)
-            out = r.route_step(arr2)
+            out = r.route_step(arr2, advance=3 if rnd else 0)      # second one: round + decode steps in one launch
             compare_outputs(ref, out, cfg, f"case{case}/{seed}/r{rnd}")
             oc.advance(2 + rnd)
-            r.advance(2 + rnd)
+            if rnd == 0:
+                r.advance(2)
             compare_state(oc, r.state(), cfg, f"case{case}/{seed}/r{rnd}")
         r.close()
 
@@ -120,6 +121,7 @@ def test_advance_many_steps_closed_form():
         r.close()
 
 
+@pytest.mark.parametrize("fused", [False, True])
 @pytest.mark.parametrize("name,steps,over", [
     ("c2", 400, dict()),
     ("c2", 300, dict(arrival_rate=4.0, seed=1001)),                    # balanced: stages alternate
@@ -127,36 +129,41 @@ def test_advance_many_steps_closed_form():
     ("c3", 200, dict(gate_pfin=0.5, beta=14.67, gamma=0.64)),
     ("c5", 150, dict(gate_pfin=0.0)),
 ])
-def test_replay(name, steps, over):
+def test_replay(name, steps, over, fused):
+    """fused: br_route_advance (round + decode step in one launch) instead of the two calls."""
     cfg = wl.config(name, **over)
-    _say(f"replay {name} {steps} {over}")
+    _say(f"replay {name} {steps} {over} fused={fused}")
     tr = wl.arrival_trace(cfg, steps, informative=(name == "c3" and over.get("gate_pfin") == 0.5))
     oc, r = br_oracle.OracleCluster(cfg), binding.Router(cfg)
     for k in range(steps):
         a = tr.step(k)
         ref = oc.route_step(a, want_scores=(k % 25 == 0))
-        out = r.route_step(a, scores=(k % 25 == 0))
+        out = r.route_step(a, scores=(k % 25 == 0), advance=int(fused))
         compare_outputs(ref, out, cfg, f"{name} step {k}")
         oc.advance(1)
-        r.advance(1)
+        if not fused:
+            r.advance(1)
         if k % 25 == 0 or k == steps - 1:
             compare_state(oc, r.state(), cfg, f"{name} step {k}")
     r.close()
 
 
-def test_c4_full_size_bench_configuration():
-    """The batched throughput workload at full size, in the launch configuration bench.py times
-    (no score matrix written, best_g / best_i on): every instance against the oracle."""
+@pytest.mark.parametrize("fused", [False, True])
+def test_c4_full_size_bench_configuration(fused):
+    """The batched throughput workload at full size, in the launch configurations bench.py times
+    (no score matrix written, best_g / best_i on; round and decode step as two calls or as the one
+    fused call): every instance against the oracle."""
     cfg = wl.config("c4")
-    _say("c4 full size")
+    _say(f"c4 full size fused={fused}")
     init, arr = wl.initial_state(cfg), wl.initial_waiting(cfg)
     oc, r = br_oracle.OracleCluster(cfg, init), binding.Router(cfg, init)
     ref = oc.route_step(arr)
-    out = r.route_step(arr, matrix=False)
+    out = r.route_step(arr, matrix=False, advance=int(fused))
     compare_outputs(ref, out, cfg, "c4")
     assert (ref["stats"][:, br_oracle.ST["admitted"]] == 256).all()
     oc.advance(1)
-    r.advance(1)
+    if not fused:
+        r.advance(1)
     compare_state(oc, r.state(), cfg, "c4")
     r.close()
 
@@ -255,6 +262,13 @@ def test_maintained_estimate_replay(H, refresh, gate):
         r.advance(t)
         if k % 10 == 0 or k == steps - 1:
             compare_state(oc, r.state(), cfg, f"mode2 step {k}")
+        if k % 3 == 0:                                   # an extra round through the fused entry, no arrivals
+            ref = oc.route_step(None, want_scores=False)
+            out = r.route_step(None, scores=False, advance=2)
+            compare_outputs(ref, out, cfg, f"mode2 fused {k}")
+            oc.advance(2)
+            if k % 30 == 0:
+                compare_state(oc, r.state(), cfg, f"mode2 fused {k}")
     assert (oc.pred[..., 0][np.arange(cfg.B)[None, None, :] < oc.n[:, :, None]] < H).any()   # estimates did move
     r.close()
 
