@@ -11,6 +11,7 @@
 #define BR_MAX_G_DEV 64
 #define BR_MAX_S_DEV 32768
 #define BR_IDX_BITS 11   // queue positions fit 11 bits (max_wait <= 2048)
+#define BR_SCORE_WAVE_MIN_N 2048  // from this many clusters on (two waves per SIMD), short queues are scored one wave per cluster
 
 struct BrParams {
   int32_t N, G, B, Bs, Q, H, P, R_max, S_greedy, W, C, pred_mode;
@@ -125,8 +126,12 @@ __device__ __forceinline__ float br_unord(int k) { return __int_as_float(k ^ ((k
 
 #define BR_KEY_NONE INT32_MIN
 
-// Sec. 3.1, eq. (br0-Fscore): F = Delta - G (Delta - m)_+ in exact int32.
-__device__ __forceinline__ int br_score0(int G, int m, int delta) { return delta - G * max(delta - m, 0); }
+// Sec. 3.1, eq. (br0-Fscore): F = Delta - G (Delta - m)_+ in exact int32.  Delta <= 8 * 32768 and
+// G <= 64, so both factors fit 24 bits; the masks say so and the product becomes one full-rate
+// 24-bit multiply-add instead of a quarter-rate 32-bit multiply.
+__device__ __forceinline__ int br_score0(int G, int m, int delta) {
+  return delta + (max(delta - m, 0) & 0x7fffff) * -(G & 0x7f);
+}
 
 // Sec. 4.1, eq. (brh-Fscore): alpha (1^T d) Delta - beta ((Delta 1 - m)_+)^T d, fp32, each
 // operation rounded on its own, penalty accumulated from h = 0 upwards.  Offsets beyond H carry

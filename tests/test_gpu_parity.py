@@ -72,6 +72,30 @@ def test_random_rounds(case):
         r.close()
 
 
+@pytest.mark.parametrize("G,B,Q,H,extra", [
+    (16, 24, 256, 0, {}),
+    (7, 9, 200, 0, dict(token_watermark=30000, token_cap=28000, tie_heavy=True)),
+    (64, 6, 70, 0, dict(R_max=5)),
+    (3, 8, 512, 0, {}),
+    (33, 12, 100, 4, dict(gate_pfin=0.0)),
+    (12, 6, 300, 8, dict(pred_mode=1)),
+    (12, 10, 130, 3, dict(gate_pfin=0.5, gamma=0.64, beta=14.67, tie_heavy=True)),
+])
+def test_many_small_clusters(G, B, Q, H, extra):
+    """Batches of 2048 clusters and more with short queues take the one-wave-per-cluster score kernel
+    (no matrix requested): per-request best worker and per-worker best request against the oracle,
+    with ragged queue lengths, full workers and the watermark filter."""
+    N = 2048
+    _say(f"many small clusters N={N} G={G} B={B} Q={Q} H={H} {extra}")
+    cfg, init, arr = wl.random_case(500 + G + Q + H, N=N, G=G, B=B, max_wait=Q, H=H, fill=0.8, **extra)
+    oc, r = run_pair(cfg, init, arr, matrix=False, tag="small clusters")
+    _, _, arr2 = wl.random_case(900 + G + Q + H, N=N, G=G, B=B, max_wait=Q, H=H, n_wait=max(1, Q // 5), **extra)
+    compare_outputs(oc.route_step(arr2), r.route_step(arr2, matrix=False, advance=1), cfg, "small clusters r2")
+    oc.advance(1)
+    compare_state(oc, r.state(), cfg, "small clusters r2")
+    r.close()
+
+
 def test_edge_cases():
     # no arrivals at all (NULL), empty queue
     cfg, init, arr = wl.random_case(5, N=3, G=4, B=8, max_wait=32, H=0)
