@@ -345,6 +345,7 @@ __global__ __launch_bounds__(256) void br_k_assign(BrParams p, BrArr a, BrOut o)
       // by ballots and passed through LDS so that every lane holds all of them
       const int w = min(p.R_max, n_alive);
       advance_head();
+      int s_last = 0;  // smallest length in the window (its w-th entry)
       {
         int base = 0;
 #pragma unroll
@@ -354,53 +355,66 @@ __global__ __launch_bounds__(256) void br_k_assign(BrParams p, BrArr a, BrOut o)
             const unsigned long long bal = br_ballot(al);
             const int ar = base + br_rank_below(bal);
             if (al && ar < w) win[ar] = (sv[j] << BR_IDX_BITS) | (j * BR_WAVE + lane);
+            if constexpr (!BRH) {
+              const unsigned long long hit = br_ballot(al && ar == w - 1);
+              if (hit != 0ull) s_last = __builtin_amdgcn_readlane(sv[j], (int)__builtin_ctzll(hit));
+            }
             base += __builtin_popcountll(bal);
           }
         }
       }
-      br_wave_sync();
-      int wv[8];
-      {
-        const int4 lo = *reinterpret_cast<const int4 *>(win);
-        const int4 hi = *reinterpret_cast<const int4 *>(win + 4);
-        wv[0] = lo.x, wv[1] = lo.y, wv[2] = lo.z, wv[3] = lo.w;
-        wv[4] = hi.x, wv[5] = hi.y, wv[6] = hi.z, wv[7] = hi.w;
-      }
-      int ws[8];
-#pragma unroll
-      for (int b = 0; b < 8; ++b) ws[b] = b < w ? (wv[b] >> BR_IDX_BITS) : 0;
-
-      // exhaustive subset search, one subset mask per lane (ascending masks, strict improvement)
-      const int kmax = min(capmax, p.R_max);
-      const int nmask = 1 << w;
+      // BR-0: every subset of the window sums to at least its smallest entry, and eq. (br0-Fscore)
+      // falls beyond the margin; if that entry alone scores <= 0 (then it exceeds the margin), no
+      // subset scores above 0 and the round goes to the starvation guard without the enumeration.
+      bool guard_sure = false;
+      if constexpr (!BRH) guard_sure = br_score0(G, mg[0], s_last) <= 0;
+      int wv[8], ws[8];
       int bestmask = 0, bestkey = BR_KEY_NONE;
-      for (int c = 0; c * BR_WAVE < nmask; ++c) {
-        int delta = (c & 1) * ws[6] + (c >> 1) * ws[7];
+      if (!guard_sure) {
+        br_wave_sync();
+        {
+          const int4 lo = *reinterpret_cast<const int4 *>(win);
+          const int4 hi = *reinterpret_cast<const int4 *>(win + 4);
+          wv[0] = lo.x, wv[1] = lo.y, wv[2] = lo.z, wv[3] = lo.w;
+          wv[4] = hi.x, wv[5] = hi.y, wv[6] = hi.z, wv[7] = hi.w;
+        }
 #pragma unroll
-        for (int b = 0; b < 6; ++b)
-          if (b < w) delta += lbit[b] * ws[b];
-        const int mask = c * BR_WAVE + lane;
-        const bool ok = mask != 0 && mask < nmask && lpop + __builtin_popcount(c) <= kmax && delta <= room;
-        if constexpr (!BRH) {
-          const int F = delta - (int)((unsigned)(max(delta - mg[0], 0) & 0x7ffff) * (unsigned)(G & 0x7f));
-          const unsigned key = ok ? (((unsigned)(F + BIAS2) << 6) | (unsigned)(63 - lane)) : 0u;
-          const unsigned km = br_wave_umax(key);
-          if (km != 0u) {
-            const int Fm = (int)(km >> 6) - BIAS2;
-            if (Fm > bestkey) {
-              bestkey = Fm;
-              bestmask = c * BR_WAVE + (63 - (int)(km & 63u));
+        for (int b = 0; b < 8; ++b) ws[b] = b < w ? (wv[b] >> BR_IDX_BITS) : 0;
+
+        // exhaustive subset search, one subset mask per lane (ascending masks, strict improvement)
+        const int kmax = min(capmax, p.R_max);
+        const int nmask = 1 << w;
+        for (int c = 0; c * BR_WAVE < nmask; ++c) {
+          int delta = (c & 1) * ws[6] + (c >> 1) * ws[7];
+#pragma unroll
+          for (int b = 0; b < 6; ++b)
+            if (b < w) delta += lbit[b] * ws[b];
+          const int mask = c * BR_WAVE + lane;
+          const bool ok = mask != 0 && mask < nmask && lpop + __builtin_popcount(c) <= kmax && delta <= room;
+          if constexpr (!BRH) {
+            const int F = delta - (int)((unsigned)(max(delta - mg[0], 0) & 0x7ffff) * (unsigned)(G & 0x7f));
+            const unsigned key = ok ? (((unsigned)(F + BIAS2) << 6) | (unsigned)(63 - lane)) : 0u;
+            const unsigned km = br_wave_umax(key);
+            if (km != 0u) {
+              const int Fm = (int)(km >> 6) - BIAS2;
+              if (Fm > bestkey) {
+                bestkey = Fm;
+                bestmask = c * BR_WAVE + (63 - (int)(km & 63u));
+              }
+            }
+          } else {
+            int key = br_score_key<BRH>(p, mg, delta);
+            key = ok ? key : BR_KEY_NONE;
+            const int km = br_wave_max(key);
+            if (km > bestkey) {
+              bestkey = km;
+              bestmask = c * BR_WAVE + (int)__builtin_ctzll(br_ballot(key == km));
             }
           }
-        } else {
-          int key = br_score_key<BRH>(p, mg, delta);
-          key = ok ? key : BR_KEY_NONE;
-          const int km = br_wave_max(key);
-          if (km > bestkey) {
-            bestkey = km;
-            bestmask = c * BR_WAVE + (int)__builtin_ctzll(br_ballot(key == km));
-          }
         }
+      } else {
+#pragma unroll
+        for (int b = 0; b < 8; ++b) wv[b] = 0, ws[b] = 0;
       }
 
       if (bestmask == 0 || bestkey <= 0) {  // starvation guard: the single best request anyway
