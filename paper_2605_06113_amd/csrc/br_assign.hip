@@ -220,11 +220,49 @@ __global__ __launch_bounds__(256) void br_k_assign(BrParams p, BrArr a, BrOut o)
     return mn;
   };
 
+  // BR-0 without watermark and with G > 1: when no waiting request is shorter than the margin,
+  // eq. (br0-Fscore) is G m - (G-1) s on the whole waiting set, so argmax_i F_g({i}) is the shortest
+  // request (earliest arrival among equals) and no scan is needed.  The shortest waiting request is
+  // the last alive position of the sorted set; it is looked up again after it has been taken.
+  const bool tail_rule = !BRH && p.W <= 0 && G > 1;
+  int tail_pos = -1, tail_s = 0;
+  bool tail_dirty = true;
+  auto ensure_tail = [&]() {
+    if (!tail_dirty) return;
+    tail_dirty = false;
+    tail_pos = -1;
+    tail_s = 0;
+#pragma unroll
+    for (int j = E - 1; j >= 0; --j) {
+      if (tail_pos < 0 && j * BR_WAVE < qn) {
+        const unsigned long long bal = br_ballot((alive >> j) & 1u);
+        if (bal != 0ull) {
+          const int l = 63 - (int)__builtin_clzll(bal);
+          tail_pos = j * BR_WAVE + l;
+          tail_s = __builtin_amdgcn_readlane(sv[j], l);
+        }
+      }
+    }
+  };
+  // the earliest arrival among the alive requests of the shortest length
+  auto pick_tail = [&](int &pos, int &swin) {
+    pos = tail_pos;
+#pragma unroll
+    for (int j = E - 1; j >= 0; --j) {
+      if (j * BR_WAVE <= tail_pos) {
+        const unsigned long long c = br_ballot(((alive >> j) & 1u) && sv[j] == tail_s);
+        if (c != 0ull) pos = j * BR_WAVE + (int)__builtin_ctzll(c);
+      }
+    }
+    swin = tail_s;
+  };
+
   // sticky binding of the request at sorted position pos to worker g
   auto bind = [&](int pos, int g, int slot) {
     adm[pos] = (g << 16) | slot;  // every lane stores the same word: no lane masking needed
     const int jw = pos >> 6, lw = pos & 63;
     alive = (lane == lw) ? (alive & ~(1u << jw)) : alive;
+    tail_dirty |= pos == tail_pos;
   };
 
   // load update: the admitted length enters every horizon offset; envelope follows
@@ -299,6 +337,7 @@ __global__ __launch_bounds__(256) void br_k_assign(BrParams p, BrArr a, BrOut o)
         const int jf = pstar >> 6, lf = pstar & 63;
         const unsigned clear = ((1u << jf) - 1u) | ((lane <= lf) ? (1u << jf) : 0u);
         alive &= ~clear;
+        tail_dirty |= pstar >= tail_pos;
         S_tot -= k0;
         n_alive -= k0;
         admitted += k0;
@@ -313,7 +352,88 @@ __global__ __launch_bounds__(256) void br_k_assign(BrParams p, BrArr a, BrOut o)
         margins_of(g, Lg, mg);
         const int room = p.W > 0 ? p.W - Lg[0] : INT32_MAX;
         int pos = 0, swin = 0;
-        if (!pick_single(mg, room, pos, swin)) {
+        bool found = false;
+        if constexpr (!BRH) {
+          if (tail_rule) {
+            ensure_tail();
+            if (tail_s >= mg[0]) {
+              // No waiting request is shorter than this worker's margin.  It takes the shortest one and
+              // the envelope becomes its new load; the next worker of the level is at least as loaded,
+              // so its margin is at most that length and the same holds for it: the rest of the level
+              // takes the waiting requests in order of (length, arrival), one each.
+              const int K = min(level - r, min(S_tot - p.S_greedy, n_alive));
+              if (K >= 3) {
+                // the 64 shortest alive requests, shortest first (position descending), through LDS
+                int base = 0;
+#pragma unroll
+                for (int j = E - 1; j >= 0; --j) {
+                  if (base < BR_WAVE && j * BR_WAVE < qn) {
+                    const bool al = (alive >> j) & 1u;
+                    const unsigned long long bal = br_ballot(al);
+                    const int cj = __builtin_popcountll(bal);
+                    const int rr = base + cj - 1 - br_rank_below(bal);
+                    if (al && rr < BR_WAVE) slots[rr] = (sv[j] << BR_IDX_BITS) | (j * BR_WAVE + lane);
+                    base += cj;
+                  }
+                }
+                br_wave_sync();
+                const int nA = min(n_alive, BR_WAVE);
+                const bool valid = lane < nA;
+                const int e = slots[lane];
+                const int eprev = slots[max(lane - 1, 0)], enext = slots[min(lane + 1, BR_WAVE - 1)];
+                const int st = e >> BR_IDX_BITS;
+                // requests of equal length are contiguous; within such a group the order of admission
+                // is by position ascending, the reverse of the order they were gathered in
+                const bool gs = valid && (lane == 0 || (eprev >> BR_IDX_BITS) != st);
+                const bool ge = valid && (lane == nA - 1 || (enext >> BR_IDX_BITS) != st);
+                const unsigned long long sm = br_ballot(gs), em = br_ballot(ge);
+                int T = BR_WAVE, ga = BR_WAVE;
+                if (valid) {
+                  ga = 63 - (int)__builtin_clzll(sm & ((2ull << lane) - 1ull));
+                  const int gb = lane + (int)__builtin_ctzll(em >> lane);
+                  T = ga + gb - lane;
+                }
+                // a group cut by the edge of the 64 gathered requests has an unknown order here
+                const bool cut = n_alive > BR_WAVE && __builtin_amdgcn_readlane(ga, BR_WAVE - 1) < K;
+                if (!cut) {
+                  br_wave_sync();  // every lane holds its entry; the array is refilled in admission order
+                  if (T < K) slots[T] = e;
+                  br_wave_sync();
+                  const bool cand = member && rank >= r && rank < r + K;
+                  const int mine = cand ? slots[cand ? rank - r : 0] : 0;
+                  const int s_k = mine >> BR_IDX_BITS, pos_k = mine & IDX_MASK;
+                  if (cand) adm[pos_k] = (lane << 16) | nn;
+                  Lh[0] += cand ? s_k : 0;
+                  nn += cand ? 1 : 0;
+                  cap -= cand ? 1 : 0;
+                  // taken: every alive request shorter than the K-th one, and of its length those up to it
+                  const int tK = (int)__builtin_ctzll(br_ballot(T == K - 1));
+                  const int eK = __builtin_amdgcn_readlane(e, tK);
+                  const int vK = eK >> BR_IDX_BITS, pK = eK & IDX_MASK;
+                  const int pend = __builtin_amdgcn_readlane(e, __builtin_amdgcn_readlane(ga, tK)) & IDX_MASK;
+#pragma unroll
+                  for (int j = 0; j < E; ++j) {
+                    const int pp = j * BR_WAVE + lane;
+                    const bool taken = pp > pend || (sv[j] == vK && pp <= pK);
+                    alive &= ~((taken ? 1u : 0u) << j);
+                  }
+                  Mh[0] = br_wave_max(Lh[0]);
+                  S_tot -= K;
+                  n_alive -= K;
+                  admitted += K;
+                  stage1 += K;
+                  tail_dirty = true;
+                  br_wave_sync();
+                  r += K - 1;
+                  continue;
+                }
+              }
+              pick_tail(pos, swin);
+              found = true;
+            }
+          }
+        }
+        if (!found && !pick_single(mg, room, pos, swin)) {
           drop_worker(g, capmax);
           continue;
         }
@@ -420,7 +540,17 @@ __global__ __launch_bounds__(256) void br_k_assign(BrParams p, BrArr a, BrOut o)
       if (bestmask == 0 || bestkey <= 0) {  // starvation guard: the single best request anyway
         ++guard;
         int pos = 0, swin = 0;
-        if (!pick_single(mg, room, pos, swin)) {
+        bool found = false;
+        if constexpr (!BRH) {
+          if (tail_rule) {
+            ensure_tail();
+            if (tail_s >= mg[0]) {
+              pick_tail(pos, swin);
+              found = true;
+            }
+          }
+        }
+        if (!found && !pick_single(mg, room, pos, swin)) {
           drop_worker(g, capmax);
           continue;
         }
@@ -441,6 +571,7 @@ __global__ __launch_bounds__(256) void br_k_assign(BrParams p, BrArr a, BrOut o)
           if ((bestmask >> b) & 1) {
             const int pb = wv[b] & IDX_MASK;
             alive = (lane == (pb & 63)) ? (alive & ~(1u << (pb >> 6))) : alive;
+            tail_dirty |= pb == tail_pos;
             delta += ws[b];
           }
         add_load(g, Lg, br_uniform(delta), __builtin_popcount(bestmask));
