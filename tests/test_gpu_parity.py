@@ -96,6 +96,45 @@ def test_many_small_clusters(G, B, Q, H, extra):
     r.close()
 
 
+@pytest.mark.parametrize("G,B,Q,n0,lengths", [
+    (16, 40, 256, 20, (50, 90)),        # ~6 requests per length: groups inside the 64 shortest
+    (16, 40, 256, 20, (500, 503)),      # 3 lengths, ~85 each: groups wider than 64
+    (16, 40, 256, 20, (16, 4000)),      # mostly distinct
+    (64, 12, 700, 4, (100, 140)),       # 11 registers of keys per lane, wide level
+    (5, 70, 512, 10, (30, 33)),
+    (2, 200, 300, 50, (7, 9)),
+])
+def test_balanced_clusters_equal_lengths(G, B, Q, n0, lengths):
+    """BR-0 clusters whose workers carry equal (or nearly equal) loads, so that no waiting request is
+    below a margin and the shortest-request rule decides nearly every admission, with many requests of
+    equal length (order of admission among equals: arrival order)."""
+    N = 12
+    rng = np.random.default_rng(G * 1000 + Q + lengths[0])
+    cfg = wl.RouteConfig(name="balanced", n_inst=N, G=G, B=B, max_wait=Q, H=0)
+    n = np.full((N, G), n0, np.int32)
+    kv = np.zeros((N, G, B), np.int32)
+    rem = np.zeros((N, G, B), np.int32)
+    kv[:, :, :n0] = 1000
+    kv[N // 2:, :, 0] += rng.integers(0, 3 * lengths[0], size=(N - N // 2, G)).astype(np.int32)  # second half: small spread
+    rem[:, :, :n0] = rng.integers(1, 6, size=(N, G, n0))
+    init = wl.InitState(n=n, kv=kv, rem=rem, pred=None)
+    _say(f"balanced clusters G={G} B={B} Q={Q} lengths={lengths}")
+    oc, r = br_oracle.OracleCluster(cfg, init), binding.Router(cfg, init)
+    for rnd in range(4):
+        cnt = rng.integers(Q // 2, Q + 1, size=N).astype(np.int32)
+        s = rng.integers(lengths[0], lengths[1], size=(N, Q)).astype(np.int32)
+        o = rng.integers(1, 5, size=(N, Q)).astype(np.int32)
+        arr = wl.Arrivals(count=cnt, s=s, o=o, id=np.arange(N * Q, dtype=np.int32).reshape(N, Q) + rnd * N * Q, pred=None)
+        ref = oc.route_step(arr)
+        out = r.route_step(arr, advance=rnd % 2)
+        compare_outputs(ref, out, cfg, f"balanced r{rnd}")
+        oc.advance(1)
+        if rnd % 2 == 0:
+            r.advance(1)
+        compare_state(oc, r.state(), cfg, f"balanced r{rnd}")
+    r.close()
+
+
 def test_edge_cases():
     # no arrivals at all (NULL), empty queue
     cfg, init, arr = wl.random_case(5, N=3, G=4, B=8, max_wait=32, H=0)
