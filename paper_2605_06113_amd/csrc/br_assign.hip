@@ -285,6 +285,76 @@ __global__ __launch_bounds__(256) void br_k_assign(BrParams p, BrArr a, BrOut o)
     ++wdrop;
   };
 
+  // Admission of the K shortest waiting requests, in order of (length, arrival), to the workers with
+  // `member` set and rank r0 .. r0+K-1 (one each; ranks order the members by load, then index).
+  // `smax` >= 0 limits K to the requests no longer than smax.  Returns the number admitted, or 0
+  // when the order cannot be read off the 64 shortest requests (a run of equal lengths crossing
+  // that edge).  Loads, free slots, the envelope and the alive set are updated; counters are the
+  // caller's.
+  auto tail_bulk = [&](bool member, int rank, int r0, int K, int smax) -> int {
+    int base = 0;
+#pragma unroll
+    for (int j = E - 1; j >= 0; --j) {  // the 64 shortest alive requests, shortest first, through LDS
+      if (base < BR_WAVE && j * BR_WAVE < qn) {
+        const bool al = (alive >> j) & 1u;
+        const unsigned long long bal = br_ballot(al);
+        const int cj = __builtin_popcountll(bal);
+        const int rr = base + cj - 1 - br_rank_below(bal);
+        if (al && rr < BR_WAVE) slots[rr] = (sv[j] << BR_IDX_BITS) | (j * BR_WAVE + lane);
+        base += cj;
+      }
+    }
+    br_wave_sync();
+    const int nA = min(n_alive, BR_WAVE);
+    const bool valid = lane < nA;
+    const int e = slots[lane];
+    const int eprev = slots[max(lane - 1, 0)], enext = slots[min(lane + 1, BR_WAVE - 1)];
+    const int st = e >> BR_IDX_BITS;
+    // requests of equal length are contiguous; within such a run the order of admission is by
+    // position ascending, the reverse of the order they were gathered in
+    const bool gs = valid && (lane == 0 || (eprev >> BR_IDX_BITS) != st);
+    const bool ge = valid && (lane == nA - 1 || (enext >> BR_IDX_BITS) != st);
+    const unsigned long long sm = br_ballot(gs), em = br_ballot(ge);
+    int T = BR_WAVE, ga = BR_WAVE;
+    if (valid) {
+      ga = 63 - (int)__builtin_clzll(sm & ((2ull << lane) - 1ull));
+      const int gb = lane + (int)__builtin_ctzll(em >> lane);
+      T = ga + gb - lane;
+    }
+    if (smax >= 0) K = min(K, (int)__builtin_popcountll(br_ballot(T < K && st <= smax)));  // lengths rise with T
+    br_wave_sync();  // every lane holds its entry; the array is refilled in admission order below
+    if (K <= 0) return 0;
+    // a run cut by the edge of the 64 gathered requests has an unknown order here
+    if (n_alive > BR_WAVE && __builtin_amdgcn_readlane(ga, BR_WAVE - 1) < K) return 0;
+    if (T < K) slots[T] = e;
+    br_wave_sync();
+    const bool cand = member && rank >= r0 && rank < r0 + K;
+    const int mine = slots[cand ? rank - r0 : 0];
+    const int s_k = mine >> BR_IDX_BITS, pos_k = mine & IDX_MASK;
+    if (cand) adm[pos_k] = (lane << 16) | nn;
+    Lh[0] += cand ? s_k : 0;
+    nn += cand ? 1 : 0;
+    cap -= cand ? 1 : 0;
+    // taken: every alive request shorter than the K-th one, and of its length those up to it
+    const int tK = (int)__builtin_ctzll(br_ballot(T == K - 1));
+    const int eK = __builtin_amdgcn_readlane(e, tK);
+    const int vK = eK >> BR_IDX_BITS, pK = eK & IDX_MASK;
+    const int pend = __builtin_amdgcn_readlane(e, __builtin_amdgcn_readlane(ga, tK)) & IDX_MASK;
+#pragma unroll
+    for (int j = 0; j < E; ++j) {
+      const int pp = j * BR_WAVE + lane;
+      const bool taken = pp > pend || (sv[j] == vK && pp <= pK);
+      alive &= ~((taken ? 1u : 0u) << j);
+    }
+    Mh[0] = br_wave_max(Lh[0]);
+    S_tot -= K;
+    n_alive -= K;
+    admitted += K;
+    tail_dirty = true;
+    br_wave_sync();
+    return K;
+  };
+
   if (run) {
     const int bound = qn + G + 1;  // every iteration admits a request or sets a worker aside
 
@@ -363,68 +433,10 @@ __global__ __launch_bounds__(256) void br_k_assign(BrParams p, BrArr a, BrOut o)
               // takes the waiting requests in order of (length, arrival), one each.
               const int K = min(level - r, min(S_tot - p.S_greedy, n_alive));
               if (K >= 3) {
-                // the 64 shortest alive requests, shortest first (position descending), through LDS
-                int base = 0;
-#pragma unroll
-                for (int j = E - 1; j >= 0; --j) {
-                  if (base < BR_WAVE && j * BR_WAVE < qn) {
-                    const bool al = (alive >> j) & 1u;
-                    const unsigned long long bal = br_ballot(al);
-                    const int cj = __builtin_popcountll(bal);
-                    const int rr = base + cj - 1 - br_rank_below(bal);
-                    if (al && rr < BR_WAVE) slots[rr] = (sv[j] << BR_IDX_BITS) | (j * BR_WAVE + lane);
-                    base += cj;
-                  }
-                }
-                br_wave_sync();
-                const int nA = min(n_alive, BR_WAVE);
-                const bool valid = lane < nA;
-                const int e = slots[lane];
-                const int eprev = slots[max(lane - 1, 0)], enext = slots[min(lane + 1, BR_WAVE - 1)];
-                const int st = e >> BR_IDX_BITS;
-                // requests of equal length are contiguous; within such a group the order of admission
-                // is by position ascending, the reverse of the order they were gathered in
-                const bool gs = valid && (lane == 0 || (eprev >> BR_IDX_BITS) != st);
-                const bool ge = valid && (lane == nA - 1 || (enext >> BR_IDX_BITS) != st);
-                const unsigned long long sm = br_ballot(gs), em = br_ballot(ge);
-                int T = BR_WAVE, ga = BR_WAVE;
-                if (valid) {
-                  ga = 63 - (int)__builtin_clzll(sm & ((2ull << lane) - 1ull));
-                  const int gb = lane + (int)__builtin_ctzll(em >> lane);
-                  T = ga + gb - lane;
-                }
-                // a group cut by the edge of the 64 gathered requests has an unknown order here
-                const bool cut = n_alive > BR_WAVE && __builtin_amdgcn_readlane(ga, BR_WAVE - 1) < K;
-                if (!cut) {
-                  br_wave_sync();  // every lane holds its entry; the array is refilled in admission order
-                  if (T < K) slots[T] = e;
-                  br_wave_sync();
-                  const bool cand = member && rank >= r && rank < r + K;
-                  const int mine = cand ? slots[cand ? rank - r : 0] : 0;
-                  const int s_k = mine >> BR_IDX_BITS, pos_k = mine & IDX_MASK;
-                  if (cand) adm[pos_k] = (lane << 16) | nn;
-                  Lh[0] += cand ? s_k : 0;
-                  nn += cand ? 1 : 0;
-                  cap -= cand ? 1 : 0;
-                  // taken: every alive request shorter than the K-th one, and of its length those up to it
-                  const int tK = (int)__builtin_ctzll(br_ballot(T == K - 1));
-                  const int eK = __builtin_amdgcn_readlane(e, tK);
-                  const int vK = eK >> BR_IDX_BITS, pK = eK & IDX_MASK;
-                  const int pend = __builtin_amdgcn_readlane(e, __builtin_amdgcn_readlane(ga, tK)) & IDX_MASK;
-#pragma unroll
-                  for (int j = 0; j < E; ++j) {
-                    const int pp = j * BR_WAVE + lane;
-                    const bool taken = pp > pend || (sv[j] == vK && pp <= pK);
-                    alive &= ~((taken ? 1u : 0u) << j);
-                  }
-                  Mh[0] = br_wave_max(Lh[0]);
-                  S_tot -= K;
-                  n_alive -= K;
-                  admitted += K;
-                  stage1 += K;
-                  tail_dirty = true;
-                  br_wave_sync();
-                  r += K - 1;
+                const int done = tail_bulk(member, rank, r, K, -1);
+                if (done > 0) {
+                  stage1 += done;
+                  r += done - 1;
                   continue;
                 }
               }
@@ -488,6 +500,36 @@ __global__ __launch_bounds__(256) void br_k_assign(BrParams p, BrArr a, BrOut o)
       // subset scores above 0 and the round goes to the starvation guard without the enumeration.
       bool guard_sure = false;
       if constexpr (!BRH) guard_sure = br_score0(G, mg[0], s_last) <= 0;
+      if constexpr (!BRH) {
+        if (guard_sure && tail_rule) {
+          ensure_tail();
+          if (tail_s >= mg[0]) {
+            // This worker takes the shortest waiting request through the guard and the envelope becomes
+            // its new load.  The next pop goes to the next lightest worker that still has this many free
+            // slots; its margin is at most the length just admitted.  While the lengths admitted stay
+            // at or below (G-1)/G of the window's smallest entry, the window is untouched, that entry
+            // still scores <= 0 for every such margin (so the guard fires again) and no waiting request
+            // is below the margin: the pops of this free-slot count follow in one step.
+            const bool member = cap == capmax;
+            const int level = __builtin_popcountll(br_ballot(member));
+            const int K = min(level, n_alive - w);
+            if (K >= 3) {
+              const int wkey = member ? (int)(((unsigned)Lh[0] << 6) | (unsigned)lane) : INT32_MAX;
+              int rank = 0;
+              for (int g0 = 0; g0 < G; g0 += 4) {
+#pragma unroll
+                for (int u = 0; u < 4; ++u) rank += (__builtin_amdgcn_readlane(wkey, g0 + u) < wkey) ? 1 : 0;
+              }
+              const int done = tail_bulk(member, rank, 0, K, (G - 1) * s_last / G);
+              if (done > 0) {
+                pops += done - 1;
+                guard += done;
+                continue;
+              }
+            }
+          }
+        }
+      }
       int wv[8], ws[8];
       int bestmask = 0, bestkey = BR_KEY_NONE;
       if (!guard_sure) {
