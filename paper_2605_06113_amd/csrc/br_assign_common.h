@@ -186,8 +186,11 @@ __device__ __forceinline__ void br_advance_cluster(int inst, int lane, int Lcur,
   const int G = p.G, NC = (p.Bs + BR_WAVE - 1) / BR_WAVE, U = G * NC;
   const int64_t row0 = (int64_t)__builtin_amdgcn_readfirstlane(inst) * G;  // scalar: list bases stay in SGPRs
   int dLw = 0, nw = nn;     // lane g: load change and new length of worker g
-  int kept = 0, dL = 0;     // running state of the list in progress
+  int kept = 0, gone = 0;   // running state of the list in progress: survivors, kv that left
   int gl = 0, cl = 0, gp = 0, cp = 0;  // (list, chunk) cursors of the load and the update pass
+  const int32_t *kl = p.kv + row0 * p.Bs, *rl = p.rem + row0 * p.Bs;  // list the load pass is at
+  int32_t *kw = p.kv + row0 * p.Bs, *rw = p.rem + row0 * p.Bs;        // list the update pass is at
+  float *pw = p.pred + row0 * p.Bs * p.P;
   for (int u0 = 0; u0 < U; u0 += UB) {
     int kv[UB], rem[UB];
 #pragma unroll
@@ -195,50 +198,48 @@ __device__ __forceinline__ void br_advance_cluster(int inst, int lane, int Lcur,
       kv[k] = 0, rem[k] = 0;
       if (gl < G) {
         const int ng = __builtin_amdgcn_readlane(nn, gl);
-        const int j = cl * BR_WAVE + lane;
-        if (j < ng) {
-          const int64_t at = (row0 + gl) * p.Bs + j;
-          kv[k] = p.kv[at];
-          rem[k] = p.rem[at];
+        const unsigned j = (unsigned)(cl * BR_WAVE + lane);
+        if ((int)j < ng) {
+          kv[k] = kl[j];
+          rem[k] = rl[j];
         }
       }
-      if (++cl == NC) cl = 0, ++gl;
+      if (++cl == NC) cl = 0, ++gl, kl += p.Bs, rl += p.Bs;
     }
 #pragma unroll
     for (int k = 0; k < UB; ++k) {
       if (gp < G) {
         const int ng = __builtin_amdgcn_readlane(nn, gp);
-        const int64_t base = (row0 + gp) * p.Bs;
         if (cp * BR_WAVE < ng) {
-          // unused lanes hold kv = rem = 0: they neither stay nor change the load
+          // unused lanes hold kv = rem = 0: they neither stay nor leave
           const bool stay = rem[k] > t;
-          dL += stay ? t : -kv[k];
           const unsigned long long bal = br_ballot(stay);
           const unsigned nj = (unsigned)(kept + br_rank_below(bal));
-          int32_t *const kvl = p.kv + base, *const reml = p.rem + base;
           if (stay) {
-            kvl[nj] = kv[k] + t;
-            reml[nj] = rem[k] - t;
+            kw[nj] = kv[k] + t;
+            rw[nj] = rem[k] - t;
             if constexpr (BRH) {
               const unsigned j = (unsigned)(cp * BR_WAVE + lane);
-              float *const pl = p.pred + base * p.P;
               if (p.pred_mode == 2) {
-                float ch = pl[j * 3], age = pl[j * 3 + 1], since = pl[j * 3 + 2];
+                float ch = pw[j * 3], age = pw[j * 3 + 1], since = pw[j * 3 + 2];
                 br_refresh_update(p, t, ch, age, since);
-                pl[nj * 3] = ch;
-                pl[nj * 3 + 1] = age;
-                pl[nj * 3 + 2] = since;
+                pw[nj * 3] = ch;
+                pw[nj * 3 + 1] = age;
+                pw[nj * 3 + 2] = since;
               } else if (nj != j) {
-                for (int q = 0; q < p.P; ++q) pl[nj * p.P + q] = pl[j * p.P + q];
+                for (int q = 0; q < p.P; ++q) pw[nj * p.P + q] = pw[j * p.P + q];
               }
             }
           }
           kept += __builtin_popcountll(bal);
+          // requests leave rarely: their kv is summed only when some lane has one
+          const bool leave = !stay && kv[k] > 0;
+          if (br_ballot(leave) != 0ull) gone += br_wave_sum(leave ? kv[k] : 0);
         }
         if (++cp == NC) {
-          const int tot = ng > 0 ? br_wave_sum(dL) : 0;
-          if (lane == gp) dLw = tot, nw = kept;
-          kept = 0, dL = 0, cp = 0, ++gp;
+          if (lane == gp) dLw = kept * t - gone, nw = kept;  // survivors gain t tokens each
+          kept = 0, gone = 0, cp = 0, ++gp;
+          kw += p.Bs, rw += p.Bs, pw += (int64_t)p.Bs * p.P;
         }
       }
     }
