@@ -181,7 +181,6 @@ template <int UB, bool BRH>
 __device__ __forceinline__ void br_advance_cluster(int inst, int lane, int Lcur, int nn) {
   const BrParams p = br_late_params();
   const int t = p.adv_t;
-  if (t <= 0) return;
   br_wave_sync();  // the round's own writes into the lists are read back below
   const int G = p.G, NC = (p.Bs + BR_WAVE - 1) / BR_WAVE, U = G * NC;
   const int64_t row0 = (int64_t)__builtin_amdgcn_readfirstlane(inst) * G;  // scalar: list bases stay in SGPRs

@@ -22,6 +22,12 @@
 // Ties: Stage 1 worker (most free slots, then lightest, then lowest index); Stage 2 worker
 // (most free slots, then largest horizon-min margin, then lowest index); equal request scores
 // resolve to the lowest sorted position; equal subset scores to the lowest mask.
+//
+// ADV: the wave goes on to apply the decode steps to the lists of the cluster it has routed
+// (br_route_advance); a separate instantiation, so that the two kinds of launch carry distinct
+// kernel names in profiles.
+#pragma once
+
 #include "br_device.h"
 #include "br_launch.h"
 #include <type_traits>
@@ -34,7 +40,7 @@ struct Log2E {
   static constexpr int v = E == 4 ? 2 : E == 8 ? 3 : E == 16 ? 4 : 5;
 };
 
-template <int E, bool BRH>
+template <int E, bool BRH, bool ADV>
 __global__ __launch_bounds__(256) void br_k_assign(BrParams p, BrArr a, BrOut o) {
   extern __shared__ int lds_all[];
   constexpr int NP = E * BR_WAVE;
@@ -630,32 +636,29 @@ __global__ __launch_bounds__(256) void br_k_assign(BrParams p, BrArr a, BrOut o)
   rc.wdrop = wdrop;
   rc.I_before = I_before;
   br_assign_epilogue<E>(inst, lane, q0, qn, cnt, skey, adm, who, Lh[0], nn, rc, c0);
-  br_advance_cluster<(BRH ? 6 : 24), BRH>(inst, lane, Lh[0], nn);  // BR-H units carry the estimator code: fewer unrolled
+  if constexpr (ADV) br_advance_cluster<(BRH ? 6 : 24), BRH>(inst, lane, Lh[0], nn);  // BR-H units carry the estimator code: fewer unrolled
 }
 
 template <int E, bool BRH>
-static void launch_one(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st) {
+static void br_launch_assign_one(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st) {
   // several single-wave clusters share a block so that the chip's per-CU block slots do not cap residency
   const int wpb = E <= 8 ? 4 : 1;
   const size_t lds = (size_t)wpb * (3 * E * BR_WAVE + BR_WAVE + 8) * sizeof(int);  // skey, adm, who, slots, win per wave
-  hipLaunchKernelGGL((br_k_assign<E, BRH>), dim3((unsigned)((p.N + wpb - 1) / wpb)), dim3(BR_WAVE * wpb), lds, st, p, a, o);
+  const dim3 grid((unsigned)((p.N + wpb - 1) / wpb)), block(BR_WAVE * wpb);
+  if (p.adv_t > 0)
+    hipLaunchKernelGGL((br_k_assign<E, BRH, true>), grid, block, lds, st, p, a, o);
+  else
+    hipLaunchKernelGGL((br_k_assign<E, BRH, false>), grid, block, lds, st, p, a, o);
 }
 
 template <bool BRH>
-static void launch_e(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st) {
+static void br_launch_assign_sized(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st) {
   if (p.Q <= 256)
-    launch_one<4, BRH>(p, a, o, st);
+    br_launch_assign_one<4, BRH>(p, a, o, st);
   else if (p.Q <= 512)
-    launch_one<8, BRH>(p, a, o, st);
+    br_launch_assign_one<8, BRH>(p, a, o, st);
   else if (p.Q <= 1024)
-    launch_one<16, BRH>(p, a, o, st);
+    br_launch_assign_one<16, BRH>(p, a, o, st);
   else
-    launch_one<32, BRH>(p, a, o, st);
-}
-
-void br_launch_assign(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st) {
-  if (p.H > 0)
-    launch_e<true>(p, a, o, st);
-  else
-    launch_e<false>(p, a, o, st);
+    br_launch_assign_one<32, BRH>(p, a, o, st);
 }

@@ -1,5 +1,5 @@
 // gfx950 kernels of the BalanceRoute route step, except the sequential assignment
-// (br_assign.hip): state initialisation, decode step, horizon projection, and the
+// (br_assign_kernel.h): state initialisation, decode step, horizon projection, and the
 // F-score matrix with its stage-one reductions.
 #include "br_device.h"
 #include "br_launch.h"

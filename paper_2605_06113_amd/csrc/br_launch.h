@@ -12,4 +12,5 @@ void br_launch_advance(const BrParams &p, int t, hipStream_t st);
 void br_launch_project(const BrParams &p, hipStream_t st);
 void br_launch_score(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st);
 void br_launch_assign(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st);
+void br_launch_assign_br0(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st);
 void br_launch_bypass(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st);
