@@ -29,8 +29,9 @@ HBM_PEAK_GBS = 8000.0
 ALU_INT_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 # HBM KiB per launch on this workload from rocprofv3 --pmc (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, see
 # profiles/bench_c4_kernels.md); an entry is None when its kernel changed after the counters were taken
-TRAFFIC_KIB = {"assign": 2.0 * 6694.0 + 17488.0, "advance": 2.0 * 37450.3 + 74669.5,
-               "score": 2.0 * 2858.2 + 4352.0}
+TRAFFIC_KIB = {"assign+advance": 2.0 * 43703.9 + 90895.4,   # br_k_assign<4,false,true>: round + decode step
+               "assign": 2.0 * 6747.5 + 17454.7, "advance": 2.0 * 37554.8 + 74417.2,
+               "score": 2.0 * 2460.3 + 4352.0}
 
 
 def cpu_baseline(cfg, init, arr, min_seconds=10.0):
