@@ -67,7 +67,9 @@ _lib = None
 def lib():
     global _lib
     if _lib is None:
-        _lib = C.CDLL(build())
+        # BR_ORACLE_LIB: a build of this oracle to load instead (the mutation test points it at copies of
+        # br_oracle.c with one planted mistake each, to show that the pins notice)
+        _lib = C.CDLL(os.environ.get("BR_ORACLE_LIB") or build())
         _lib.orc_score_br0.restype = C.c_int64
         _lib.orc_score_br0.argtypes = [C.c_int64, C.c_int64, C.c_int64]
         _lib.orc_score_brh.restype = C.c_float

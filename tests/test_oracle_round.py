@@ -366,3 +366,59 @@ def test_projection_informative_hazards_cut(orc):
     pr = _mk(orc, cfg, st).project()
     assert pr["chat"][0, 0].tolist() == [2.0, 4.0]
     assert pr["Lh"][0, 0].tolist() == [300, 302, 304, 203, 204]
+
+
+# ---- the loop bounds and tie rules taken where the paper leaves them open, each on a hand-worked case ----
+
+def test_stage1_runs_only_while_free_slots_exceed_threshold(orc):
+    # Alg. BR-0: the greedy stage runs while S_tot > S_greedy (strictly).  One worker with three free
+    # slots, S_greedy = 2, three waiting: one greedy admission (3 > 2), then the refined stage (2 > 2 fails).
+    cfg = wl.RouteConfig(name="thr", n_inst=1, G=1, B=3, max_wait=8, R_max=1, S_greedy=2)
+    oc = _mk(orc, cfg, _init([0], [[]], 3))
+    st = oc.route_step(_arr([5, 4, 3]))["stats"][0]
+    assert st[orc.ST["admitted"]] == 3 and st[orc.ST["stage1"]] == 1 and st[orc.ST["stage2_pops"]] == 2
+
+
+def test_equal_subset_scores_resolve_to_lowest_mask(orc):
+    # window (4, 4), one free slot, margin 100: masks 0b01 and 0b10 both score 4 -> 0b01
+    P = orc.params_from(wl.RouteConfig(name="t2", n_inst=1, G=2, B=4, max_wait=8, R_max=2))
+    assert orc.best_subset(P, [100], 0, 1, [4, 4]) == (1, 4.0)
+    # window (8, 4, 4), two free slots, margin 8, G = 2: {8} scores 8, {4,4} scores 8, {8,4} 12-2*4=4 -> {8}
+    P3 = orc.params_from(wl.RouteConfig(name="t2", n_inst=1, G=2, B=4, max_wait=8, R_max=3))
+    assert orc.best_subset(P3, [8], 0, 2, [8, 4, 4]) == (1, 8.0)
+
+
+def test_equal_single_scores_resolve_to_lowest_sorted_position(orc):
+    # one worker slot to fill in the greedy stage (S_greedy = 0).
+    # (a) equal lengths: the earlier arrival goes first
+    cfg = wl.RouteConfig(name="t3", n_inst=1, G=2, B=1, max_wait=8, R_max=1, S_greedy=0)
+    oc = _mk(orc, cfg, _init([0, 1], [[], [50]], 1))
+    out = oc.route_step(_arr([7, 7, 7], ids=[11, 12, 13]))
+    assert out["assign"][0, :3].tolist() == [0, -1, -1]
+    # (b) equal scores of different lengths: worker 0 has margin 6 against worker 1's load; with G = 2,
+    # s = 4 scores 4 and s = 8 scores 8 - 2*2 = 4: the longer request is first in the sorted order
+    oc = _mk(orc, cfg, _init([0, 1], [[], [6]], 1))
+    out = oc.route_step(_arr([4, 8], ids=[21, 22]))
+    assert out["assign"][0, :2].tolist() == [-1, 0]
+
+
+def test_admitted_load_enters_every_horizon_offset(orc):
+    # BR-H, H = 1, gamma = 0.5, (alpha, beta) = (1, G = 2): d = (1, 0.5), alpha*D = 1.5; greedy stage only.
+    # Two empty workers with one slot each, waiting (10, 12).  Worker 0 (lowest index) has margins (0, 0):
+    # 12 scores 18 - 2*(12 + 6) = -18, 10 scores 15 - 2*(10 + 5) = -15 -> takes 10.  The 10 tokens count at
+    # offsets 0 and 1: envelope (10, 10), worker 1 has margins (10, 10) and 12 scores 18 - 2*(2 + 1) = 12.
+    # (Were the admitted load added at offset 0 only, the margin at offset 1 would be 0 and the score 2.)
+    kw = dict(n_inst=1, G=2, max_wait=8, H=1, R_max=1, S_greedy=0, gamma=0.5, alpha=1.0, beta=2.0, pred_mode=1)
+    oc = _mk(orc, wl.RouteConfig(name="a8", B=1, **kw), _init([0, 0], [[], []], 1))
+    out = oc.route_step(_arr([10, 12], pred=np.ones((1, 2, 1), np.float32)), want_events=True)
+    ev = out["events"][0][:out["n_events"][0]]
+    assert [(int(e["g"]), int(e["delta"]), float(e["score"])) for e in ev] == [(0, 10, -15.0), (1, 12, 12.0)]
+    # Two slots each, waiting (10, 12, 5, 4).  Worker 0, margins (0, 0): 4 scores 6 - 12 = -6, the best -> loads
+    # (4, 0).  Worker 1 (two free slots), margins (4, 4): 12 -> -6, 10 -> -3, 5 -> 7.5 - 2*(1 + 0.5) = 4.5 ->
+    # takes 5; loads (4, 5), envelope (5, 5).  One slot each: lighter worker 0, margins (1, 1): 12 -> -15,
+    # 10 -> 15 - 2*(9 + 4.5) = -12 -> takes 10; envelope (14, 14).  Worker 1, margins (9, 9): 12 -> 18 - 2*4.5 = 9.
+    oc = _mk(orc, wl.RouteConfig(name="a8b", B=2, **kw), _init([0, 0], [[], []], 2))
+    out = oc.route_step(_arr([10, 12, 5, 4], pred=np.ones((1, 4, 1), np.float32)), want_events=True)
+    ev = out["events"][0][:out["n_events"][0]]
+    assert [(int(e["g"]), int(e["delta"]), float(e["score"])) for e in ev] == \
+        [(0, 4, -6.0), (1, 5, 4.5), (0, 10, -12.0), (1, 12, 9.0)]
