@@ -92,36 +92,57 @@ __device__ __forceinline__ void br_assign_epilogue(int inst, int lane, int q0, i
   }
   br_wave_sync();
 
-  // ---- outputs in arrival order; the queue keeps the deferred requests, order preserved
+  // ---- outputs in arrival order; the queue keeps the deferred requests, order preserved.
+  // Blocks of 64 entries are taken GR at a time: everything the group reads is requested before its
+  // first store, so the loads of a group overlap (a 2048-entry queue is 32 blocks, each a round trip to
+  // memory otherwise).  In place: a deferred entry moves to a position at or below its own, inside or
+  // before its group, and later groups read only beyond it.
+  constexpr int GR = E < 4 ? E : 4;
   int kept = 0;
 #pragma unroll
-  for (int j = 0; j < E; ++j) {
-    const int i = j * BR_WAVE + lane;
-    if (j * BR_WAVE < t.Q) {
-      const bool in = i < qn;
-      const int wg = in ? who[i] : -1;
-      const bool old = i < q0;
-      int id = -1;
-      if (in) id = old ? t.qid[qrow + i] : (t.aid ? t.aid[arow + (i - q0)] : i - q0);
-      if (i < t.Q) {
-        if (t.assign) t.assign[qrow + i] = wg;
-        if (t.assign_id) t.assign_id[qrow + i] = id;
+  for (int j0 = 0; j0 < E; j0 += GR) {
+    if (j0 * BR_WAVE < t.Q) {
+      int wg[GR], id[GR], sq[GR], oq[GR];
+      float pr[GR][BR_HP];
+      bool keep[GR];
+#pragma unroll
+      for (int u = 0; u < GR; ++u) {
+        const int i = (j0 + u) * BR_WAVE + lane;
+        const bool in = i < qn, old = i < q0;
+        wg[u] = in ? who[i] : -1;
+        id[u] = -1;
+        if (in) id[u] = old ? t.qid[qrow + i] : (t.aid ? t.aid[arow + (i - q0)] : i - q0);
+        keep[u] = in && wg[u] < 0;
+        sq[u] = 1, oq[u] = 1;
+        if (keep[u]) {
+          sq[u] = old ? t.qs[qrow + i] : t.as[arow + (i - q0)];
+          oq[u] = old ? t.qo[qrow + i] : t.ao[arow + (i - q0)];
+#pragma unroll
+          for (int q = 0; q < BR_HP; ++q)
+            if (q < t.Pq) pr[u][q] = old ? t.qpred[(qrow + i) * t.Pq + q] : t.apred[(arow + (i - q0)) * t.Pq + q];
+        }
       }
-      const bool keep = in && wg < 0;
-      const unsigned long long bal = br_ballot(keep);
-      const int ni = kept + br_rank_below(bal);
-      if (keep && (ni != i || !old)) {
-        int s = old ? t.qs[qrow + i] : t.as[arow + (i - q0)];
-        s = min(max(s, 1), BR_MAX_S_DEV);
-        const int oo = old ? t.qo[qrow + i] : max(t.ao[arow + (i - q0)], 1);
-        float pr[BR_HP];
-        for (int q = 0; q < t.Pq; ++q) pr[q] = old ? t.qpred[(qrow + i) * t.Pq + q] : t.apred[(arow + (i - q0)) * t.Pq + q];
-        t.qs[qrow + ni] = s;
-        t.qo[qrow + ni] = oo;
-        t.qid[qrow + ni] = id;
-        for (int q = 0; q < t.Pq; ++q) t.qpred[(qrow + ni) * t.Pq + q] = pr[q];
+#pragma unroll
+      for (int u = 0; u < GR; ++u) {
+        const int i = (j0 + u) * BR_WAVE + lane;
+        if ((j0 + u) * BR_WAVE < t.Q) {
+          if (i < t.Q) {
+            if (t.assign) t.assign[qrow + i] = wg[u];
+            if (t.assign_id) t.assign_id[qrow + i] = id[u];
+          }
+          const unsigned long long bal = br_ballot(keep[u]);
+          const int ni = kept + br_rank_below(bal);
+          if (keep[u] && (ni != i || i >= q0)) {
+            t.qs[qrow + ni] = min(max(sq[u], 1), BR_MAX_S_DEV);
+            t.qo[qrow + ni] = max(oq[u], 1);
+            t.qid[qrow + ni] = id[u];
+#pragma unroll
+            for (int q = 0; q < BR_HP; ++q)
+              if (q < t.Pq) t.qpred[(qrow + ni) * t.Pq + q] = pr[u][q];
+          }
+          kept += __builtin_popcountll(bal);
+        }
       }
-      kept += __builtin_popcountll(bal);
     }
   }
 

@@ -139,8 +139,13 @@ __device__ __forceinline__ int br_score0(int G, int m, int delta) {
 __device__ __forceinline__ float br_scoreh(const BrParams &p, const int (&m)[BR_HP + 1], int delta) {
   float pen = 0.0f;
 #pragma unroll
-  for (int h = 0; h <= BR_HP; ++h)
+  for (int h = 0; h <= BR_HP / 2; ++h)
     pen = __fadd_rn(pen, __fmul_rn(p.d[h], (float)max(delta - m[h], 0)));
+  if (p.H > BR_HP / 2) {  // short horizons: the remaining terms are +0 and leave the sum as it is
+#pragma unroll
+    for (int h = BR_HP / 2 + 1; h <= BR_HP; ++h)
+      pen = __fadd_rn(pen, __fmul_rn(p.d[h], (float)max(delta - m[h], 0)));
+  }
   return __fsub_rn(__fmul_rn(p.aD, (float)delta), __fmul_rn(p.beta, pen));
 }
 

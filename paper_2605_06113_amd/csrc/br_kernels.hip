@@ -206,7 +206,10 @@ __global__ __launch_bounds__(512) void br_k_score(BrParams p, BrArr a, BrOut o, 
   int *ss = scap + G;                    // [Q] prefill lengths of the waiting set
   int *cand = ss + p.Q;                  // [3][blockDim] candidates of pass B
   int *tiles = cand + 3 * blockDim.x;    // [waves][64][G+1] when the matrix is written out
-  const int inst = blockIdx.x;
+  // a cluster may be spread over gridDim.y blocks: block `split` scores its share of the requests
+  // against all workers (pass A) and all requests against its share of the workers (pass B), so no
+  // result needs combining across blocks
+  const int inst = blockIdx.x, split = blockIdx.y, nsplit = gridDim.y;
   const int tid = threadIdx.x, lane = br_lane(), wave = tid >> 6, nw = blockDim.x >> 6;
 
   const int q0 = min(max(p.qlen[inst], 0), p.Q);
@@ -238,7 +241,7 @@ __global__ __launch_bounds__(512) void br_k_score(BrParams p, BrArr a, BrOut o, 
 
   // pass A: one request per lane, loop over workers
   int *tile = tiles + wave * (BR_WAVE * (G + 1));
-  for (int t0 = wave * BR_WAVE; t0 < qn; t0 += nw * BR_WAVE) {
+  for (int t0 = (split * nw + wave) * BR_WAVE; t0 < qn; t0 += nsplit * nw * BR_WAVE) {
     const int i = t0 + lane;
     const bool valid = i < qn;
     const int s = valid ? ss[i] : 1;
@@ -266,16 +269,17 @@ __global__ __launch_bounds__(512) void br_k_score(BrParams p, BrArr a, BrOut o, 
       }
     }
   }
-  if (o.best_g)
+  if (o.best_g && split == 0)
     for (int i = qn + tid; i < p.Q; i += blockDim.x) o.best_g[(int64_t)inst * p.Q + i] = -1;
 
-  // pass B: lane = (sub-slot, worker); running best request per worker
+  // pass B: lane = (sub-slot, worker of this block's share); running best request per worker
   if (o.best_i) {
+    const int Gs = (G + nsplit - 1) / nsplit, gbase = split * Gs;  // workers [gbase, gbase + Gs)
     int Gp = 1;
-    while (Gp < G) Gp <<= 1;
+    while (Gp < Gs) Gp <<= 1;
     const int nsub = BR_WAVE / Gp;
-    const int sub = lane / Gp, g = lane - sub * Gp;
-    const bool act = g < G;
+    const int sub = lane / Gp, gl = lane - sub * Gp, g = gbase + gl;
+    const bool act = gl < Gs && g < G;
     int m[BR_HP + 1];
 #pragma unroll
     for (int h = 0; h <= BR_HP; ++h) m[h] = (act && (BRH || h == 0)) ? sm[g * (BR_HP + 1) + h] : 0;
@@ -296,7 +300,7 @@ __global__ __launch_bounds__(512) void br_k_score(BrParams p, BrArr a, BrOut o, 
     cand[blockDim.x + tid] = bs;
     cand[2 * blockDim.x + tid] = bi;
     __syncthreads();
-    if (tid < G) {
+    if (tid < Gs && gbase + tid < G) {
       bk = BR_KEY_NONE, bs = 0, bi = -1;
       for (int w = 0; w < nw; ++w)
         for (int sb = 0; sb < nsub; ++sb) {
@@ -309,7 +313,7 @@ __global__ __launch_bounds__(512) void br_k_score(BrParams p, BrArr a, BrOut o, 
             bi = i;
           }
         }
-      o.best_i[(int64_t)inst * G + tid] = bi;
+      o.best_i[(int64_t)inst * G + gbase + tid] = bi;
     }
   }
 }
@@ -483,8 +487,12 @@ void br_launch_score(const BrParams &p, const BrArr &a, const BrOut &o, hipStrea
   };
   while (waves > 1 && lds_words(waves) * 4 > 60 * 1024) --waves;  // stay within the default 64 KiB of LDS per block
   const size_t lds = lds_words(waves) * 4;
+  // few clusters: spread each over several blocks (at most 8, at most one per worker) to fill more CUs
+  int nsplit = 1;
+  while (nsplit < 8 && nsplit * 2 <= p.G && (int64_t)p.N * nsplit * 2 <= 512 && p.Q > 64 * waves * nsplit) nsplit *= 2;
+  const dim3 grid((unsigned)p.N, (unsigned)nsplit);
   if (p.H > 0)
-    hipLaunchKernelGGL(br_k_score<true>, dim3((unsigned)p.N), dim3(64 * waves), lds, st, p, a, o, want_tile);
+    hipLaunchKernelGGL(br_k_score<true>, grid, dim3(64 * waves), lds, st, p, a, o, want_tile);
   else
-    hipLaunchKernelGGL(br_k_score<false>, dim3((unsigned)p.N), dim3(64 * waves), lds, st, p, a, o, want_tile);
+    hipLaunchKernelGGL(br_k_score<false>, grid, dim3(64 * waves), lds, st, p, a, o, want_tile);
 }
