@@ -60,7 +60,7 @@ def latency_run(steps, device):
     """Single-instance BR-H stress shape (G=64, H=8, queue cap 2048): host wall-clock per round."""
     import torch
     from paper_2605_06113_amd import binding, workloads as wl
-    cfg = wl.config("c5", gate_pfin=0.0)
+    cfg = wl.config("c5")   # the paper's p_fin gate at its default
     tr = wl.arrival_trace(cfg, steps)
     r = binding.Router(cfg, None, device=device)
     P = r.P
@@ -99,7 +99,7 @@ def brh_run(device, steps=6, warmup=2):
     1024 clusters of the c3 shape (G=32, B=96, H=4), 76 active requests per worker, 256 waiting."""
     import torch
     from paper_2605_06113_amd import binding, workloads as wl
-    cfg = wl.config("c3", n_inst=1024, gate_pfin=0.0, token_watermark=0, token_cap=0, init_active_per_worker=76, init_kv_lo=256, init_kv_hi=8192,
+    cfg = wl.config("c3", n_inst=1024, token_watermark=0, token_cap=0, init_active_per_worker=76, init_kv_lo=256, init_kv_hi=8192,
                     init_rem_lo=1, init_rem_hi=1024, init_waiting=256)
     init, arr = wl.initial_state(cfg), wl.initial_waiting(cfg)
     routers = [binding.Router(cfg, init, device=device) for _ in range(steps + warmup)]

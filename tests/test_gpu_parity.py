@@ -231,7 +231,7 @@ def test_c4_full_size_bench_configuration(fused):
     r.close()
 
 
-@pytest.mark.parametrize("name,over", [("c2", {}), ("c3", dict(gate_pfin=0.5)), ("c5", dict(gate_pfin=0.0))])
+@pytest.mark.parametrize("name,over", [("c2", {}), ("c3", dict(gate_pfin=0.5)), ("c5", {})])
 def test_replay_full_length(name, over):
     """The replay workloads at their full length (2000 / 1000 / 10000 decode steps): assignments and
     statistics of every step, the whole state every 250 steps."""
@@ -257,9 +257,12 @@ def test_replay_full_length(name, over):
     r.close()
 
 
-def test_brh_batched_bench_configuration():
-    """The batched BR-H side workload of bench.py at full size (1024 clusters), every instance."""
-    cfg = wl.config("c3", n_inst=1024, gate_pfin=0.0, token_watermark=0, token_cap=0, init_active_per_worker=76,
+@pytest.mark.parametrize("gate", [None, 0.0])
+def test_brh_batched_bench_configuration(gate):
+    """The batched BR-H side workload of bench.py at full size (1024 clusters), every instance; also with
+    the p_fin gate off (then no request counts at the last offset and every score is negative)."""
+    over = {} if gate is None else dict(gate_pfin=gate)
+    cfg = wl.config("c3", n_inst=1024, token_watermark=0, **over, token_cap=0, init_active_per_worker=76,
                     init_kv_lo=256, init_kv_hi=8192, init_rem_lo=1, init_rem_hi=1024, init_waiting=256)
     _say("brh batched full size")
     init, arr = wl.initial_state(cfg), wl.initial_waiting(cfg)
