@@ -135,6 +135,52 @@ def test_balanced_clusters_equal_lengths(G, B, Q, n0, lengths):
     r.close()
 
 
+@pytest.mark.parametrize("seed", [11, 12])
+def test_random_shapes_equal_lengths_and_loads(seed):
+    """Many small BR-0 shapes drawn at random, built to produce ties: few distinct request lengths,
+    equal or nearly equal worker loads, thresholds from "refined stage only" to "greedy stage only".
+    This is where the admission shortcuts of the assignment kernel must still follow the one-by-one loop."""
+    rng = np.random.default_rng(seed)
+    for case in range(60):
+        G = int(rng.choice([2, 3, 5, 8, 16, 16, 31, 64]))
+        Q = int(rng.choice([64, 100, 256, 256, 300, 512, 700, 1024, 2048]))
+        B = int(rng.integers(2, 60))
+        N = int(rng.choice([7, 64, 300])) if Q < 1024 else 8
+        R_max = int(rng.choice([1, 2, 4, 4, 4, 6, 8]))
+        S_greedy = int(rng.choice([0, G, G * R_max, G * R_max, 3 * G * R_max, 10 ** 6]))
+        n0 = int(rng.integers(0, B))
+        spread = int(rng.choice([0, 0, 5, 50, 500, 5000, 50000]))
+        lo = int(rng.choice([1, 5, 50, 500, 3000]))
+        width = int(rng.choice([1, 2, 3, 10, 100, 1000, 20000]))
+        cfg = wl.RouteConfig(name="shapes", n_inst=N, G=G, B=B, max_wait=Q, H=0, R_max=R_max, S_greedy=S_greedy)
+        n = np.full((N, G), n0, np.int32)
+        n[:, ::3] = rng.integers(0, B + 1, size=n[:, ::3].shape)
+        kv = np.zeros((N, G, B), np.int32)
+        rem = np.zeros((N, G, B), np.int32)
+        used = np.arange(B)[None, None, :] < n[:, :, None]
+        kv[used] = 1000
+        if spread:
+            kv[:, :, 0] += rng.integers(0, spread + 1, size=(N, G)).astype(np.int32) * (n > 0)
+        rem[used] = rng.integers(1, 4, size=int(used.sum()))
+        init = wl.InitState(n=n, kv=kv, rem=rem, pred=None)
+        tag = f"shapes {seed}/{case}: N={N} G={G} B={B} Q={Q} R_max={R_max} S_greedy={S_greedy} n0={n0} spread={spread} s in [{lo},{lo + width})"
+        _say(tag)
+        oc, r = br_oracle.OracleCluster(cfg, init), binding.Router(cfg, init)
+        for rnd in range(3):
+            cnt = rng.integers(0, Q + 1, size=N).astype(np.int32)
+            s = rng.integers(lo, lo + width, size=(N, Q)).astype(np.int32)
+            o = rng.integers(1, 4, size=(N, Q)).astype(np.int32)
+            arr = wl.Arrivals(count=cnt, s=s, o=o, id=np.arange(N * Q, dtype=np.int32).reshape(N, Q), pred=None)
+            ref = oc.route_step(arr, want_scores=False)
+            out = r.route_step(arr, scores=False, advance=rnd % 2)
+            compare_outputs(ref, out, cfg, f"{tag} r{rnd}")
+            oc.advance(1)
+            if rnd % 2 == 0:
+                r.advance(1)
+            compare_state(oc, r.state(), cfg, f"{tag} r{rnd}")
+        r.close()
+
+
 def test_edge_cases():
     # no arrivals at all (NULL), empty queue
     cfg, init, arr = wl.random_case(5, N=3, G=4, B=8, max_wait=32, H=0)
