@@ -8,7 +8,7 @@ B=144, 256 waiting requests and 128 active requests per worker each.  Every time
 its own copy of the cluster state (prepared before the timed region), so all steps do identical
 work on data that is resident in HBM but not warm in cache.
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line.
 """
 from __future__ import annotations
 
@@ -29,8 +29,8 @@ HBM_PEAK_GBS = 8000.0
 ALU_INT_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 # HBM KiB per launch on this workload from rocprofv3 --pmc (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, see
 # profiles/bench_c4_kernels.md); an entry is None when its kernel changed after the counters were taken
-TRAFFIC_KIB = {"assign+advance": 2.0 * 43703.9 + 90895.4,   # br_k_assign<4,false,true>: round + decode step
-               "assign": 2.0 * 6747.5 + 17454.7, "advance": 2.0 * 37554.8 + 74417.2,
+TRAFFIC_KIB = {"assign+advance": 2.0 * 43697.8 + 90711.5,   # br_k_assign<4,false,true>: round + decode step
+               "assign": 2.0 * 6733.0 + 17454.7, "advance": 2.0 * 37555.5 + 74404.5,
                "score": 2.0 * 2460.3 + 4352.0}
 
 
@@ -261,7 +261,7 @@ def main():
     qn = int(stats[:, binding.ST["qlen"]].sum())
     pairs_per_step = qn * cfg.G
 
-    # algorithmic work per launch of each kernel (stated in the design doc)
+    # algorithmic work per launch of each kernel
     N, G, B, Q = cfg.n_inst, cfg.G, cfg.B, cfg.max_wait
     occupied_after = N * G * 128 + admitted          # slots the decode step touches
     bytes_advance = occupied_after * 16 + N * G * 16  # kv, rem read + written; L, n read + written
