@@ -94,12 +94,13 @@ def latency_run(steps, device):
     return res
 
 
-def brh_run(device, steps=6, warmup=2):
+def brh_run(device, steps=6, warmup=2, gate=None):
     """Batched BR-H round (horizon projection + scores + assignment) and decode step:
     1024 clusters of the c3 shape (G=32, B=96, H=4), 76 active requests per worker, 256 waiting."""
     import torch
     from paper_2605_06113_amd import binding, workloads as wl
-    cfg = wl.config("c3", n_inst=1024, token_watermark=0, token_cap=0, init_active_per_worker=76, init_kv_lo=256, init_kv_hi=8192,
+    over = {} if gate is None else dict(gate_pfin=gate)
+    cfg = wl.config("c3", n_inst=1024, **over, token_watermark=0, token_cap=0, init_active_per_worker=76, init_kv_lo=256, init_kv_hi=8192,
                     init_rem_lo=1, init_rem_hi=1024, init_waiting=256)
     init, arr = wl.initial_state(cfg), wl.initial_waiting(cfg)
     routers = [binding.Router(cfg, init, device=device) for _ in range(steps + warmup)]
@@ -132,7 +133,8 @@ def brh_run(device, steps=6, warmup=2):
     active = N * G * 76
     bytes_k = dict(project=active * (4 + 4 * P) + N * G * 4 + N * (H + 1) * 4 * (2 * G + 1) + N * G * 4,
                    advance=(active + admitted) * 16 + N * G * 16)
-    res = dict(workload="1024 clusters of the c3 shape: BR-H H=4, G=32, B=96, 76 active per worker, 256 waiting",
+    res = dict(workload="1024 clusters of the c3 shape: BR-H H=4, G=32, B=96, 76 active per worker, 256 waiting; "
+                        f"p_fin gate {cfg.gate_pfin}",
                ms_per_step=elapsed / steps * 1e3, pairs_per_s=qn * G * steps / elapsed,
                decisions_per_s=admitted * steps / elapsed, kernels={})
     for k, (ms, c) in kern.items():
@@ -143,6 +145,45 @@ def brh_run(device, steps=6, warmup=2):
             gbs = bytes_k[k] / (ms / c * 1e-3) / 1e9
             e.update(bound="hbm", achieved_GBs=gbs, frac=gbs / HBM_PEAK_GBS)
         res["kernels"][k] = e
+    return res
+
+
+def replay_run(device, n_inst=1024, steps=300):
+    """Replayed decode steps, batched: n_inst independent copies (own arrival streams) of the BR-0 replay
+    shape (G=16, B=96, Poisson(40) arrivals per step, queue cap 256), from empty clusters; every step is one
+    br_route_advance (round + decode step in one launch, no score outputs)."""
+    import torch
+    from paper_2605_06113_amd import binding, workloads as wl
+    cfg = wl.config("c2", n_inst=n_inst)
+    tr = wl.arrival_trace(cfg, steps)
+    r = binding.Router(cfg, None, device=device)
+    t = lambda a: torch.as_tensor(np.ascontiguousarray(a, np.int32), device=device)
+    count, s, o, ids = t(tr.count), t(tr.s), t(tr.o), t(tr.id)
+    cap = int(tr.s.shape[-1])
+    out = r.alloc_outputs(scores=False)
+    stats_all = torch.zeros((steps, n_inst, binding.NSTATS), dtype=torch.int64, device=device)  # one row block per step
+    import ctypes as C
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(steps):
+        a = binding.Arrivals(count=count[k].data_ptr(), s=s[k].data_ptr(), o=o[k].data_ptr(), id=ids[k].data_ptr(),
+                             pred=None, arr_cap=cap, pad=0)
+        out["stats"] = stats_all[k]
+        ostruct = r.out_struct(out)
+        rc = r.lib.br_route_advance(r.ctx, C.byref(a), C.byref(ostruct), 1)
+        assert rc == 0
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    st_all = stats_all.cpu().numpy()
+    admitted = int(st_all[:, :, binding.ST["admitted"]].sum())
+    pairs = int(st_all[:, :, binding.ST["qlen"]].sum())
+    st = st_all[-1]
+    res = dict(workload=f"{n_inst} instances of the c2 shape replayed from empty for {steps} decode steps "
+                        "(BR-0, G=16, B=96, Poisson(40) arrivals, queue cap 256), one br_route_advance per step",
+               ms_per_step=elapsed / steps * 1e3, instance_steps_per_s=n_inst * steps / elapsed,
+               decisions_per_s=admitted / elapsed, pairs_per_s=pairs * cfg.G / elapsed,
+               final_mean_queue=float(st[:, binding.ST["deferred"]].mean()))
+    r.close()
     return res
 
 
@@ -183,7 +224,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--latency-steps", type=int, default=1000)
+    ap.add_argument("--latency-steps", type=int, default=10000,
+                    help="decode steps of the single-instance latency replay (the stress shape runs 10000)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--two-calls", action="store_true",
                     help="time br_route_step + br_advance_decode instead of the fused br_route_advance")
@@ -325,7 +367,9 @@ def main():
                                 pairs_per_s=pairs_per_step * K / e2, kernels=kernel_table(k2, False))
     if not args.no_brh:
         res["brh_batched"] = brh_run(device)
+        res["brh_batched_gate_off"] = brh_run(device, gate=0.0)   # hazards live: no request counts at the last offset
         res["bypass"] = bypass_run(device, cfg, init, arr)
+        res["replay_batched"] = replay_run(device)
     if args.latency_steps > 0:
         res["latency"] = latency_run(args.latency_steps, device)
     if not args.no_cpu_baseline:

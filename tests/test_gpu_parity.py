@@ -257,6 +257,29 @@ def test_replay(name, steps, over, fused):
     r.close()
 
 
+def test_batched_replay_fused_steps():
+    """bench.py's replay leg at reduced size: 48 instances of the BR-0 replay shape with their own arrival
+    streams, 160 decode steps from empty, one fused call per step and nothing read back in between."""
+    cfg = wl.config("c2", n_inst=48)
+    steps = 160
+    _say(f"batched replay {cfg.n_inst} x {steps}")
+    tr = wl.arrival_trace(cfg, steps)
+    oc, r = br_oracle.OracleCluster(cfg), binding.Router(cfg)
+    out = r.alloc_outputs(scores=False)
+    refs = []
+    for k in range(steps):
+        a = tr.step(k)
+        r.route_advance_device(binding.DeviceArrivals(a, r.device, r.Pq), out, 1)
+        ref = oc.route_step(a, want_scores=False)
+        oc.advance(1)
+        if k % 40 == 39 or k == steps - 1:
+            r.stream.synchronize()
+            got = {kk: out[kk].cpu().numpy() for kk in ("assign", "assign_id", "stats")}
+            compare_outputs(ref, got, cfg, f"batched replay step {k}")
+            compare_state(oc, r.state(), cfg, f"batched replay step {k}")
+    r.close()
+
+
 @pytest.mark.parametrize("fused", [False, True])
 def test_c4_full_size_bench_configuration(fused):
     """The batched throughput workload at full size, in the launch configurations bench.py times
