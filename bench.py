@@ -227,6 +227,8 @@ def main():
     ap.add_argument("--latency-steps", type=int, default=10000,
                     help="decode steps of the single-instance latency replay (the stress shape runs 10000)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--profile-every", type=int, default=4,
+                    help="bracket the kernels of every n-th timed step with HIP events (per-kernel durations)")
     ap.add_argument("--two-calls", action="store_true",
                     help="time br_route_step + br_advance_decode instead of the fused br_route_advance")
     ap.add_argument("--no-two-calls-leg", action="store_true", help="skip the side measurement of the two-call step")
@@ -264,7 +266,7 @@ def main():
     darr = binding.DeviceArrivals(arr, device, 0)
 
     def timed(fused):
-        """W + K steps, each on its own copy of the cluster state; per-kernel HIP-event times of the K."""
+        """W + K steps, each on its own copy of the cluster state; per-kernel HIP-event times from every n-th of the K."""
         routers = [binding.Router(cfg, init, device=device) for _ in range(K + W)]
         out = routers[0].alloc_outputs(scores=True, matrix=False)
         torch.cuda.synchronize()
@@ -279,8 +281,8 @@ def main():
         for r in routers[:W]:
             step(r)
         torch.cuda.synchronize()
-        for r in routers[W:]:
-            r.profile(True)
+        for r in routers[W::args.profile_every]:
+            r.profile(True)       # HIP-event pairs around every kernel of these steps (each costs ~7 us of stream time)
         t0 = time.perf_counter()
         for r in routers[W:]:
             step(r)
