@@ -191,19 +191,15 @@ __device__ __forceinline__ BrParams br_late_params() {
   return p;
 }
 
-// Decode advance of one cluster by the wave that has just routed it: the arithmetic of the
-// stand-alone advance kernel (Sec. 2.2 load model: a request that stays gains t tokens, one whose
-// remaining output is used up leaves with its whole kv), applied to the cluster's G lists in
-// (list, 64-slot chunk) units.  UB units are requested before the first is used.  Chunks are taken
-// in order and a chunk's survivors move to positions at or below their own, all of which were read
-// by this or an earlier chunk, so the compaction is safe in place.  `Lcur`, `nn`: load and list
-// length of worker `lane` after the round.
+// Decode advance of one cluster by the wave that has just routed it: br_adv_apply (the arithmetic of
+// the stand-alone advance kernel) over the cluster's G lists in (list, 256-slot chunk) units, UB units
+// requested before the first is used.  `Lcur`, `nn`: load and list length of worker `lane` after the round.
 template <int UB, bool BRH>
 __device__ __forceinline__ void br_advance_cluster(int inst, int lane, int Lcur, int nn) {
   const BrParams p = br_late_params();
   const int t = p.adv_t;
   br_wave_sync();  // the round's own writes into the lists are read back below
-  const int G = p.G, NC = (p.Bs + BR_WAVE - 1) / BR_WAVE, U = G * NC;
+  const int G = p.G, NC = (p.Bs + 255) >> 8, U = G * NC;
   const int64_t row0 = (int64_t)__builtin_amdgcn_readfirstlane(inst) * G;  // scalar: list bases stay in SGPRs
   int dLw = 0, nw = nn;     // lane g: load change and new length of worker g
   int kept = 0, gone = 0;   // running state of the list in progress: survivors, kv that left
@@ -212,50 +208,18 @@ __device__ __forceinline__ void br_advance_cluster(int inst, int lane, int Lcur,
   int32_t *kw = p.kv + row0 * p.Bs, *rw = p.rem + row0 * p.Bs;        // list the update pass is at
   float *pw = p.pred + row0 * p.Bs * p.P;
   for (int u0 = 0; u0 < U; u0 += UB) {
-    int kv[UB], rem[UB];
+    int4 kv[UB], rem[UB];
 #pragma unroll
     for (int k = 0; k < UB; ++k) {
-      kv[k] = 0, rem[k] = 0;
-      if (gl < G) {
-        const int ng = __builtin_amdgcn_readlane(nn, gl);
-        const unsigned j = (unsigned)(cl * BR_WAVE + lane);
-        if ((int)j < ng) {
-          kv[k] = kl[j];
-          rem[k] = rl[j];
-        }
-      }
+      kv[k] = make_int4(0, 0, 0, 0), rem[k] = make_int4(0, 0, 0, 0);
+      if (gl < G) br_adv_load(kl, rl, cl * 256 + 4 * lane, __builtin_amdgcn_readlane(nn, gl), kv[k], rem[k]);
       if (++cl == NC) cl = 0, ++gl, kl += p.Bs, rl += p.Bs;
     }
 #pragma unroll
     for (int k = 0; k < UB; ++k) {
       if (gp < G) {
         const int ng = __builtin_amdgcn_readlane(nn, gp);
-        if (cp * BR_WAVE < ng) {
-          // unused lanes hold kv = rem = 0: they neither stay nor leave
-          const bool stay = rem[k] > t;
-          const unsigned long long bal = br_ballot(stay);
-          const unsigned nj = (unsigned)(kept + br_rank_below(bal));
-          if (stay) {
-            kw[nj] = kv[k] + t;
-            rw[nj] = rem[k] - t;
-            if constexpr (BRH) {
-              const unsigned j = (unsigned)(cp * BR_WAVE + lane);
-              if (p.pred_mode == 2) {
-                float ch = pw[j * 3], age = pw[j * 3 + 1], since = pw[j * 3 + 2];
-                br_refresh_update(p, t, ch, age, since);
-                pw[nj * 3] = ch;
-                pw[nj * 3 + 1] = age;
-                pw[nj * 3 + 2] = since;
-              } else if (nj != j) {
-                for (int q = 0; q < p.P; ++q) pw[nj * p.P + q] = pw[j * p.P + q];
-              }
-            }
-          }
-          kept += __builtin_popcountll(bal);
-          // requests leave rarely: their kv is summed only when some lane has one
-          const bool leave = !stay && kv[k] > 0;
-          if (br_ballot(leave) != 0ull) gone += br_wave_sum(leave ? kv[k] : 0);
-        }
+        if (cp * 256 < ng) br_adv_apply<BRH>(p, t, cp * 256 + 4 * lane, ng, cp * 256, kv[k], rem[k], kw, rw, pw, kept, gone);
         if (++cp == NC) {
           if (lane == gp) dLw = kept * t - gone, nw = kept;  // survivors gain t tokens each
           kept = 0, gone = 0, cp = 0, ++gp;

@@ -636,7 +636,7 @@ __global__ __launch_bounds__(256) void br_k_assign(BrParams p, BrArr a, BrOut o)
   rc.wdrop = wdrop;
   rc.I_before = I_before;
   br_assign_epilogue<E>(inst, lane, q0, qn, cnt, skey, adm, who, Lh[0], nn, rc, c0);
-  if constexpr (ADV) br_advance_cluster<(BRH ? 6 : 24), BRH>(inst, lane, Lh[0], nn);  // BR-H units carry the estimator code: fewer unrolled
+  if constexpr (ADV) br_advance_cluster<(BRH ? 2 : 8), BRH>(inst, lane, Lh[0], nn);  // BR-H units carry the estimator code: fewer unrolled
 }
 
 template <int E, bool BRH>

@@ -251,3 +251,103 @@ __device__ __forceinline__ void br_refresh_update(const BrParams &p, int t, floa
     }
   }
 }
+
+// ---------------------------------------------------------------- decode step on one list chunk
+// Sec. 2.2 load model applied to 256 consecutive slots of one worker list, four slots per lane
+// (16-byte accesses): a request whose remaining output is used up within t steps leaves, the others
+// gain t tokens and move up to keep the list dense.  `kept` counts the survivors of the list so far
+// (uniform), `gone` the kv that left it.  While no request of the list has left, positions do not
+// change and the chunk is updated in place with vector stores; from the first leaver on, survivors are
+// ranked (lower lanes first, then the lane's own slots in order) and stored one by one.  Every slot
+// the chunk overwrites lies at or below the slot it came from and was read by this call or an earlier
+// one, so the compaction is safe in place.
+__device__ __forceinline__ void br_adv_load(const int32_t *kl, const int32_t *rl, int e0, int ng, int4 &kv, int4 &rem) {
+  kv = make_int4(0, 0, 0, 0);
+  rem = make_int4(0, 0, 0, 0);
+  if (e0 < ng) {
+    kv = *reinterpret_cast<const int4 *>(kl + e0);
+    rem = *reinterpret_cast<const int4 *>(rl + e0);
+  }
+}
+
+template <bool PRED>
+__device__ __forceinline__ void br_adv_apply(const BrParams &p, int t, int e0, int ng, int chunk0, const int4 &kv4,
+                                             const int4 &rem4, int32_t *kw, int32_t *rw, float *pw, int &kept,
+                                             int &gone) {
+  const int kv[4] = {kv4.x, kv4.y, kv4.z, kv4.w}, rem[4] = {rem4.x, rem4.y, rem4.z, rem4.w};
+  bool stay[4], leave[4];
+  unsigned long long bs[4];
+  bool any_leave = false;
+  int nstay = 0;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const bool used = e0 + k < ng;
+    stay[k] = used && rem[k] > t;
+    leave[k] = used && !stay[k];
+    any_leave |= leave[k];
+    bs[k] = br_ballot(stay[k]);
+    nstay += __builtin_popcountll(bs[k]);
+  }
+  const bool shifted = kept != chunk0;  // an earlier chunk of this list lost a request
+  if (!shifted && br_ballot(any_leave) == 0ull) {
+    if (e0 < ng) {  // same positions: 16-byte stores; slots beyond the list keep what they held
+      *reinterpret_cast<int4 *>(kw + e0) = make_int4(kv[0] + (stay[0] ? t : 0), kv[1] + (stay[1] ? t : 0),
+                                                      kv[2] + (stay[2] ? t : 0), kv[3] + (stay[3] ? t : 0));
+      *reinterpret_cast<int4 *>(rw + e0) = make_int4(rem[0] - (stay[0] ? t : 0), rem[1] - (stay[1] ? t : 0),
+                                                      rem[2] - (stay[2] ? t : 0), rem[3] - (stay[3] ? t : 0));
+      if constexpr (PRED) {
+        if (p.pred_mode == 2) {
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {
+            if (stay[k]) {
+              float *q = pw + (int64_t)(e0 + k) * 3;
+              float ch = q[0], age = q[1], since = q[2];
+              br_refresh_update(p, t, ch, age, since);
+              q[0] = ch, q[1] = age, q[2] = since;
+            }
+          }
+        }
+      }
+    }
+  } else {
+    int below = 0;  // survivors in lower lanes
+#pragma unroll
+    for (int k = 0; k < 4; ++k) below += br_rank_below(bs[k]);
+    int pos = kept + below;
+    if constexpr (PRED) {
+      // prediction rows move with their requests: all rows of the lane are read before the first is written
+      float pr[4][BR_HP];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        if (stay[k]) {
+#pragma unroll
+          for (int q = 0; q < BR_HP; ++q)
+            if (q < p.P) pr[k][q] = pw[(int64_t)(e0 + k) * p.P + q];
+          if (p.pred_mode == 2) br_refresh_update(p, t, pr[k][0], pr[k][1], pr[k][2]);
+        }
+      }
+      int pp = pos;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        if (stay[k]) {
+#pragma unroll
+          for (int q = 0; q < BR_HP; ++q)
+            if (q < p.P) pw[(int64_t)pp * p.P + q] = pr[k][q];
+          ++pp;
+        }
+      }
+    }
+    int lost = 0;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      if (stay[k]) {
+        kw[pos] = kv[k] + t;
+        rw[pos] = rem[k] - t;
+        ++pos;
+      }
+      lost += leave[k] ? kv[k] : 0;
+    }
+    gone += br_wave_sum(lost);
+  }
+  kept += nstay;
+}

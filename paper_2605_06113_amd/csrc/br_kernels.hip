@@ -46,75 +46,43 @@ __global__ __launch_bounds__(256) void br_k_load_init(BrParams p, const int32_t 
 // footprint goes with it.  t steps are applied in closed form: a request with rem <= t
 // leaves (net load change -kv), the others gain t tokens.  One wave owns one worker's dense
 // list and compacts it in place, order preserved (writes never run ahead of reads).
-template <int NC, int RW>
+template <int NC, int RW, bool PRED>
 __global__ __launch_bounds__(256) void br_k_advance(BrParams p, int t) {
-  // each wave owns RW consecutive worker lists; everything it will touch is requested before the
-  // first result is needed, so that enough bytes are in flight to cover the HBM latency, and the
-  // in-place compaction cannot overtake its own reads
+  // each wave owns RW consecutive worker lists, NC chunks of 256 slots each, four slots per lane;
+  // everything it will touch is requested before the first result is needed, so that enough bytes
+  // are in flight to cover the HBM latency, and the in-place compaction cannot overtake its own reads
   const int64_t row0 = ((int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6)) * RW;
   const int64_t rows = (int64_t)p.N * p.G;
   if (row0 >= rows) return;
   const int lane = br_lane();
-  int n_g[RW], kv[RW][NC], rem[RW][NC];
+  int n_g[RW];
+  int4 kv[RW][NC], rem[RW][NC];
 #pragma unroll
   for (int r = 0; r < RW; ++r) n_g[r] = row0 + r < rows ? p.n[row0 + r] : 0;
 #pragma unroll
   for (int r = 0; r < RW; ++r) {
     const int64_t base = (row0 + r) * p.Bs;
 #pragma unroll
-    for (int c = 0; c < NC; ++c) {
-      const int j = c * BR_WAVE + lane;
-      const bool used = j < n_g[r];
-      kv[r][c] = used ? p.kv[base + j] : 0;
-      rem[r][c] = used ? p.rem[base + j] : 0;
-    }
+    for (int c = 0; c < NC; ++c) br_adv_load(p.kv + base, p.rem + base, c * 256 + 4 * lane, n_g[r], kv[r][c], rem[r][c]);
   }
 #pragma unroll
   for (int r = 0; r < RW; ++r) {
     if (row0 + r >= rows) break;
     const int64_t base = (row0 + r) * p.Bs;
-    int kept = 0;  // uniform
-    int dL = 0;
+    int kept = 0, gone = 0;  // uniform
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
-      if (c * BR_WAVE < n_g[r]) {
-        const int j = c * BR_WAVE + lane;
-        const bool used = j < n_g[r];
-        const bool stay = used && rem[r][c] > t;
-        dL += used ? (stay ? t : -kv[r][c]) : 0;
-        const unsigned long long bal = br_ballot(stay);
-        const int nj = kept + br_rank_below(bal);
-        if (stay) {
-          p.kv[base + nj] = kv[r][c] + t;
-          p.rem[base + nj] = rem[r][c] - t;
-          if (p.pred_mode == 2) {
-            float ch = p.pred[(base + j) * 3], age = p.pred[(base + j) * 3 + 1], since = p.pred[(base + j) * 3 + 2];
-            br_refresh_update(p, t, ch, age, since);
-            p.pred[(base + nj) * 3] = ch;
-            p.pred[(base + nj) * 3 + 1] = age;
-            p.pred[(base + nj) * 3 + 2] = since;
-          } else if (p.P && nj != j) {
-            for (int q = 0; q < p.P; ++q) p.pred[(base + nj) * p.P + q] = p.pred[(base + j) * p.P + q];
-          }
-        }
-        kept += __builtin_popcountll(bal);
+      if (c * 256 < n_g[r]) {
+        br_adv_apply<PRED>(p, t, c * 256 + 4 * lane, n_g[r], c * 256, kv[r][c], rem[r][c], p.kv + base, p.rem + base,
+                           PRED ? p.pred + base * p.P : nullptr, kept, gone);
       }
     }
-    const int tot = br_wave_sum(dL);
     if (lane == 0) {
-      p.L[row0 + r] += tot;
+      p.L[row0 + r] += kept * t - gone;  // survivors gain t tokens each
       p.n[row0 + r] = kept;
     }
   }
 }
-
-// ------------------------------------------------------------------ horizon projection
-// Preparation step of Alg. BR-H, part 1: per worker and offset h = 0..H the projected load
-// L_g(k+h) = sum over active requests of (kv + h) while h <= c_hat (eq. (wprofile-new)).
-// A pure stream over the active lists: one wave owns RW consecutive worker lists and requests
-// everything it will read (kv and the prediction inputs, as 16-byte loads when P is 4 or 8)
-// before the first use; per list it then forms c_hat per request, H+1 integer partial sums per
-// lane, and H+1 DPP wave sums.
 template <int NC, int RW>
 __global__ __launch_bounds__(256) void br_k_project_rows(BrParams p) {
   const int64_t row0 = ((int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6)) * RW;
@@ -420,23 +388,24 @@ void br_launch_load_init(const BrParams &p, const int32_t *n, const int32_t *kv,
 
 template <int NC, int RW>
 static void launch_advance(const BrParams &p, int t, hipStream_t st) {
-  const int64_t waves = ((int64_t)p.N * p.G + RW - 1) / RW;
-  hipLaunchKernelGGL((br_k_advance<NC, RW>), dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, st, p, t);
+  // lists that carry prediction rows take a quarter of the lists per wave (their rows are moved too)
+  constexpr int RWP = RW >= 4 ? RW / 4 : 1;
+  if (p.P) {
+    const int64_t waves = ((int64_t)p.N * p.G + RWP - 1) / RWP;
+    hipLaunchKernelGGL((br_k_advance<NC, RWP, true>), dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, st, p, t);
+  } else {
+    const int64_t waves = ((int64_t)p.N * p.G + RW - 1) / RW;
+    hipLaunchKernelGGL((br_k_advance<NC, RW, false>), dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, st, p, t);
+  }
 }
 
 void br_launch_advance(const BrParams &p, int t, hipStream_t st) {
-  if (p.B <= 64)
-    launch_advance<1, 4>(p, t, st);
-  else if (p.B <= 128)
+  if (p.Bs <= 256)
+    launch_advance<1, 2>(p, t, st);
+  else if (p.Bs <= 512)
     launch_advance<2, 4>(p, t, st);
-  else if (p.B <= 192)
-    launch_advance<3, 4>(p, t, st);
-  else if (p.B <= 256)
-    launch_advance<4, 2>(p, t, st);
-  else if (p.B <= 512)
-    launch_advance<8, 1>(p, t, st);
   else
-    launch_advance<16, 1>(p, t, st);
+    launch_advance<4, 2>(p, t, st);
 }
 
 template <int NC, int RW>
