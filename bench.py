@@ -29,9 +29,9 @@ HBM_PEAK_GBS = 8000.0
 ALU_INT_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 # HBM KiB per launch on this workload from rocprofv3 --pmc (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, see
 # profiles/bench_c4_kernels.md); an entry is None when its kernel changed after the counters were taken
-TRAFFIC_KIB = {"assign+advance": 2.0 * 43697.8 + 90711.5,   # br_k_assign<4,false,true>: round + decode step
-               "assign": 2.0 * 6733.0 + 17454.7, "advance": 2.0 * 37555.5 + 74404.5,
-               "score": 2.0 * 2460.3 + 4352.0}
+TRAFFIC_KIB = {"assign+advance": 2.0 * 43686.1 + 88920.7,   # br_k_assign<4,false,true>: round + decode step
+               "assign": 2.0 * 6739.5 + 17454.5, "advance": 2.0 * 37926.6 + 75017.8,
+               "score": 2.0 * 2459.3 + 4352.0}
 
 
 def cpu_baseline(cfg, init, arr, min_seconds=10.0):
