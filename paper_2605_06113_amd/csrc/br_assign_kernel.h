@@ -40,9 +40,9 @@ struct Log2E {
   static constexpr int v = E == 4 ? 2 : E == 8 ? 3 : E == 16 ? 4 : 5;
 };
 
+// One cluster's round on one wave.  `lds`: this wave's 3*E*64 + 72 words.
 template <int E, bool BRH, bool ADV>
-__global__ __launch_bounds__(256) void br_k_assign(BrParams p, BrArr a, BrOut o) {
-  extern __shared__ int lds_all[];
+__device__ __forceinline__ void br_assign_body(const BrParams &p, const BrArr &a, const BrOut &o, int *lds, int inst) {
   constexpr int NP = E * BR_WAVE;
   constexpr int NH = BRH ? BR_HP + 1 : 1;
   constexpr int IDX_MASK = (1 << BR_IDX_BITS) - 1;
@@ -50,10 +50,7 @@ __global__ __launch_bounds__(256) void br_k_assign(BrParams p, BrArr a, BrOut o)
   constexpr bool PACK1 = !BRH && E <= 16;      // (score, position) of one request fits 32 bits
   constexpr int BIAS1 = 1 << 21;               // single request: score in (-2^21, 2^15]
   constexpr int BIAS2 = 1 << 24;               // subset of <= 8 requests: score in (-2^24, 2^18]
-  // every wave of the block owns one cluster and its own slice of LDS; waves never meet at a barrier
-  const int inst = (int)(blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6));
   if (inst >= p.N) return;
-  int *lds = lds_all + (threadIdx.x >> 6) * (3 * NP + BR_WAVE + 8);
   int *skey = lds;            // [NP] sort buffer, then the sorted keys (s << 11 | 2047 - arrival position)
   int *adm = lds + NP;        // [NP] by sorted position: worker << 16 | slot, or -1
   int *who = lds + 2 * NP;    // [NP] by arrival position: worker, or -1
@@ -637,6 +634,14 @@ __global__ __launch_bounds__(256) void br_k_assign(BrParams p, BrArr a, BrOut o)
   rc.I_before = I_before;
   br_assign_epilogue<E>(inst, lane, q0, qn, cnt, skey, adm, who, Lh[0], nn, rc, c0);
   if constexpr (ADV) br_advance_cluster<(BRH ? 2 : 8), BRH>(inst, lane, Lh[0], nn);  // BR-H units carry the estimator code: fewer unrolled
+}
+
+// every wave of the block owns one cluster and its own slice of LDS; waves never meet at a barrier
+template <int E, bool BRH, bool ADV>
+__global__ __launch_bounds__(256) void br_k_assign(BrParams p, BrArr a, BrOut o) {
+  extern __shared__ int lds_all[];
+  const int w = threadIdx.x >> 6;
+  br_assign_body<E, BRH, ADV>(p, a, o, lds_all + w * (3 * E * BR_WAVE + BR_WAVE + 8), (int)(blockIdx.x * (blockDim.x >> 6)) + w);
 }
 
 template <int E, bool BRH>

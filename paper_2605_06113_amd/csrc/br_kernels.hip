@@ -3,6 +3,7 @@
 // F-score matrix with its stage-one reductions.
 #include "br_device.h"
 #include "br_launch.h"
+#include "br_score_wave.h"
 
 // ------------------------------------------------------------------ initialisation
 
@@ -286,91 +287,15 @@ __global__ __launch_bounds__(512) void br_k_score(BrParams p, BrArr a, BrOut o, 
   }
 }
 
-// K2 + K3 for large batches of small clusters: one wavefront per cluster, no LDS and no barrier.
-// Lane g holds worker g (margins of eq. (br0-Fscore) / eq. (brh-Fscore)); each lane holds E waiting
-// requests in arrival order.  For every worker (margins broadcast by readlane) all requests are
-// scored once; the same score feeds the running best worker of each request (ties: lowest g) and
-// the best request of this worker (ties: larger s, then earlier arrival), the latter finished by two
-// wave reductions.  Results equal br_k_score's; the score matrix itself is not written here.
+// K2 + K3, one wave per cluster (br_score_wave.h)
 template <int E, bool BRH>
 __global__ __launch_bounds__(256) void br_k_score_wave(BrParams p, BrArr a, BrOut o) {
-  constexpr int NH = BRH ? BR_HP + 1 : 1;
-  constexpr int IDX_MASK = (1 << BR_IDX_BITS) - 1;
   const int inst = (int)(blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6));
   if (inst >= p.N) return;
   const int lane = br_lane();
-  const int G = p.G;
-  const int q0 = br_uniform(min(max(p.qlen[inst], 0), p.Q));
-  int cnt = a.count ? a.count[inst] : 0;
-  cnt = br_uniform(min(max(cnt, 0), a.arr_cap));
-  const int qn = q0 + min(cnt, p.Q - q0);
-  const int64_t qrow = (int64_t)inst * p.Q, arow = (int64_t)inst * a.arr_cap;
-
-  const bool act = lane < G;
-  const int64_t wrow = (int64_t)inst * G + lane;
-  const int L = act ? p.L[wrow] : BR_LOW;
-  const int cap = act ? p.B - p.n[wrow] : 0;
-  int m[NH];
-  if constexpr (BRH) {
-#pragma unroll
-    for (int h = 0; h < NH; ++h) m[h] = (act && h <= p.H) ? p.mh[wrow * (p.H + 1) + h] : 0;
-  } else {
-    m[0] = br_wave_max(L) - L;  // M(k) = max_g L_g, m_g = M - L_g
-  }
-
-  int s[E], sec[E], bk[E], bg[E];
-#pragma unroll
-  for (int e = 0; e < E; ++e) {
-    const int i = e * BR_WAVE + lane;
-    int v = 1;
-    if (i < qn) v = i < q0 ? p.qs[qrow + i] : a.s[arow + (i - q0)];
-    s[e] = min(max(v, 1), BR_MAX_S_DEV);
-    sec[e] = i < qn ? ((s[e] << BR_IDX_BITS) | (IDX_MASK - i)) : -1;  // larger s first, then earlier arrival
-    bk[e] = BR_KEY_NONE;
-    bg[e] = -1;
-  }
-
-  int bi_mine = -1;  // lane g: best request of worker g
-  for (int g = 0; g < G; ++g) {
-    int mg[BR_HP + 1];
-#pragma unroll
-    for (int h = 0; h <= BR_HP; ++h) mg[h] = 0;
-#pragma unroll
-    for (int h = 0; h < NH; ++h) mg[h] = __builtin_amdgcn_readlane(m[h], g);
-    const int Lg = __builtin_amdgcn_readlane(L, g);
-    const bool free_slot = __builtin_amdgcn_readlane(cap, g) > 0;
-    int bi = -1;
-    if (free_slot) {
-      const int room = p.W > 0 ? p.W - Lg : INT32_MAX;
-      int kk[E], lmax = BR_KEY_NONE;
-#pragma unroll
-      for (int e = 0; e < E; ++e) {  // straight-line selects; lanes without a request carry sec = -1
-        const int key = br_score_key<BRH>(p, mg, s[e]);
-        kk[e] = ((sec[e] >= 0) & (s[e] <= room)) ? key : BR_KEY_NONE;
-        const bool newg = kk[e] > bk[e];
-        bk[e] = newg ? kk[e] : bk[e];
-        bg[e] = newg ? g : bg[e];
-        lmax = max(lmax, kk[e]);
-      }
-      const int km = br_wave_max(lmax);
-      if (km != BR_KEY_NONE) {  // among the requests that reach the best score: larger s, then earlier arrival
-        int w2 = -1;
-#pragma unroll
-        for (int e = 0; e < E; ++e) w2 = max(w2, kk[e] == km ? sec[e] : -1);
-        bi = IDX_MASK - (br_wave_max(w2) & IDX_MASK);
-      }
-    }
-    bi_mine = lane == g ? bi : bi_mine;
-  }
-
-  if (o.best_g) {
-#pragma unroll
-    for (int e = 0; e < E; ++e) {
-      const int i = e * BR_WAVE + lane;
-      if (i < p.Q) o.best_g[qrow + i] = i < qn ? bg[e] : -1;
-    }
-  }
-  if (o.best_i && act) o.best_i[wrow] = bi_mine;
+  BrScoreIn<E, BRH> in;
+  br_score_wave_load<E, BRH>(p, a, inst, lane, in);
+  br_score_wave_run<E, BRH>(p, o, inst, lane, in);
 }
 
 // ------------------------------------------------------------------ launchers

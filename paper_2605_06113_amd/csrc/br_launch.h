@@ -13,4 +13,6 @@ void br_launch_project(const BrParams &p, hipStream_t st);
 void br_launch_score(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st);
 void br_launch_assign(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st);
 void br_launch_assign_br0(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st);
+// BR-0, Q <= 256: snapshot reductions and assignment of four clusters per block in one launch
+void br_launch_route4(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st);
 void br_launch_bypass(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st);
