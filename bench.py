@@ -93,13 +93,13 @@ def latency_run(steps, device):
     return res
 
 
-def brh_run(device, steps=6, warmup=2, gate=None):
+def brh_run(device, steps=5, warmup=1, gate=None):
     """Batched BR-H round (horizon projection + scores + assignment) and decode step:
-    1024 clusters of the c3 shape (G=32, B=96, H=4), 76 active requests per worker, 256 waiting."""
+    4096 clusters of the c3 shape (G=32, B=96, H=4), 76 active requests per worker, 256 waiting."""
     import torch
     from paper_2605_06113_amd import binding, workloads as wl
     over = {} if gate is None else dict(gate_pfin=gate)
-    cfg = wl.config("c3", n_inst=1024, **over, token_watermark=0, token_cap=0, init_active_per_worker=76, init_kv_lo=256, init_kv_hi=8192,
+    cfg = wl.config("c3", n_inst=4096, **over, token_watermark=0, token_cap=0, init_active_per_worker=76, init_kv_lo=256, init_kv_hi=8192,
                     init_rem_lo=1, init_rem_hi=1024, init_waiting=256)
     init, arr = wl.initial_state(cfg), wl.initial_waiting(cfg)
     routers = [binding.Router(cfg, init, device=device) for _ in range(steps + warmup)]
@@ -132,7 +132,7 @@ def brh_run(device, steps=6, warmup=2, gate=None):
     active = N * G * 76
     bytes_k = dict(project=active * (4 + 4 * P) + N * G * 4 + N * (H + 1) * 4 * (2 * G + 1) + N * G * 4,
                    advance=(active + admitted) * 16 + N * G * 16)
-    res = dict(workload="1024 clusters of the c3 shape: BR-H H=4, G=32, B=96, 76 active per worker, 256 waiting; "
+    res = dict(workload="4096 clusters of the c3 shape: BR-H H=4, G=32, B=96, 76 active per worker, 256 waiting; "
                         f"p_fin gate {cfg.gate_pfin}",
                ms_per_step=elapsed / steps * 1e3, pairs_per_s=qn * G * steps / elapsed,
                decisions_per_s=admitted * steps / elapsed, kernels={})

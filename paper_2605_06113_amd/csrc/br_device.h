@@ -261,10 +261,12 @@ __device__ __forceinline__ void br_refresh_update(const BrParams &p, int t, floa
 // ranked (lower lanes first, then the lane's own slots in order) and stored one by one.  Every slot
 // the chunk overwrites lies at or below the slot it came from and was read by this call or an earlier
 // one, so the compaction is safe in place.
-__device__ __forceinline__ void br_adv_load(const int32_t *kl, const int32_t *rl, int e0, int ng, int4 &kv, int4 &rem) {
+// `lim`: slots to fetch, the list length if it is already known, else the row length (the request then does
+// not wait for the length to arrive; what lies beyond the list is ignored by br_adv_apply)
+__device__ __forceinline__ void br_adv_load(const int32_t *kl, const int32_t *rl, int e0, int lim, int4 &kv, int4 &rem) {
   kv = make_int4(0, 0, 0, 0);
   rem = make_int4(0, 0, 0, 0);
-  if (e0 < ng) {
+  if (e0 < lim) {
     kv = *reinterpret_cast<const int4 *>(kl + e0);
     rem = *reinterpret_cast<const int4 *>(rl + e0);
   }

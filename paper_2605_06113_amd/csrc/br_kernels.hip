@@ -64,7 +64,7 @@ __global__ __launch_bounds__(256) void br_k_advance(BrParams p, int t) {
   for (int r = 0; r < RW; ++r) {
     const int64_t base = (row0 + r) * p.Bs;
 #pragma unroll
-    for (int c = 0; c < NC; ++c) br_adv_load(p.kv + base, p.rem + base, c * 256 + 4 * lane, n_g[r], kv[r][c], rem[r][c]);
+    for (int c = 0; c < NC; ++c) br_adv_load(p.kv + base, p.rem + base, c * 256 + 4 * lane, row0 + r < rows ? p.Bs : 0, kv[r][c], rem[r][c]);
   }
 #pragma unroll
   for (int r = 0; r < RW; ++r) {
@@ -313,8 +313,7 @@ void br_launch_load_init(const BrParams &p, const int32_t *n, const int32_t *kv,
 
 template <int NC, int RW>
 static void launch_advance(const BrParams &p, int t, hipStream_t st) {
-  // lists that carry prediction rows take a quarter of the lists per wave (their rows are moved too)
-  constexpr int RWP = RW >= 4 ? RW / 4 : 1;
+  constexpr int RWP = NC == 1 ? 2 : 1;  // lists that carry prediction rows: at most four chunks per wave (code size)
   if (p.P) {
     const int64_t waves = ((int64_t)p.N * p.G + RWP - 1) / RWP;
     hipLaunchKernelGGL((br_k_advance<NC, RWP, true>), dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, st, p, t);

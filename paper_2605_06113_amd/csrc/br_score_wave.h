@@ -83,6 +83,10 @@ __device__ __forceinline__ void br_score_wave_run(const BrParams &p, const BrOut
       int kk[E], lmax = BR_KEY_NONE;
 #pragma unroll
       for (int e = 0; e < E; ++e) {  // straight-line selects; lanes without a request carry sec = -1
+        if (E > 4 && e * BR_WAVE >= qn) {  // wide layouts: skip the registers beyond the queue
+          kk[e] = BR_KEY_NONE;
+          continue;
+        }
         const int key = br_score_key<BRH>(p, mg, s[e]);
         kk[e] = ((sec[e] >= 0) & (s[e] <= room)) ? key : BR_KEY_NONE;
         const bool newg = kk[e] > bk[e];

@@ -328,10 +328,10 @@ def test_replay_full_length(name, over):
 
 @pytest.mark.parametrize("gate", [None, 0.0])
 def test_brh_batched_bench_configuration(gate):
-    """The batched BR-H side workload of bench.py at full size (1024 clusters), every instance; also with
+    """The batched BR-H side workload of bench.py at full size (4096 clusters), every instance; also with
     the p_fin gate off (then no request counts at the last offset and every score is negative)."""
     over = {} if gate is None else dict(gate_pfin=gate)
-    cfg = wl.config("c3", n_inst=1024, token_watermark=0, **over, token_cap=0, init_active_per_worker=76,
+    cfg = wl.config("c3", n_inst=4096, token_watermark=0, **over, token_cap=0, init_active_per_worker=76,
                     init_kv_lo=256, init_kv_hi=8192, init_rem_lo=1, init_rem_hi=1024, init_waiting=256)
     _say("brh batched full size")
     init, arr = wl.initial_state(cfg), wl.initial_waiting(cfg)
