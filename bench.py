@@ -107,15 +107,13 @@ def brh_run(device, steps=5, warmup=1, gate=None):
     out = routers[0].alloc_outputs(scores=True, matrix=False)
     torch.cuda.synchronize()
     for r in routers[:warmup]:
-        r.route_step_device(darr, out)
-        r.advance(1)
+        r.route_advance_device(darr, out, 1)
     torch.cuda.synchronize()
     for r in routers[warmup:]:
         r.profile(True)
     t0 = time.perf_counter()
     for r in routers[warmup:]:
-        r.route_step_device(darr, out)
-        r.advance(1)
+        r.route_advance_device(darr, out, 1)   # projection, scores, assignment + decode step
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     stats = out["stats"].cpu().numpy()

@@ -633,12 +633,14 @@ __device__ __forceinline__ void br_assign_body(const BrParams &p, const BrArr &a
   rc.wdrop = wdrop;
   rc.I_before = I_before;
   br_assign_epilogue<E>(inst, lane, q0, qn, cnt, skey, adm, who, Lh[0], nn, rc, c0);
-  if constexpr (ADV) br_advance_cluster<(BRH ? 2 : 8), BRH>(inst, lane, Lh[0], nn);  // BR-H units carry the estimator code: fewer unrolled
+  if constexpr (ADV) br_advance_cluster<(BRH ? 4 : 8), BRH>(inst, lane, Lh[0], nn);  // BR-H units carry the estimator code: fewer unrolled
 }
 
 // every wave of the block owns one cluster and its own slice of LDS; waves never meet at a barrier
+// The BR-H kernel for queues of up to 512 needs one register more than lets four waves share a SIMD
+// (a batch of 4096 clusters is four waves per SIMD): it is asked to fit.
 template <int E, bool BRH, bool ADV>
-__global__ __launch_bounds__(256) void br_k_assign(BrParams p, BrArr a, BrOut o) {
+__global__ __launch_bounds__(256, (BRH && E == 8) ? 4 : 1) void br_k_assign(BrParams p, BrArr a, BrOut o) {
   extern __shared__ int lds_all[];
   const int w = threadIdx.x >> 6;
   br_assign_body<E, BRH, ADV>(p, a, o, lds_all + w * (3 * E * BR_WAVE + BR_WAVE + 8), (int)(blockIdx.x * (blockDim.x >> 6)) + w);
