@@ -342,7 +342,7 @@ void br_launch_project(const BrParams &p, hipStream_t st) {
   if (p.B <= 64)
     launch_project_rows<1, 4>(p, st);
   else if (p.B <= 128)
-    launch_project_rows<2, 4>(p, st);
+    launch_project_rows<2, 2>(p, st);
   else if (p.B <= 192)
     launch_project_rows<3, 2>(p, st);
   else if (p.B <= 256)
