@@ -61,30 +61,56 @@ __device__ __forceinline__ void br_assign_epilogue(int inst, int lane, int q0, i
   const int64_t wrow = (int64_t)inst * G + lane;
   const int64_t qrow = (int64_t)inst * t.Q, arow = (int64_t)inst * t.arr_cap;
   const int admitted = rc.admitted;
-  // ---- commit the admitted requests into their workers' dense lists
+  // ---- commit the admitted requests into their workers' dense lists, GR blocks of sorted positions
+  //      at a time: what a group reads from the queue and the arrivals is requested before its first store
+  constexpr int GR = E < 4 ? E : 4;
   if (admitted > 0) {
 #pragma unroll
-    for (int j = 0; j < E; ++j) {
-      const int pos = j * BR_WAVE + lane;
-      if (pos < qn) {
-        const int ad = adm[pos];
-        if (ad >= 0) {
-          const int key = skey[pos];
-          const int idx = IDX_MASK - (key & IDX_MASK);
-          const int g = ad >> 16, slot = ad & 0xffff;
-          if (g < G && slot < t.B && idx < qn) {
-            const int64_t row = ((int64_t)inst * G + g) * t.Bs + slot;
-            const bool old = idx < q0;
-            t.kv[row] = key >> BR_IDX_BITS;
-            t.rem[row] = old ? t.qo[qrow + idx] : max(t.ao[arow + (idx - q0)], 1);
-            for (int q = 0; q < t.Pq; ++q)
-              t.pred[row * t.P + q] = old ? t.qpred[(qrow + idx) * t.Pq + q] : t.apred[(arow + (idx - q0)) * t.Pq + q];
-            if (t.P == 3 && t.Pq == 0) {  // maintained estimate: first query at age 0, nothing generated yet
-              t.pred[row * 3] = c0;
-              t.pred[row * 3 + 1] = 0.0f;
-              t.pred[row * 3 + 2] = 0.0f;
+    for (int j0 = 0; j0 < E; j0 += GR) {
+      if (j0 * BR_WAVE < qn) {
+        int64_t row[GR];
+        int idx[GR], kvv[GR], remv[GR];
+        float pr[GR][BR_HP];
+        bool ok[GR];
+#pragma unroll
+        for (int u = 0; u < GR; ++u) {
+          const int pos = (j0 + u) * BR_WAVE + lane;
+          ok[u] = false;
+          idx[u] = 0, kvv[u] = 0, remv[u] = 1, row[u] = 0;
+          if (pos < qn) {
+            const int ad = adm[pos];
+            if (ad >= 0) {
+              const int key = skey[pos];
+              idx[u] = IDX_MASK - (key & IDX_MASK);
+              const int g = ad >> 16, slot = ad & 0xffff;
+              if (g < G && slot < t.B && idx[u] < qn) {
+                ok[u] = true;
+                row[u] = ((int64_t)inst * G + g) * t.Bs + slot;
+                kvv[u] = key >> BR_IDX_BITS;
+                const bool old = idx[u] < q0;
+                remv[u] = old ? t.qo[qrow + idx[u]] : max(t.ao[arow + (idx[u] - q0)], 1);
+#pragma unroll
+                for (int q = 0; q < BR_HP; ++q)
+                  if (q < t.Pq)
+                    pr[u][q] = old ? t.qpred[(qrow + idx[u]) * t.Pq + q] : t.apred[(arow + (idx[u] - q0)) * t.Pq + q];
+                who[idx[u]] = g;
+              }
             }
-            who[idx] = g;
+          }
+        }
+#pragma unroll
+        for (int u = 0; u < GR; ++u) {
+          if (ok[u]) {
+            t.kv[row[u]] = kvv[u];
+            t.rem[row[u]] = remv[u];
+#pragma unroll
+            for (int q = 0; q < BR_HP; ++q)
+              if (q < t.Pq) t.pred[row[u] * t.P + q] = pr[u][q];
+            if (t.P == 3 && t.Pq == 0) {  // maintained estimate: first query at age 0, nothing generated yet
+              t.pred[row[u] * 3] = c0;
+              t.pred[row[u] * 3 + 1] = 0.0f;
+              t.pred[row[u] * 3 + 2] = 0.0f;
+            }
           }
         }
       }
@@ -97,7 +123,6 @@ __device__ __forceinline__ void br_assign_epilogue(int inst, int lane, int q0, i
   // first store, so the loads of a group overlap (a 2048-entry queue is 32 blocks, each a round trip to
   // memory otherwise).  In place: a deferred entry moves to a position at or below its own, inside or
   // before its group, and later groups read only beyond it.
-  constexpr int GR = E < 4 ? E : 4;
   int kept = 0;
 #pragma unroll
   for (int j0 = 0; j0 < E; j0 += GR) {
