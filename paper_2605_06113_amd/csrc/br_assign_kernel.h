@@ -19,6 +19,14 @@
 // takes the k-th largest waiting request.  The first worker for which this fails falls back to
 // the full single-request search.
 //
+// BR-0 (no watermark, G > 1) has three more steps of the same kind, each stated and argued where it
+// is coded: when no waiting request is shorter than a worker's margin the best single request is the
+// shortest one (two ballots instead of a scan); from the first Stage-1 worker of a level for which
+// that holds, the rest of the level takes the shortest requests in order, in one step; Stage 2 skips
+// the subset enumeration when the window's smallest entry alone scores <= 0 (the starvation guard is
+// then certain), and takes the consecutive guard pops of one free-slot count in one step while the
+// window stays untouched.
+//
 // Ties: Stage 1 worker (most free slots, then lightest, then lowest index); Stage 2 worker
 // (most free slots, then largest horizon-min margin, then lowest index); equal request scores
 // resolve to the lowest sorted position; equal subset scores to the lowest mask.
