@@ -19,8 +19,8 @@
 // takes the k-th largest waiting request.  The first worker for which this fails falls back to
 // the full single-request search.
 //
-// BR-0 (no watermark, G > 1) has three more steps of the same kind, each stated and argued where it
-// is coded: when no waiting request is shorter than a worker's margin the best single request is the
+// BR-0 with G > 1 has three more steps of the same kind (the one-step forms only without a token
+// watermark), each stated and argued where it is coded: when no waiting request is shorter than a worker's margin the best single request is the
 // shortest one (two ballots instead of a scan); from the first Stage-1 worker of a level for which
 // that holds, the rest of the level takes the shortest requests in order, in one step; Stage 2 skips
 // the subset enumeration when the window's smallest entry alone scores <= 0 (the starvation guard is
@@ -231,11 +231,12 @@ __device__ __forceinline__ void br_assign_body(const BrParams &p, const BrArr &a
     return mn;
   };
 
-  // BR-0 without watermark and with G > 1: when no waiting request is shorter than the margin,
+  // BR-0 with G > 1: when no waiting request is shorter than the margin,
   // eq. (br0-Fscore) is G m - (G-1) s on the whole waiting set, so argmax_i F_g({i}) is the shortest
   // request (earliest arrival among equals) and no scan is needed.  The shortest waiting request is
   // the last alive position of the sorted set; it is looked up again after it has been taken.
-  const bool tail_rule = !BRH && p.W <= 0 && G > 1;
+  const bool tail_rule = !BRH && G > 1;
+  const bool tail_bulk_ok = p.W <= 0;  // the one-step admissions below are argued without the watermark
   int tail_pos = -1, tail_s = 0;
   bool tail_dirty = true;
   auto ensure_tail = [&]() {
@@ -443,13 +444,17 @@ __device__ __forceinline__ void br_assign_body(const BrParams &p, const BrArr &a
               // so its margin is at most that length and the same holds for it: the rest of the level
               // takes the waiting requests in order of (length, arrival), one each.
               const int K = min(level - r, min(S_tot - p.S_greedy, n_alive));
-              if (K >= 3) {
+              if (tail_bulk_ok && K >= 3) {
                 const int done = tail_bulk(member, rank, r, K, -1);
                 if (done > 0) {
                   stage1 += done;
                   r += done - 1;
                   continue;
                 }
+              }
+              if (tail_s > room) {  // under the watermark even the shortest request is too long: nothing is admissible
+                drop_worker(g, capmax);
+                continue;
               }
               pick_tail(pos, swin);
               found = true;
@@ -512,7 +517,7 @@ __device__ __forceinline__ void br_assign_body(const BrParams &p, const BrArr &a
       bool guard_sure = false;
       if constexpr (!BRH) guard_sure = br_score0(G, mg[0], s_last) <= 0;
       if constexpr (!BRH) {
-        if (guard_sure && tail_rule) {
+        if (guard_sure && tail_rule && tail_bulk_ok) {
           ensure_tail();
           if (tail_s >= mg[0]) {
             // This worker takes the shortest waiting request through the guard and the envelope becomes
@@ -598,6 +603,10 @@ __device__ __forceinline__ void br_assign_body(const BrParams &p, const BrArr &a
           if (tail_rule) {
             ensure_tail();
             if (tail_s >= mg[0]) {
+              if (tail_s > room) {  // nothing is admissible under the watermark
+                drop_worker(g, capmax);
+                continue;
+              }
               pick_tail(pos, swin);
               found = true;
             }

@@ -152,7 +152,10 @@ def test_random_shapes_equal_lengths_and_loads(seed):
         spread = int(rng.choice([0, 0, 5, 50, 500, 5000, 50000]))
         lo = int(rng.choice([1, 5, 50, 500, 3000]))
         width = int(rng.choice([1, 2, 3, 10, 100, 1000, 20000]))
-        cfg = wl.RouteConfig(name="shapes", n_inst=N, G=G, B=B, max_wait=Q, H=0, R_max=R_max, S_greedy=S_greedy)
+        # a token watermark around the loads in a third of the shapes: some workers can take nothing
+        wm = int(rng.choice([0, 0, 0, 0, 1000 * n0 + lo, 1000 * n0 + 2 * (lo + width), 1000 * n0 + 6 * (lo + width)]))
+        cfg = wl.RouteConfig(name="shapes", n_inst=N, G=G, B=B, max_wait=Q, H=0, R_max=R_max, S_greedy=S_greedy,
+                             token_watermark=wm, token_cap=wm)
         n = np.full((N, G), n0, np.int32)
         n[:, ::3] = rng.integers(0, B + 1, size=n[:, ::3].shape)
         kv = np.zeros((N, G, B), np.int32)
@@ -163,7 +166,7 @@ def test_random_shapes_equal_lengths_and_loads(seed):
             kv[:, :, 0] += rng.integers(0, spread + 1, size=(N, G)).astype(np.int32) * (n > 0)
         rem[used] = rng.integers(1, 4, size=int(used.sum()))
         init = wl.InitState(n=n, kv=kv, rem=rem, pred=None)
-        tag = f"shapes {seed}/{case}: N={N} G={G} B={B} Q={Q} R_max={R_max} S_greedy={S_greedy} n0={n0} spread={spread} s in [{lo},{lo + width})"
+        tag = f"shapes {seed}/{case}: W={wm} N={N} G={G} B={B} Q={Q} R_max={R_max} S_greedy={S_greedy} n0={n0} spread={spread} s in [{lo},{lo + width})"
         _say(tag)
         oc, r = br_oracle.OracleCluster(cfg, init), binding.Router(cfg, init)
         for rnd in range(3):
