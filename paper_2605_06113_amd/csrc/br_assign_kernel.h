@@ -503,10 +503,8 @@ __device__ __forceinline__ void br_assign_body(const BrParams &p, const BrArr &a
             const unsigned long long bal = br_ballot(al);
             const int ar = base + br_rank_below(bal);
             if (al && ar < w) win[ar] = (sv[j] << BR_IDX_BITS) | (j * BR_WAVE + lane);
-            if constexpr (!BRH) {
-              const unsigned long long hit = br_ballot(al && ar == w - 1);
-              if (hit != 0ull) s_last = __builtin_amdgcn_readlane(sv[j], (int)__builtin_ctzll(hit));
-            }
+            const unsigned long long hit = br_ballot(al && ar == w - 1);
+            if (hit != 0ull) s_last = __builtin_amdgcn_readlane(sv[j], (int)__builtin_ctzll(hit));
             base += __builtin_popcountll(bal);
           }
         }
@@ -514,8 +512,21 @@ __device__ __forceinline__ void br_assign_body(const BrParams &p, const BrArr &a
       // BR-0: every subset of the window sums to at least its smallest entry, and eq. (br0-Fscore)
       // falls beyond the margin; if that entry alone scores <= 0 (then it exceeds the margin), no
       // subset scores above 0 and the round goes to the starvation guard without the enumeration.
+      // BR-H: eq. (brh-Fscore) is concave in Delta with F(0) = 0, so F(Delta) <= F(s) Delta / s for every
+      // Delta >= s.  The scores are compared as computed in fp32: each of the at most H + 5 roundings of
+      // one evaluation is relative 2^-24 on terms bounded by (alpha D + beta D) Delta, under 8e-7 of that in
+      // all.  If the smallest entry's computed score is below -8e-6 (alpha D + beta D) s, its exact score
+      // is below -7e-6 of it, every subset's exact score below the same fraction of its own Delta, and
+      // every subset's computed score below zero: the guard is certain here too.
       bool guard_sure = false;
-      if constexpr (!BRH) guard_sure = br_score0(G, mg[0], s_last) <= 0;
+      if constexpr (!BRH) {
+        guard_sure = br_score0(G, mg[0], s_last) <= 0;
+      } else {
+        float Dsum = 0.0f;
+#pragma unroll
+        for (int h = 0; h <= BR_HP; ++h) Dsum += p.d[h];
+        guard_sure = br_scoreh(p, mg, s_last) <= -8e-6f * (p.aD + p.beta * Dsum) * (float)s_last;
+      }
       if constexpr (!BRH) {
         if (guard_sure && tail_rule && tail_bulk_ok) {
           ensure_tail();
