@@ -23,6 +23,23 @@ def test_c1_single_step():
     _say("c1")
     oc, r = run_pair(cfg, wl.initial_state(cfg), wl.initial_waiting(cfg), tag="c1")
     r.close()
+    # and against the stored result of the oracle (tests/golden/c1_round.txt)
+    import os
+    gold = {}
+    for line in open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "c1_round.txt")):
+        if not line.startswith("#"):
+            k, *v = line.split()
+            gold[k] = [int(x) for x in v]
+    r = binding.Router(cfg, wl.initial_state(cfg))
+    out = r.route_step(wl.initial_waiting(cfg))
+    assert out["assign"][0, :32].tolist() == gold["assign"] and out["best_g"][0, :32].tolist() == gold["best_g"]
+    assert out["best_i"][0].tolist() == gold["best_i"] and out["stats"][0, :10].tolist() == gold["stats"]
+    st = r.state()
+    assert st["L"][0].tolist() == gold["L"] and st["n"][0].tolist() == gold["n"]
+    r.advance(1)
+    st = r.state()
+    assert st["L"][0].tolist() == gold["L1"] and st["n"][0].tolist() == gold["n1"]
+    r.close()
 
 
 CASES = [

@@ -422,3 +422,15 @@ def test_admitted_load_enters_every_horizon_offset(orc):
     ev = out["events"][0][:out["n_events"][0]]
     assert [(int(e["g"]), int(e["delta"]), float(e["score"])) for e in ev] == \
         [(0, 4, -6.0), (1, 5, 4.5), (0, 10, -12.0), (1, 12, 9.0)]
+
+
+def test_c1_matches_stored_round(orc):
+    """The smallest workload against tests/golden/c1_round.txt (written by tests/golden/make_c1_golden.py from
+    the oracle alone): a change of the oracle's arithmetic or of the input generators shows up here."""
+    import importlib.util
+    import os
+    here = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+    spec = importlib.util.spec_from_file_location("make_c1_golden", os.path.join(here, "make_c1_golden.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    assert mod.compute() == open(os.path.join(here, "c1_round.txt")).read()
