@@ -77,7 +77,9 @@ def _build(tmp, name, text):
 
 def _pins_pass(so):
     env = dict(os.environ, BR_ORACLE_LIB=so)
-    r = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider", "-m", "not gpu"] + PIN_FILES,
+    # the stored c1 round was written by the oracle itself: it guards against drift, it is no independent pin
+    r = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider", "-m", "not gpu",
+                        "-k", "not stored_round"] + PIN_FILES,
                        cwd=ROOT, env=env, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, timeout=300)
     return r.returncode == 0, r.stdout.decode()[-800:]
 
