@@ -127,6 +127,15 @@ class DeviceArrivals:
 
     def __init__(self, arr, device, P: int):
         import torch
+        # the C ABI takes bare pointers: sizes are checked here, before anything reaches a kernel
+        n_inst, cap = np.shape(arr.s)
+        for name in ("o", "id"):
+            if np.shape(getattr(arr, name)) != (n_inst, cap):
+                raise BrError(f"arrivals.{name} must have shape {(n_inst, cap)}")
+        if np.shape(arr.count) != (n_inst,):
+            raise BrError(f"arrivals.count must have shape {(n_inst,)}")
+        if P and (arr.pred is None or np.shape(arr.pred) != (n_inst, cap, P)):
+            raise BrError(f"arrivals.pred must have shape {(n_inst, cap, P)}")
         self.count = torch.as_tensor(np.ascontiguousarray(arr.count, np.int32), device=device)
         self.s = torch.as_tensor(np.ascontiguousarray(arr.s, np.int32), device=device)
         self.o = torch.as_tensor(np.ascontiguousarray(arr.o, np.int32), device=device)
@@ -170,6 +179,13 @@ class Router:
         ini = None
         self._keep = []
         if init is not None:
+            if np.shape(init.n) != (self.N, self.G):
+                raise BrError(f"init.n must have shape {(self.N, self.G)}")
+            for name in ("kv", "rem"):
+                if np.shape(getattr(init, name)) != (self.N, self.G, self.B):
+                    raise BrError(f"init.{name} must have shape {(self.N, self.G, self.B)}")
+            if self.P and (init.pred is None or np.shape(init.pred) != (self.N, self.G, self.B, self.P)):
+                raise BrError(f"init.pred must have shape {(self.N, self.G, self.B, self.P)}")
             t = lambda a, dt: torch.as_tensor(np.ascontiguousarray(a, dt), device=self.device)
             n, kv, rem = t(init.n, np.int32), t(init.kv, np.int32), t(init.rem, np.int32)
             pred = t(init.pred, np.float32) if self.P else None

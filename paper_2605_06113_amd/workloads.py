@@ -190,6 +190,26 @@ def _instance_rngs(cfg: RouteConfig):
     return [np.random.Generator(np.random.PCG64(k)) for k in kids]
 
 
+def slot_pred_width(cfg: RouteConfig) -> int:
+    """Floats an ACTIVE request carries: H hazards, one estimate, or (estimate, age, tokens since the last
+    query) when the library maintains the estimate itself (pred_mode 2)."""
+    if cfg.H == 0:
+        return 0
+    return 3 if cfg.pred_mode == 2 else (1 if cfg.pred_mode == 1 else cfg.H)
+
+
+def maintained_triples(rng, cfg: RouteConfig, size) -> np.ndarray:
+    """Initial (estimate, age, tokens since the last query) of requests that are already active when the
+    library takes over (pred_mode 2): estimate anywhere in [1, H], a small integer age, a phase below the
+    refresh period.  All three are exact in fp32."""
+    shape = (size,) if np.isscalar(size) else tuple(size)
+    out = np.zeros(shape + (3,), np.float32)
+    out[..., 0] = rng.integers(4, 4 * cfg.H + 1, size=shape) / 4.0
+    out[..., 1] = rng.integers(0, 40, size=shape)
+    out[..., 2] = rng.integers(0, max(cfg.refresh_eff, 1), size=shape)
+    return out
+
+
 def pred_width(cfg: RouteConfig) -> int:
     """Floats a waiting request / an arrival carries for the prediction interface."""
     if cfg.H == 0 or cfg.pred_mode == 2:
@@ -205,11 +225,13 @@ def output_history(cfg: RouteConfig, n: int = 4096) -> np.ndarray:
 
 def initial_state(cfg: RouteConfig) -> InitState:
     """Active sets at step 0 (dense per-worker lists)."""
-    N, G, B, P = cfg.n_inst, cfg.G, cfg.B, pred_width(cfg)
+    N, G, B, P = cfg.n_inst, cfg.G, cfg.B, slot_pred_width(cfg)
     n = np.zeros((N, G), np.int32)
     kv = np.zeros((N, G, B), np.int32)
     rem = np.zeros((N, G, B), np.int32)
     pred = np.zeros((N, G, B, P), np.float32) if P else None
+    slot_pred = (lambda rng, size: maintained_triples(rng, cfg, size)) if cfg.pred_mode == 2 else \
+        (lambda rng, size: hazards(rng, cfg, size))
     rngs = _instance_rngs(cfg)
     for i, rng in enumerate(rngs):
         if cfg.init_active_per_worker:
@@ -218,7 +240,7 @@ def initial_state(cfg: RouteConfig) -> InitState:
             kv[i, :, :a] = rng.integers(cfg.init_kv_lo, cfg.init_kv_hi + 1, size=(G, a))
             rem[i, :, :a] = rng.integers(cfg.init_rem_lo, cfg.init_rem_hi + 1, size=(G, a))
             if P:
-                pred[i, :, :a] = hazards(rng, cfg, (G, a)).reshape(G, a, P)
+                pred[i, :, :a] = slot_pred(rng, (G, a)).reshape(G, a, P)
         elif cfg.init_active_total:
             for _ in range(cfg.init_active_total):
                 while True:
@@ -229,7 +251,7 @@ def initial_state(cfg: RouteConfig) -> InitState:
                 kv[i, g, j] = rng.integers(cfg.init_kv_lo, cfg.init_kv_hi + 1)
                 rem[i, g, j] = rng.integers(cfg.init_rem_lo, cfg.init_rem_hi + 1)
                 if P:
-                    pred[i, g, j] = hazards(rng, cfg, 1).reshape(P)
+                    pred[i, g, j] = slot_pred(rng, 1).reshape(P)
                 n[i, g] += 1
     return InitState(n, kv, rem, pred)
 
@@ -316,6 +338,9 @@ def random_case(seed: int, N: int, G: int, B: int, max_wait: int, H: int = 0,
     kv[used] = kvv[used]
     remv = rng.integers(1, max(2 * H, 8) + 1, size=(N, G, B), dtype=np.int32)
     rem[used] = remv[used]
+    if pred_mode == 2 and H > 0:   # the library maintains the estimate: active requests carry (estimate, age, phase)
+        pred = np.zeros((N, G, B, 3), np.float32)
+        pred[used] = maintained_triples(rng, cfg, (N, G, B))[used]
     if P:
         pv = hazards(rng, cfg, (N, G, B)).reshape(N, G, B, P)
         if pred_mode == 0:

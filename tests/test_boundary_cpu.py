@@ -71,3 +71,20 @@ def test_no_cpu_fallback_when_library_missing(monkeypatch):
     monkeypatch.setattr(binding, "LIB_PATH", "/nonexistent/libbr_hip.so")
     with pytest.raises(RuntimeError):
         binding.load()
+
+
+def test_binding_checks_sizes_before_anything_reaches_a_kernel():
+    """The C ABI takes bare pointers; the Python side refuses arrays whose shapes do not match."""
+    import numpy as np
+    from paper_2605_06113_amd import workloads as wl
+    a = wl.Arrivals(count=np.zeros(2, np.int32), s=np.ones((2, 5), np.int32), o=np.ones((2, 5), np.int32),
+                    id=np.zeros((2, 5), np.int32), pred=None)
+    binding.DeviceArrivals(a, "cpu", 0)
+    with pytest.raises(binding.BrError):
+        binding.DeviceArrivals(a, "cpu", 4)                       # predictions missing
+    a.pred = np.zeros((2, 5, 3), np.float32)
+    with pytest.raises(binding.BrError):
+        binding.DeviceArrivals(a, "cpu", 4)                       # wrong width
+    a.o = np.ones((2, 4), np.int32)
+    with pytest.raises(binding.BrError):
+        binding.DeviceArrivals(a, "cpu", 0)

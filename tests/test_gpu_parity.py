@@ -201,6 +201,48 @@ def test_random_shapes_equal_lengths_and_loads(seed):
         r.close()
 
 
+def test_random_shapes_horizon():
+    """Many small BR-H shapes drawn at random: every prediction mode (hazards, direct estimate, estimate kept
+    by the library with initial (estimate, age, phase) triples), gates, discounts, weights, thresholds."""
+    rng = np.random.default_rng(41)
+    for case in range(50):
+        G = int(rng.choice([2, 3, 8, 16, 31, 64]))
+        Q = int(rng.choice([64, 100, 256, 300, 512, 700, 1024, 2048]))
+        B = int(rng.integers(2, 50))
+        N = int(rng.choice([3, 16, 64])) if Q < 1024 else 4
+        H = int(rng.integers(1, 9))
+        mode = int(rng.choice([0, 0, 1, 2]))
+        kw = dict(R_max=int(rng.choice([1, 2, 4, 4, 8])), gate_pfin=float(rng.choice([0.0, 0.3, 0.5])),
+                  gamma=float(rng.choice([0.64, 0.9, 1.0])), beta=float(rng.choice([-1.0, 14.67, 0.5, 2.0])),
+                  tie_heavy=bool(rng.integers(0, 2)), s_hi=int(rng.choice([64, 4096, 32768])),
+                  fill=float(rng.choice([0.2, 0.6, 0.95])))
+        if mode == 2:
+            kw["refresh_period"] = int(rng.integers(0, 5))
+        if kw["beta"] < 0:
+            kw.pop("beta")
+        S_greedy = int(rng.choice([0, G, 4 * G, 10 ** 6]))
+        cfg, init, arr = wl.random_case(int(rng.integers(1, 10 ** 6)), N=N, G=G, B=B, max_wait=Q, H=H, pred_mode=mode,
+                                        S_greedy=S_greedy, **kw)
+        hist = wl.output_history(cfg, 500) if mode == 2 else None
+        tag = f"horizon shapes {case}: N={N} G={G} B={B} Q={Q} H={H} mode={mode} S_greedy={S_greedy} {kw}"
+        _say(tag)
+        oc, r = br_oracle.OracleCluster(cfg, init, hist=hist), binding.Router(cfg, init, hist=hist)
+        for rnd in range(3):
+            if rnd:
+                _, _, arr = wl.random_case(int(rng.integers(1, 10 ** 6)), N=N, G=G, B=B, max_wait=Q, H=H, pred_mode=mode,
+                                           n_wait=max(1, Q // 3), **{k: v for k, v in kw.items() if k != "fill"})
+            ref = oc.route_step(arr, want_prep=True)
+            out = r.route_step(arr, advance=rnd % 2)
+            if rnd % 2 == 0:
+                compare_prep(ref, r.state(), f"{tag} r{rnd}")
+            compare_outputs(ref, out, cfg, f"{tag} r{rnd}")
+            oc.advance(1)
+            if rnd % 2 == 0:
+                r.advance(1)
+            compare_state(oc, r.state(), cfg, f"{tag} r{rnd}")
+        r.close()
+
+
 def test_edge_cases():
     # no arrivals at all (NULL), empty queue
     cfg, init, arr = wl.random_case(5, N=3, G=4, B=8, max_wait=32, H=0)
