@@ -164,6 +164,7 @@ class OracleCluster:
             self.kv[...] = init.kv
             self.rem[...] = init.rem
             if self.P:
+                assert init.pred is not None and np.shape(init.pred) == self.pred.shape, "init.pred: wrong shape"
                 self.pred[...] = init.pred
             used = np.arange(B)[None, None, :] < self.n[:, :, None]
             self.kv[~used] = 0
