@@ -164,8 +164,11 @@ class OracleCluster:
             self.kv[...] = init.kv
             self.rem[...] = init.rem
             if self.P:
-                assert init.pred is not None and np.shape(init.pred) == self.pred.shape, "init.pred: wrong shape"
-                self.pred[...] = init.pred
+                if init.pred is None:
+                    assert not np.any(init.n), "active requests need their prediction rows"
+                else:
+                    assert np.shape(init.pred) == self.pred.shape, "init.pred: wrong shape"
+                    self.pred[...] = init.pred
             used = np.arange(B)[None, None, :] < self.n[:, :, None]
             self.kv[~used] = 0
             self.rem[~used] = 0
