@@ -48,9 +48,13 @@ struct Log2E {
   static constexpr int v = E == 4 ? 2 : E == 8 ? 3 : E == 16 ? 4 : 5;
 };
 
-// One cluster's round on one wave.  `lds`: this wave's 3*E*64 + 72 words.
-template <int E, bool BRH, bool ADV>
-__device__ __forceinline__ void br_assign_body(const BrParams &p, const BrArr &a, const BrOut &o, int *lds, int inst) {
+// One cluster's round on one wave.  `lds`: this wave's 3*E*64 + 72 words.  COOP (queues of up to 2048):
+// the block has four waves; all of them sort the waiting set together (br_sort_desc_block4), then wave 0
+// runs the round alone, with the sorted keys read back from LDS.
+template <int E, bool BRH, bool ADV, bool COOP = false>
+__device__ __forceinline__ void br_assign_body(const BrParams &p, const BrArr &a, const BrOut &o, int *lds, int inst,
+                                               int w = 0) {
+  static_assert(!COOP || E == 32, "the four-wave sort covers 4 x 512 keys");
   constexpr int NP = E * BR_WAVE;
   constexpr int NH = BRH ? BR_HP + 1 : 1;
   constexpr int IDX_MASK = (1 << BR_IDX_BITS) - 1;
@@ -72,6 +76,37 @@ __device__ __forceinline__ void br_assign_body(const BrParams &p, const BrArr &a
   cnt = br_uniform(min(max(cnt, 0), a.arr_cap));
   const int qn = q0 + min(cnt, p.Q - q0);
   const int64_t qrow = (int64_t)inst * p.Q, arow = (int64_t)inst * a.arr_cap;
+
+  unsigned xk[E];
+  if constexpr (COOP) {
+    unsigned x8[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int i = w * 512 + j * BR_WAVE + lane;
+      unsigned key = 0;
+      if (i < qn) {
+        int s = i < q0 ? p.qs[qrow + i] : a.s[arow + (i - q0)];
+        s = min(max(s, 1), BR_MAX_S_DEV);
+        key = ((unsigned)s << BR_IDX_BITS) | (unsigned)(IDX_MASK - i);
+      }
+      x8[j] = key;
+      adm[i] = -1;
+      who[i] = -1;
+    }
+    if (qn > 512) {  // same for every wave of the block
+      br_sort_desc_block4(x8, skey, w, lane);
+    } else if (w == 0 && qn > 0) {  // everything is in wave 0's slice
+      int N2 = BR_WAVE;
+      while (N2 < qn) N2 <<= 1;
+      br_sort_desc<8>(x8, lane, N2);
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) skey[w * 512 + j * BR_WAVE + lane] = (int)x8[j];
+    __syncthreads();
+    if (w != 0) return;
+#pragma unroll
+    for (int j = 0; j < E; ++j) xk[j] = (unsigned)skey[j * BR_WAVE + lane];
+  }
 
   // first estimate of a newly admitted request when the library maintains c_hat (age 0)
   float c0 = 0.0f;
@@ -104,25 +139,26 @@ __device__ __forceinline__ void br_assign_body(const BrParams &p, const BrArr &a
 
   // ---- waiting set: keys (s << 11 | 2047 - arrival position) sorted in registers, descending;
   //      a copy goes to LDS for uniform look-ups
-  unsigned xk[E];
-#pragma unroll
-  for (int j = 0; j < E; ++j) {
-    const int i = j * BR_WAVE + lane;
-    unsigned key = 0;
-    if (i < qn) {
-      int s = i < q0 ? p.qs[qrow + i] : a.s[arow + (i - q0)];
-      s = min(max(s, 1), BR_MAX_S_DEV);
-      key = ((unsigned)s << BR_IDX_BITS) | (unsigned)(IDX_MASK - i);
-    }
-    xk[j] = key;
-    adm[i] = -1;
-    who[i] = -1;
-  }
   const bool run = S_tot > 0 && qn > 0;
-  if (run) {
-    int N2 = BR_WAVE;
-    while (N2 < qn) N2 <<= 1;
-    br_sort_desc<E>(xk, lane, N2);
+  if constexpr (!COOP) {
+#pragma unroll
+    for (int j = 0; j < E; ++j) {
+      const int i = j * BR_WAVE + lane;
+      unsigned key = 0;
+      if (i < qn) {
+        int s = i < q0 ? p.qs[qrow + i] : a.s[arow + (i - q0)];
+        s = min(max(s, 1), BR_MAX_S_DEV);
+        key = ((unsigned)s << BR_IDX_BITS) | (unsigned)(IDX_MASK - i);
+      }
+      xk[j] = key;
+      adm[i] = -1;
+      who[i] = -1;
+    }
+    if (run) {
+      int N2 = BR_WAVE;
+      while (N2 < qn) N2 <<= 1;
+      br_sort_desc<E>(xk, lane, N2);
+    }
   }
   int sv[E];
   unsigned alive = 0;
@@ -671,15 +707,18 @@ template <int E, bool BRH, bool ADV>
 __global__ __launch_bounds__(256, (BRH && E == 8) ? 4 : 1) void br_k_assign(BrParams p, BrArr a, BrOut o) {
   extern __shared__ int lds_all[];
   const int w = threadIdx.x >> 6;
-  br_assign_body<E, BRH, ADV>(p, a, o, lds_all + w * (3 * E * BR_WAVE + BR_WAVE + 8), (int)(blockIdx.x * (blockDim.x >> 6)) + w);
+  if constexpr (E == 32)  // one cluster per block, four waves for the sort
+    br_assign_body<E, BRH, ADV, true>(p, a, o, lds_all, (int)blockIdx.x, w);
+  else
+    br_assign_body<E, BRH, ADV>(p, a, o, lds_all + w * (3 * E * BR_WAVE + BR_WAVE + 8), (int)(blockIdx.x * (blockDim.x >> 6)) + w);
 }
 
 template <int E, bool BRH>
 static void br_launch_assign_one(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st) {
   // several single-wave clusters share a block so that the chip's per-CU block slots do not cap residency
-  const int wpb = E <= 8 ? 4 : 1;
+  const int wpb = E <= 8 ? 4 : 1;  // clusters per block
   const size_t lds = (size_t)wpb * (3 * E * BR_WAVE + BR_WAVE + 8) * sizeof(int);  // skey, adm, who, slots, win per wave
-  const dim3 grid((unsigned)((p.N + wpb - 1) / wpb)), block(BR_WAVE * wpb);
+  const dim3 grid((unsigned)((p.N + wpb - 1) / wpb)), block(E == 32 ? 4 * BR_WAVE : BR_WAVE * wpb);
   if (p.adv_t > 0)
     hipLaunchKernelGGL((br_k_assign<E, BRH, true>), grid, block, lds, st, p, a, o);
   else

@@ -86,3 +86,33 @@ template <int E>
 __device__ __forceinline__ void br_sort_desc(unsigned (&x)[E], int lane, int n2) {
   br_sort_levels<E, E * 64>(x, lane, n2);
 }
+
+// Sort of up to 2048 keys by the four waves of a block, 512 per wave (8 registers per lane):
+// position = w*512 + j*64 + lane, descending over the whole block.  Each wave sorts its own 512, then
+// two merge levels follow.  A level starts by comparing the two sorted halves mirrored (element i of
+// the first with element n-1-i of the second, through `buf` in LDS); after that every element of the
+// first half is at least every element of the second and each half is bitonic, so halves are finished
+// by plain half-cleaners: across waves at distance 512 (same position in the partner wave), inside a
+// wave by the register and lane stages above.  Every wave of the block must call this (block barriers).
+__device__ __forceinline__ void br_sort_block4_exchange(unsigned (&x)[8], int *buf, int w, int lane, int partner,
+                                                        bool mirrored, bool keep_max) {
+#pragma unroll
+  for (int j = 0; j < 8; ++j) buf[w * 512 + j * 64 + lane] = (int)x[j];
+  __syncthreads();
+  unsigned y[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j)
+    y[j] = (unsigned)(mirrored ? buf[partner * 512 + (7 - j) * 64 + (63 - lane)] : buf[partner * 512 + j * 64 + lane]);
+  __syncthreads();
+#pragma unroll
+  for (int j = 0; j < 8; ++j) x[j] = keep_max ? max(x[j], y[j]) : min(x[j], y[j]);
+}
+
+__device__ __forceinline__ void br_sort_desc_block4(unsigned (&x)[8], int *buf, int w, int lane) {
+  br_sort_desc<8>(x, lane, 512);
+  br_sort_block4_exchange(x, buf, w, lane, w ^ 1, true, (w & 1) == 0);   // pairs of waves: 1024 keys each
+  br_sort_merge<8, 512, 256>(x, lane, 512);
+  br_sort_block4_exchange(x, buf, w, lane, 3 - w, true, w < 2);          // all four: 2048 keys
+  br_sort_block4_exchange(x, buf, w, lane, w ^ 1, false, (w & 1) == 0);
+  br_sort_merge<8, 512, 256>(x, lane, 512);
+}
