@@ -50,129 +50,130 @@ __device__ __forceinline__ BrTailArgs br_tail_args() {
   return t;
 }
 
-template <int E>
-__device__ __forceinline__ void br_assign_epilogue(int inst, int lane, int q0, int qn, int cnt, const int *skey,
-                                                   const int *adm, int *who, int Lcur, int nn,
-                                                   const BrRoundCounts &rc, float c0) {
+// ---- pieces of the epilogue, each over GR blocks of 64 positions starting at block j0 ----
+
+// Commit of the admitted requests at sorted positions [j0*64, (j0+GR)*64) into their workers' dense
+// lists: what the group reads from the queue and the arrivals is requested before its first store.
+template <int GR>
+__device__ __forceinline__ void br_commit_group(const BrTailArgs &t, int inst, int lane, int j0, int q0, int qn,
+                                                const int *skey, const int *adm, int *who, float c0) {
   constexpr int IDX_MASK = (1 << BR_IDX_BITS) - 1;
-  const BrTailArgs t = br_tail_args();
+  const int G = t.G;
+  const int64_t qrow = (int64_t)inst * t.Q, arow = (int64_t)inst * t.arr_cap;
+  int64_t row[GR];
+  int idx[GR], kvv[GR], remv[GR];
+  float pr[GR][BR_HP];
+  bool ok[GR];
+#pragma unroll
+  for (int u = 0; u < GR; ++u) {
+    const int pos = (j0 + u) * BR_WAVE + lane;
+    ok[u] = false;
+    idx[u] = 0, kvv[u] = 0, remv[u] = 1, row[u] = 0;
+    if (pos < qn) {
+      const int ad = adm[pos];
+      if (ad >= 0) {
+        const int key = skey[pos];
+        idx[u] = IDX_MASK - (key & IDX_MASK);
+        const int g = ad >> 16, slot = ad & 0xffff;
+        if (g < G && slot < t.B && idx[u] < qn) {
+          ok[u] = true;
+          row[u] = ((int64_t)inst * G + g) * t.Bs + slot;
+          kvv[u] = key >> BR_IDX_BITS;
+          const bool old = idx[u] < q0;
+          remv[u] = old ? t.qo[qrow + idx[u]] : max(t.ao[arow + (idx[u] - q0)], 1);
+#pragma unroll
+          for (int q = 0; q < BR_HP; ++q)
+            if (q < t.Pq)
+              pr[u][q] = old ? t.qpred[(qrow + idx[u]) * t.Pq + q] : t.apred[(arow + (idx[u] - q0)) * t.Pq + q];
+          who[idx[u]] = g;
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < GR; ++u) {
+    if (ok[u]) {
+      t.kv[row[u]] = kvv[u];
+      t.rem[row[u]] = remv[u];
+#pragma unroll
+      for (int q = 0; q < BR_HP; ++q)
+        if (q < t.Pq) t.pred[row[u] * t.P + q] = pr[u][q];
+      if (t.P == 3 && t.Pq == 0) {  // maintained estimate: first query at age 0, nothing generated yet
+        t.pred[row[u] * 3] = c0;
+        t.pred[row[u] * 3 + 1] = 0.0f;
+        t.pred[row[u] * 3 + 2] = 0.0f;
+      }
+    }
+  }
+}
+
+// What the arrival positions [j0*64, (j0+GR)*64) hold and where they went.
+template <int GR>
+struct BrQueueGroup {
+  int wg[GR], id[GR], sq[GR], oq[GR];
+  float pr[GR][BR_HP];
+  bool keep[GR];
+};
+
+template <int GR>
+__device__ __forceinline__ void br_queue_load(const BrTailArgs &t, int inst, int lane, int j0, int q0, int qn,
+                                              const int *who, BrQueueGroup<GR> &v) {
+  const int64_t qrow = (int64_t)inst * t.Q, arow = (int64_t)inst * t.arr_cap;
+#pragma unroll
+  for (int u = 0; u < GR; ++u) {
+    const int i = (j0 + u) * BR_WAVE + lane;
+    const bool in = i < qn, old = i < q0;
+    v.wg[u] = in ? who[i] : -1;
+    v.id[u] = -1;
+    if (in) v.id[u] = old ? t.qid[qrow + i] : (t.aid ? t.aid[arow + (i - q0)] : i - q0);
+    v.keep[u] = in && v.wg[u] < 0;
+    v.sq[u] = 1, v.oq[u] = 1;
+    if (v.keep[u]) {
+      v.sq[u] = old ? t.qs[qrow + i] : t.as[arow + (i - q0)];
+      v.oq[u] = old ? t.qo[qrow + i] : t.ao[arow + (i - q0)];
+#pragma unroll
+      for (int q = 0; q < BR_HP; ++q)
+        if (q < t.Pq) v.pr[u][q] = old ? t.qpred[(qrow + i) * t.Pq + q] : t.apred[(arow + (i - q0)) * t.Pq + q];
+    }
+  }
+}
+
+// Outputs of those positions in arrival order, and their deferred requests to queue positions `kept`
+// onwards (order preserved); `kept` moves on by the number stored.
+template <int GR>
+__device__ __forceinline__ void br_queue_store(const BrTailArgs &t, int inst, int lane, int j0, int q0,
+                                               const BrQueueGroup<GR> &v, int &kept) {
+  const int64_t qrow = (int64_t)inst * t.Q;
+#pragma unroll
+  for (int u = 0; u < GR; ++u) {
+    const int i = (j0 + u) * BR_WAVE + lane;
+    if ((j0 + u) * BR_WAVE < t.Q) {
+      if (i < t.Q) {
+        if (t.assign) t.assign[qrow + i] = v.wg[u];
+        if (t.assign_id) t.assign_id[qrow + i] = v.id[u];
+      }
+      const unsigned long long bal = br_ballot(v.keep[u]);
+      const int ni = kept + br_rank_below(bal);
+      if (v.keep[u] && (ni != i || i >= q0)) {
+        t.qs[qrow + ni] = min(max(v.sq[u], 1), BR_MAX_S_DEV);
+        t.qo[qrow + ni] = max(v.oq[u], 1);
+        t.qid[qrow + ni] = v.id[u];
+#pragma unroll
+        for (int q = 0; q < BR_HP; ++q)
+          if (q < t.Pq) t.qpred[(qrow + ni) * t.Pq + q] = v.pr[u][q];
+      }
+      kept += __builtin_popcountll(bal);
+    }
+  }
+}
+
+// Worker state and the statistics of the round (one wave).
+__device__ __forceinline__ void br_write_state(const BrTailArgs &t, int inst, int lane, int q0, int qn, int cnt, int kept,
+                                               int Lcur, int nn, const BrRoundCounts &rc, bool store_workers = true) {
   const int G = t.G;
   const bool act = lane < G;
   const int64_t wrow = (int64_t)inst * G + lane;
-  const int64_t qrow = (int64_t)inst * t.Q, arow = (int64_t)inst * t.arr_cap;
-  const int admitted = rc.admitted;
-  // ---- commit the admitted requests into their workers' dense lists, GR blocks of sorted positions
-  //      at a time: what a group reads from the queue and the arrivals is requested before its first store
-  constexpr int GR = E < 4 ? E : 4;
-  if (admitted > 0) {
-#pragma unroll
-    for (int j0 = 0; j0 < E; j0 += GR) {
-      if (j0 * BR_WAVE < qn) {
-        int64_t row[GR];
-        int idx[GR], kvv[GR], remv[GR];
-        float pr[GR][BR_HP];
-        bool ok[GR];
-#pragma unroll
-        for (int u = 0; u < GR; ++u) {
-          const int pos = (j0 + u) * BR_WAVE + lane;
-          ok[u] = false;
-          idx[u] = 0, kvv[u] = 0, remv[u] = 1, row[u] = 0;
-          if (pos < qn) {
-            const int ad = adm[pos];
-            if (ad >= 0) {
-              const int key = skey[pos];
-              idx[u] = IDX_MASK - (key & IDX_MASK);
-              const int g = ad >> 16, slot = ad & 0xffff;
-              if (g < G && slot < t.B && idx[u] < qn) {
-                ok[u] = true;
-                row[u] = ((int64_t)inst * G + g) * t.Bs + slot;
-                kvv[u] = key >> BR_IDX_BITS;
-                const bool old = idx[u] < q0;
-                remv[u] = old ? t.qo[qrow + idx[u]] : max(t.ao[arow + (idx[u] - q0)], 1);
-#pragma unroll
-                for (int q = 0; q < BR_HP; ++q)
-                  if (q < t.Pq)
-                    pr[u][q] = old ? t.qpred[(qrow + idx[u]) * t.Pq + q] : t.apred[(arow + (idx[u] - q0)) * t.Pq + q];
-                who[idx[u]] = g;
-              }
-            }
-          }
-        }
-#pragma unroll
-        for (int u = 0; u < GR; ++u) {
-          if (ok[u]) {
-            t.kv[row[u]] = kvv[u];
-            t.rem[row[u]] = remv[u];
-#pragma unroll
-            for (int q = 0; q < BR_HP; ++q)
-              if (q < t.Pq) t.pred[row[u] * t.P + q] = pr[u][q];
-            if (t.P == 3 && t.Pq == 0) {  // maintained estimate: first query at age 0, nothing generated yet
-              t.pred[row[u] * 3] = c0;
-              t.pred[row[u] * 3 + 1] = 0.0f;
-              t.pred[row[u] * 3 + 2] = 0.0f;
-            }
-          }
-        }
-      }
-    }
-  }
-  br_wave_sync();
-
-  // ---- outputs in arrival order; the queue keeps the deferred requests, order preserved.
-  // Blocks of 64 entries are taken GR at a time: everything the group reads is requested before its
-  // first store, so the loads of a group overlap (a 2048-entry queue is 32 blocks, each a round trip to
-  // memory otherwise).  In place: a deferred entry moves to a position at or below its own, inside or
-  // before its group, and later groups read only beyond it.
-  int kept = 0;
-#pragma unroll
-  for (int j0 = 0; j0 < E; j0 += GR) {
-    if (j0 * BR_WAVE < t.Q) {
-      int wg[GR], id[GR], sq[GR], oq[GR];
-      float pr[GR][BR_HP];
-      bool keep[GR];
-#pragma unroll
-      for (int u = 0; u < GR; ++u) {
-        const int i = (j0 + u) * BR_WAVE + lane;
-        const bool in = i < qn, old = i < q0;
-        wg[u] = in ? who[i] : -1;
-        id[u] = -1;
-        if (in) id[u] = old ? t.qid[qrow + i] : (t.aid ? t.aid[arow + (i - q0)] : i - q0);
-        keep[u] = in && wg[u] < 0;
-        sq[u] = 1, oq[u] = 1;
-        if (keep[u]) {
-          sq[u] = old ? t.qs[qrow + i] : t.as[arow + (i - q0)];
-          oq[u] = old ? t.qo[qrow + i] : t.ao[arow + (i - q0)];
-#pragma unroll
-          for (int q = 0; q < BR_HP; ++q)
-            if (q < t.Pq) pr[u][q] = old ? t.qpred[(qrow + i) * t.Pq + q] : t.apred[(arow + (i - q0)) * t.Pq + q];
-        }
-      }
-#pragma unroll
-      for (int u = 0; u < GR; ++u) {
-        const int i = (j0 + u) * BR_WAVE + lane;
-        if ((j0 + u) * BR_WAVE < t.Q) {
-          if (i < t.Q) {
-            if (t.assign) t.assign[qrow + i] = wg[u];
-            if (t.assign_id) t.assign_id[qrow + i] = id[u];
-          }
-          const unsigned long long bal = br_ballot(keep[u]);
-          const int ni = kept + br_rank_below(bal);
-          if (keep[u] && (ni != i || i >= q0)) {
-            t.qs[qrow + ni] = min(max(sq[u], 1), BR_MAX_S_DEV);
-            t.qo[qrow + ni] = max(oq[u], 1);
-            t.qid[qrow + ni] = id[u];
-#pragma unroll
-            for (int q = 0; q < BR_HP; ++q)
-              if (q < t.Pq) t.qpred[(qrow + ni) * t.Pq + q] = pr[u][q];
-          }
-          kept += __builtin_popcountll(bal);
-        }
-      }
-    }
-  }
-
-  // ---- state and statistics
-  if (act) {
+  if (act && store_workers) {
     t.L[wrow] = Lcur;
     t.n[wrow] = nn;
   }
@@ -188,7 +189,7 @@ __device__ __forceinline__ void br_assign_epilogue(int inst, int lane, int q0, i
   if (lane == 0) {
     t.qlen[inst] = kept;
     if (t.stats) {
-      BR_STAT(t, inst, 0) = admitted;
+      BR_STAT(t, inst, 0) = rc.admitted;
       BR_STAT(t, inst, 1) = kept;
       BR_STAT(t, inst, 2) = cnt - (qn - q0);
       BR_STAT(t, inst, 3) = rc.stage1;
@@ -203,6 +204,75 @@ __device__ __forceinline__ void br_assign_epilogue(int inst, int lane, int q0, i
       for (int k = 12; k < 16; ++k) BR_STAT(t, inst, k) = 0;
     }
   }
+}
+
+// The epilogue on the wave that ran the round.  Blocks are taken GR at a time so that the loads of a
+// group overlap (each block is a round trip to memory otherwise).  The queue is compacted in place: a
+// deferred entry moves to a position at or below its own, inside or before its group, and later groups
+// read only beyond it.
+template <int E>
+__device__ __forceinline__ void br_assign_epilogue(int inst, int lane, int q0, int qn, int cnt, const int *skey,
+                                                   const int *adm, int *who, int Lcur, int nn,
+                                                   const BrRoundCounts &rc, float c0) {
+  const BrTailArgs t = br_tail_args();
+  constexpr int GR = E < 4 ? E : 4;
+  if (rc.admitted > 0) {
+#pragma unroll
+    for (int j0 = 0; j0 < E; j0 += GR)
+      if (j0 * BR_WAVE < qn) br_commit_group<GR>(t, inst, lane, j0, q0, qn, skey, adm, who, c0);
+  }
+  br_wave_sync();
+  int kept = 0;
+#pragma unroll
+  for (int j0 = 0; j0 < E; j0 += GR) {
+    if (j0 * BR_WAVE < t.Q) {
+      BrQueueGroup<GR> v;
+      br_queue_load<GR>(t, inst, lane, j0, q0, qn, who, v);
+      br_queue_store<GR>(t, inst, lane, j0, q0, v, kept);
+    }
+  }
+  br_write_state(t, inst, lane, q0, qn, cnt, kept, Lcur, nn, rc);
+}
+
+// The epilogue on the four waves of a block (queues of up to 2048 entries): wave w owns the sorted
+// positions and the arrival positions [w*512, (w+1)*512).  Every wave requests all it will read of the
+// queue before the barrier that precedes the first store, so the in-place compaction needs no order
+// between waves; the counts of deferred requests per wave go through `sh` (4 words of LDS).
+// With `share_workers` wave 0's per-worker (load, count) are handed to every wave (for a decode step split
+// among the waves) and wave 0 leaves their store to that step.
+__device__ __forceinline__ void br_assign_epilogue_block4(int inst, int lane, int w, int q0, int qn, int cnt, int *skey,
+                                                          const int *adm, int *who, int *sh, int &Lcur, int &nn,
+                                                          const BrRoundCounts &rc, float c0, bool share_workers) {
+  const BrTailArgs t = br_tail_args();
+  __syncthreads();  // the round is over: adm[] is complete
+  br_commit_group<4>(t, inst, lane, w * 8, q0, qn, skey, adm, who, c0);
+  br_commit_group<4>(t, inst, lane, w * 8 + 4, q0, qn, skey, adm, who, c0);
+  __syncthreads();  // who[] is complete
+  BrQueueGroup<4> va, vb;
+  br_queue_load<4>(t, inst, lane, w * 8, q0, qn, who, va);
+  br_queue_load<4>(t, inst, lane, w * 8 + 4, q0, qn, who, vb);
+  int mine = 0;
+#pragma unroll
+  for (int u = 0; u < 4; ++u) mine += __builtin_popcountll(br_ballot(va.keep[u])) + __builtin_popcountll(br_ballot(vb.keep[u]));
+  // the loaded values must have arrived before any wave stores
+  asm volatile("" ::"v"(va.sq[0]), "v"(va.sq[1]), "v"(va.sq[2]), "v"(va.sq[3]), "v"(vb.sq[0]), "v"(vb.sq[1]), "v"(vb.sq[2]),
+               "v"(vb.sq[3])
+               : "memory");
+  __builtin_amdgcn_s_waitcnt(0);
+  if (lane == 0) sh[w] = mine;
+  if (share_workers && w == 0) skey[lane] = Lcur, skey[BR_WAVE + lane] = nn;  // the sorted keys are no longer needed
+  __syncthreads();
+  if (share_workers) Lcur = skey[lane], nn = skey[BR_WAVE + lane];
+  int kept = 0, total = 0;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const int c = sh[k];
+    kept += k < w ? c : 0;
+    total += c;
+  }
+  br_queue_store<4>(t, inst, lane, w * 8, q0, va, kept);
+  br_queue_store<4>(t, inst, lane, w * 8 + 4, q0, vb, kept);
+  if (w == 0) br_write_state(t, inst, lane, q0, qn, cnt, total, Lcur, nn, rc, !share_workers);
 }
 
 // Late copy of the whole parameter block from the kernel-argument segment (same reason as above).
@@ -220,18 +290,19 @@ __device__ __forceinline__ BrParams br_late_params() {
 // the stand-alone advance kernel) over the cluster's G lists in (list, 256-slot chunk) units, UB units
 // requested before the first is used.  `Lcur`, `nn`: load and list length of worker `lane` after the round.
 template <int UB, bool BRH>
-__device__ __forceinline__ void br_advance_cluster(int inst, int lane, int Lcur, int nn) {
+__device__ __forceinline__ void br_advance_cluster(int inst, int lane, int Lcur, int nn, int g0 = 0, int g1 = 64) {
   const BrParams p = br_late_params();
   const int t = p.adv_t;
   br_wave_sync();  // the round's own writes into the lists are read back below
-  const int G = p.G, NC = (p.Bs + 255) >> 8, U = G * NC;
-  const int64_t row0 = (int64_t)__builtin_amdgcn_readfirstlane(inst) * G;  // scalar: list bases stay in SGPRs
+  const int G = min(p.G, g1), NC = (p.Bs + 255) >> 8, U = max(G - g0, 0) * NC;  // lists [g0, G) are this wave's
+  const int64_t row0 = (int64_t)__builtin_amdgcn_readfirstlane(inst) * p.G;  // scalar: list bases stay in SGPRs
+  const int64_t rowa = row0 + g0;
   int dLw = 0, nw = nn;     // lane g: load change and new length of worker g
   int kept = 0, gone = 0;   // running state of the list in progress: survivors, kv that left
-  int gl = 0, cl = 0, gp = 0, cp = 0;  // (list, chunk) cursors of the load and the update pass
-  const int32_t *kl = p.kv + row0 * p.Bs, *rl = p.rem + row0 * p.Bs;  // list the load pass is at
-  int32_t *kw = p.kv + row0 * p.Bs, *rw = p.rem + row0 * p.Bs;        // list the update pass is at
-  float *pw = p.pred + row0 * p.Bs * p.P;
+  int gl = g0, cl = 0, gp = g0, cp = 0;  // (list, chunk) cursors of the load and the update pass
+  const int32_t *kl = p.kv + rowa * p.Bs, *rl = p.rem + rowa * p.Bs;  // list the load pass is at
+  int32_t *kw = p.kv + rowa * p.Bs, *rw = p.rem + rowa * p.Bs;        // list the update pass is at
+  float *pw = p.pred + rowa * p.Bs * p.P;
   for (int u0 = 0; u0 < U; u0 += UB) {
     int4 kv[UB], rem[UB];
 #pragma unroll
@@ -253,7 +324,7 @@ __device__ __forceinline__ void br_advance_cluster(int inst, int lane, int Lcur,
       }
     }
   }
-  if (lane < G) {
+  if (lane >= g0 && lane < G) {
     p.L[row0 + lane] = Lcur + dLw;
     p.n[row0 + lane] = nw;
   }

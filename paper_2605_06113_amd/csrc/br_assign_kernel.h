@@ -49,8 +49,8 @@ struct Log2E {
 };
 
 // One cluster's round on one wave.  `lds`: this wave's 3*E*64 + 72 words.  COOP (queues of up to 2048):
-// the block has four waves; all of them sort the waiting set together (br_sort_desc_block4), then wave 0
-// runs the round alone, with the sorted keys read back from LDS.
+// the block has four waves; all of them sort the waiting set together (br_sort_desc_block4), wave 0 runs
+// the round alone with the sorted keys read back from LDS, and all four share the epilogue and the decode step.
 template <int E, bool BRH, bool ADV, bool COOP = false>
 __device__ __forceinline__ void br_assign_body(const BrParams &p, const BrArr &a, const BrOut &o, int *lds, int inst,
                                                int w = 0) {
@@ -76,6 +76,12 @@ __device__ __forceinline__ void br_assign_body(const BrParams &p, const BrArr &a
   cnt = br_uniform(min(max(cnt, 0), a.arr_cap));
   const int qn = q0 + min(cnt, p.Q - q0);
   const int64_t qrow = (int64_t)inst * p.Q, arow = (int64_t)inst * a.arr_cap;
+
+  // first estimate of a newly admitted request when the library maintains c_hat (age 0)
+  float c0 = 0.0f;
+  if constexpr (BRH) {
+    if (p.pred_mode == 2) c0 = br_survival(p, 0);
+  }
 
   unsigned xk[E];
   if constexpr (COOP) {
@@ -103,15 +109,18 @@ __device__ __forceinline__ void br_assign_body(const BrParams &p, const BrArr &a
 #pragma unroll
     for (int j = 0; j < 8; ++j) skey[w * 512 + j * BR_WAVE + lane] = (int)x8[j];
     __syncthreads();
-    if (w != 0) return;
+    if (w != 0) {  // waves 1-3 wait for the round, then take their share of the epilogue and the decode step
+      int Lw = 0, nw = 0;
+      BrRoundCounts none = {};
+      br_assign_epilogue_block4(inst, lane, w, q0, qn, cnt, skey, adm, who, slots, Lw, nw, none, c0, ADV);
+      if constexpr (ADV) {
+        const int per = (G + 3) >> 2;
+        br_advance_cluster<4, BRH>(inst, lane, Lw, nw, min(w * per, G), min(w * per + per, G));
+      }
+      return;
+    }
 #pragma unroll
     for (int j = 0; j < E; ++j) xk[j] = (unsigned)skey[j * BR_WAVE + lane];
-  }
-
-  // first estimate of a newly admitted request when the library maintains c_hat (age 0)
-  float c0 = 0.0f;
-  if constexpr (BRH) {
-    if (p.pred_mode == 2) c0 = br_survival(p, 0);
   }
 
   // ---- worker state, one worker per lane
@@ -165,7 +174,7 @@ __device__ __forceinline__ void br_assign_body(const BrParams &p, const BrArr &a
 #pragma unroll
   for (int j = 0; j < E; ++j) {
     const int pos = j * BR_WAVE + lane;
-    skey[pos] = (int)xk[j];
+    if constexpr (!COOP) skey[pos] = (int)xk[j];  // (already there after the four-wave sort)
     sv[j] = (int)(xk[j] >> BR_IDX_BITS);
     if (pos < qn) alive |= 1u << j;
   }
@@ -696,8 +705,14 @@ __device__ __forceinline__ void br_assign_body(const BrParams &p, const BrArr &a
   rc.guard = guard;
   rc.wdrop = wdrop;
   rc.I_before = I_before;
-  br_assign_epilogue<E>(inst, lane, q0, qn, cnt, skey, adm, who, Lh[0], nn, rc, c0);
-  if constexpr (ADV) br_advance_cluster<(BRH ? 4 : 8), BRH>(inst, lane, Lh[0], nn);  // BR-H units carry the estimator code: fewer unrolled
+  if constexpr (COOP) {
+    int Lw = Lh[0];
+    br_assign_epilogue_block4(inst, lane, 0, q0, qn, cnt, skey, adm, who, slots, Lw, nn, rc, c0, ADV);
+    if constexpr (ADV) br_advance_cluster<4, BRH>(inst, lane, Lw, nn, 0, min((G + 3) >> 2, G));
+  } else {
+    br_assign_epilogue<E>(inst, lane, q0, qn, cnt, skey, adm, who, Lh[0], nn, rc, c0);
+    if constexpr (ADV) br_advance_cluster<(BRH ? 4 : 8), BRH>(inst, lane, Lh[0], nn);  // BR-H units carry the estimator code: fewer unrolled
+  }
 }
 
 // every wave of the block owns one cluster and its own slice of LDS; waves never meet at a barrier
