@@ -20,8 +20,9 @@
  *  - Every entry point returns BR_OK or a negative error code; nothing is printed,
  *    nothing aborts.  Data-dependent conditions (a full waiting queue, a worker that
  *    can take nothing) are not errors: they are counted in the stats block.
- *  - Limits: G <= 64, B <= 1024, max_wait <= 2048, H <= 8, R_max <= 8, prefill length
- *    in [1, 32768] (values outside are clamped on arrival), per-worker load < 2^25.
+ *  - Limits: G <= 64, B <= 1024, max_wait <= 2048, H <= 128 (H <= 8 with pred_mode 0),
+ *    R_max <= 8, prefill length in [1, 32768] (values outside are clamped on arrival),
+ *    per-worker load < 2^25.
  */
 #ifndef BR_H
 #define BR_H
@@ -35,7 +36,7 @@ extern "C" {
 #define BR_MAX_G 64
 #define BR_MAX_B 1024
 #define BR_MAX_WAIT 2048
-#define BR_MAX_H 8
+#define BR_MAX_H 128
 #define BR_MAX_RMAX 8
 #define BR_MAX_S 32768
 #define BR_NSTATS 16
@@ -84,7 +85,9 @@ typedef struct {
   int32_t G;               /* DP workers per cluster, 1..64 */
   int32_t B;               /* max concurrent requests per worker (slot limit), 1..1024 */
   int32_t max_wait;        /* capacity of the waiting queue per cluster, 1..2048 */
-  int32_t H;               /* lookahead horizon; 0 selects BR-0 (exact integers) */
+  int32_t H;               /* lookahead horizon, 0..128; 0 selects BR-0 (exact integers); beyond 8 the
+                              per-offset state moves from registers to on-chip memory (same results,
+                              other kernels) and pred_mode must be 1 or 2 */
   int32_t S_greedy;        /* Stage 1 runs while total free slots > S_greedy; >= 0 */
   int32_t R_max;           /* Stage-2 candidate window and subset size, 1..8 */
   int32_t token_watermark; /* 0 = off; else a request is admissible on g only if L_g + s <= watermark */

@@ -29,6 +29,7 @@ bool config_ok(const br_config *c) {
   if (c->R_max < 1 || c->R_max > BR_MAX_RMAX || c->S_greedy < 0) return false;
   if (c->token_watermark < 0 || c->token_cap < 0) return false;
   if (c->pred_mode < 0 || c->pred_mode > 2) return false;
+  if (c->H > BR_HP && c->pred_mode == 0) return false;  // a hazard per offset is carried for short horizons only
   if (c->pred_mode == 2) {
     if (c->H == 0 || !c->hist || !c->hist_sum || c->hist_n < 1 || c->hist_n > (1 << 20) || c->refresh_period < 1)
       return false;
@@ -39,7 +40,9 @@ bool config_ok(const br_config *c) {
   return true;
 }
 
-void make_layout(const br_config &c, br_layout *l) {
+// `dl`: byte offset of the discount table that horizons beyond BR_HP keep in the workspace (after the
+// arrays of the public layout), or 0
+void make_layout(const br_config &c, br_layout *l, uint64_t *dl = nullptr) {
   const uint64_t N = (uint64_t)c.n_inst, G = (uint64_t)c.G, Q = (uint64_t)c.max_wait, H1 = (uint64_t)c.H + 1;
   const uint64_t P = (uint64_t)pred_width(c), Pq = (uint64_t)queue_pred_width(c);
   const uint64_t Bs = ((uint64_t)c.B + 3u) & ~(uint64_t)3u;
@@ -63,6 +66,8 @@ void make_layout(const br_config &c, br_layout *l) {
   l->Mh = take(N * H1);
   l->mh = take(N * G * H1);
   l->minm = take(N * G);
+  const uint64_t dl_at = c.H > BR_HP ? take((uint64_t)BR_HS(c.H)) : 0;
+  if (dl) *dl = dl_at;
   l->total_bytes = off;
   l->B_stride = (int32_t)Bs;
   l->P = (int32_t)P;
@@ -135,7 +140,8 @@ int32_t br_init(const br_config *cfg, const br_init_state *init, br_ctx **out) {
   if (!out || !config_ok(cfg) || !cfg->workspace) return BR_EINVAL;
   if (((uintptr_t)cfg->workspace & 255u) != 0) return BR_EINVAL;
   br_layout l;
-  make_layout(*cfg, &l);
+  uint64_t dl_at = 0;
+  make_layout(*cfg, &l, &dl_at);
   if (cfg->workspace_bytes < l.total_bytes) return BR_ENOMEM;
   const int P = pred_width(*cfg);
   if (init && (!init->n || !init->kv || !init->rem || (P > 0 && !init->pred))) return BR_EINVAL;
@@ -178,7 +184,7 @@ int32_t br_init(const br_config *cfg, const br_init_state *init, br_ctx **out) {
   volatile float acc = 0.0f, dh = 1.0f;
   for (int h = 0; h <= cfg->H; ++h) {
     if (h > 0) dh = dh * cfg->gamma;
-    p.d[h] = dh;
+    if (h <= BR_HP) p.d[h] = dh;
     acc = acc + dh;
   }
   volatile float aD = cfg->alpha * acc;
@@ -200,8 +206,10 @@ int32_t br_init(const br_config *cfg, const br_init_state *init, br_ctx **out) {
   p.Mh = (int32_t *)(base + l.Mh);
   p.mh = (int32_t *)(base + l.mh);
   p.minm = (int32_t *)(base + l.minm);
+  p.dl = dl_at ? (const float *)(base + dl_at) : nullptr;
 
   int32_t rc = enqueue(ctx, BR_K_INIT, [&] { br_launch_clear(p, ctx->st); });
+  if (rc == BR_OK && p.dl) rc = enqueue(ctx, BR_K_INIT, [&] { br_launch_discounts(p, cfg->gamma, ctx->st); });
   if (rc == BR_OK && init)
     rc = enqueue(ctx, BR_K_INIT, [&] { br_launch_load_init(p, init->n, init->kv, init->rem, init->pred, ctx->st); });
   if (rc != BR_OK) {

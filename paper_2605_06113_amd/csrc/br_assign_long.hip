@@ -1,0 +1,365 @@
+// Two-stage assignment of one scheduling round for horizons beyond the offsets the register kernel
+// carries (Appendix, Alg. BR-H; H up to 128, the deployed value of Sec. 6 is 80), one wavefront per
+// cluster.
+//
+// The round is the plain loop of Alg. BR-H: Stage 1 gives the worker with the most free slots (then
+// the lightest, then the lowest index) its best single request while free capacity exceeds S_greedy;
+// Stage 2 pops workers by (free slots, horizon-min margin), searches the subsets of the top-R_max window
+// and falls back to the single best request when no subset scores above zero.
+//
+// What differs from the short-horizon kernel is where the per-offset state lives:
+//   - the step-start projections L_g(k+h) stay in LDS, sL[h][g] (row stride 65 words, so that both
+//     "lane = worker" and "lane = offset" reads spread over the banks) and are never rewritten: an
+//     admission adds its length at every offset (constant-s approximation of Sec. 4.1), so worker g's
+//     current projection is sL[h][g] + add_g with one register add_g per lane;
+//   - the envelope M_h and the margins of the worker in hand are LDS arrays maintained with lanes
+//     mapped to offsets;
+//   - a score walks the offsets in order with margins and discounts broadcast from LDS, four per load,
+//     for four waiting requests (or four subset sums) per lane at a time (br_scoreh_long).
+// Waiting set, sticky binding, epilogue and the optional decode steps are those of the short-horizon
+// kernel (br_sort.h, br_assign_common.h).
+#include "br_device.h"
+#include "br_launch.h"
+#include "br_sort.h"
+#include "br_assign_common.h"
+
+#define BR_LSTRIDE 65  // words between offsets in sL
+
+template <int E, bool ADV>
+__global__ __launch_bounds__(64) void br_k_assign_long(BrParams p, BrArr a, BrOut o) {
+  extern __shared__ int lds[];
+  constexpr int NP = E * BR_WAVE;
+  constexpr int IDX_MASK = (1 << BR_IDX_BITS) - 1;
+  const int inst = (int)blockIdx.x;
+  if (inst >= p.N) return;
+  const int H1 = p.H + 1, HS = BR_HS(p.H);
+  int *skey = lds;                  // [NP] sorted keys (s << 11 | 2047 - arrival position)
+  int *adm = lds + NP;              // [NP] by sorted position: worker << 16 | slot, or -1
+  int *who = lds + 2 * NP;          // [NP] by arrival position: worker, or -1
+  int *win = lds + 3 * NP;          // [8]  Stage-2 candidate window (16-byte aligned), padded to 64
+  int *sM = win + BR_WAVE;          // [HS] envelope M_h
+  int *smg = sM + HS;               // [HS] margins of the worker in hand
+  float *sd = (float *)(smg + HS);  // [HS] discounts, zero beyond H
+  int *sL = smg + 2 * HS;           // [H1][65] step-start projections
+
+  const int lane = br_lane();
+  const int G = p.G;
+  const int q0 = br_uniform(min(max(p.qlen[inst], 0), p.Q));
+  int cnt = a.count ? a.count[inst] : 0;
+  cnt = br_uniform(min(max(cnt, 0), a.arr_cap));
+  const int qn = q0 + min(cnt, p.Q - q0);
+  const int64_t qrow = (int64_t)inst * p.Q, arow = (int64_t)inst * a.arr_cap;
+
+  float c0 = 0.0f;  // first estimate of a newly admitted request when the library maintains c_hat
+  if (p.pred_mode == 2) c0 = br_survival(p, 0);
+
+  // ---- worker state: lane g holds worker g
+  const bool act = lane < G;
+  const int64_t wrow = (int64_t)inst * G + lane;
+  int nn = act ? min(max(p.n[wrow], 0), p.B) : p.B;
+  int cap = p.B - nn;
+  int Lcur = act ? p.Lh[wrow * H1] : BR_LOW;  // L_g(k) + what this round admits
+  int add = 0;                                // tokens admitted to this lane's worker in this round
+  for (int h0 = 0; h0 < HS; h0 += BR_WAVE) {
+    const int h = h0 + lane;
+    if (h < HS) {
+      sM[h] = h < H1 ? p.Mh[(int64_t)inst * H1 + h] : 0;
+      sd[h] = p.dl[h];
+      smg[h] = 0;
+    }
+  }
+  for (int g = 0; g < BR_WAVE; ++g) {  // rows of workers beyond G read as "no worker"
+    for (int h0 = 0; h0 < H1; h0 += BR_WAVE) {
+      const int h = h0 + lane;
+      if (h < H1) sL[h * BR_LSTRIDE + g] = g < G ? p.Lh[((int64_t)inst * G + g) * H1 + h] : BR_LOW;
+    }
+  }
+  int S_tot = br_wave_sum(cap);
+  long long I_before = 0;
+  if (o.stats) {
+    const int L0 = act ? Lcur : 0;
+    const long long sumL = ((long long)br_wave_sum(L0 >> 16) << 16) + br_wave_sum(L0 & 0xffff);
+    I_before = (long long)G * br_wave_max(Lcur) - sumL;
+  }
+
+  // ---- waiting set, sorted in registers (largest prefill first, arrival order among equals)
+  const bool run = S_tot > 0 && qn > 0;
+  unsigned xk[E];
+#pragma unroll
+  for (int j = 0; j < E; ++j) {
+    const int i = j * BR_WAVE + lane;
+    unsigned key = 0;
+    if (i < qn) {
+      int s = i < q0 ? p.qs[qrow + i] : a.s[arow + (i - q0)];
+      s = min(max(s, 1), BR_MAX_S_DEV);
+      key = ((unsigned)s << BR_IDX_BITS) | (unsigned)(IDX_MASK - i);
+    }
+    xk[j] = key;
+    adm[i] = -1;
+    who[i] = -1;
+  }
+  if (run) {
+    int N2 = BR_WAVE;
+    while (N2 < qn) N2 <<= 1;
+    br_sort_desc<E>(xk, lane, N2);
+  }
+  int sv[E];
+  unsigned alive = 0;
+#pragma unroll
+  for (int j = 0; j < E; ++j) {
+    const int pos = j * BR_WAVE + lane;
+    skey[pos] = (int)xk[j];
+    sv[j] = (int)(xk[j] >> BR_IDX_BITS);
+    if (pos < qn) alive |= 1u << j;
+  }
+  br_wave_sync();
+
+  int n_alive = qn;
+  int stage1 = 0, pops = 0, guard = 0, wdrop = 0, admitted = 0;
+
+  // margins of worker g against the current envelope, into smg (lanes = offsets)
+  auto margins_of = [&](int g) {
+    const int ag = __builtin_amdgcn_readlane(add, g);
+    for (int h0 = 0; h0 < H1; h0 += BR_WAVE) {
+      const int h = h0 + lane;
+      if (h < H1) smg[h] = max(sM[h] - (sL[h * BR_LSTRIDE + g] + ag), 0);
+    }
+    br_wave_sync();
+  };
+
+  // horizon-min margin of the worker each lane holds
+  auto lane_minm = [&]() {
+    int mn = INT32_MAX;
+    for (int h = 0; h < H1; ++h) mn = min(mn, max(sM[h] - (sL[h * BR_LSTRIDE + lane] + add), 0));
+    return mn;
+  };
+
+  // argmax_i F_g({i}) over alive, admissible requests against the margins in smg (lowest sorted
+  // position on ties); false when no request is admissible
+  auto pick_single = [&](int room, int &pos, int &swin) -> bool {
+    int bk = BR_KEY_NONE, bp = INT32_MAX;
+#pragma unroll
+    for (int j0 = 0; j0 < E; j0 += 4) {
+      if (j0 * BR_WAVE < qn) {
+        const int dv[4] = {sv[j0], sv[j0 + 1], sv[j0 + 2], sv[j0 + 3]};
+        float Fv[4];
+        br_scoreh_long<4>(p.aD, p.beta, smg, sd, HS, dv, Fv);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int j = j0 + u;
+          const bool ok = ((alive >> j) & 1u) && dv[u] <= room;
+          const int key = ok ? br_ord(Fv[u]) : BR_KEY_NONE;
+          if (key > bk) {  // positions rise with j within a lane: the first best stays
+            bk = key;
+            bp = j * BR_WAVE + lane;
+          }
+        }
+      }
+    }
+    const int km = br_wave_max(bk);
+    if (km == BR_KEY_NONE) return false;
+    pos = br_wave_min(bk == km ? bp : INT32_MAX);
+    swin = br_uniform(skey[pos] >> BR_IDX_BITS);
+    return true;
+  };
+
+  // sticky binding of the request at sorted position pos to worker g
+  auto bind = [&](int pos, int g, int slot) {
+    adm[pos] = (g << 16) | slot;  // every lane stores the same word
+    const int jw = pos >> 6, lw = pos & 63;
+    alive = (lane == lw) ? (alive & ~(1u << jw)) : alive;
+  };
+
+  // load update: the admitted length enters every horizon offset of worker g; the envelope follows
+  auto add_load = [&](int g, int delta, int k) {
+    add += (lane == g) ? delta : 0;
+    Lcur += (lane == g) ? delta : 0;
+    const int ag = __builtin_amdgcn_readlane(add, g);
+    for (int h0 = 0; h0 < H1; h0 += BR_WAVE) {
+      const int h = h0 + lane;
+      if (h < H1) sM[h] = max(sM[h], sL[h * BR_LSTRIDE + g] + ag);
+    }
+    br_wave_sync();
+    cap -= (lane == g) ? k : 0;
+    nn += (lane == g) ? k : 0;
+    S_tot -= k;
+    n_alive -= k;
+    admitted += k;
+  };
+
+  auto drop_worker = [&](int g, int capg) {
+    S_tot -= capg;
+    cap = (lane == g) ? 0 : cap;
+    ++wdrop;
+  };
+
+  if (run) {
+    const int bound = qn + G + 1;  // every iteration admits a request or sets a worker aside
+
+    // ---- Stage 1: greedy fill while free capacity is abundant
+    for (int it = 0; it < bound; ++it) {
+      if (!(S_tot > p.S_greedy && n_alive > 0)) break;
+      const int capmax = br_wave_max(cap);
+      if (capmax <= 0) break;
+      const bool member = cap == capmax;
+      const int Lmin = br_wave_min(member ? Lcur : INT32_MAX);
+      const int g = (int)__builtin_ctzll(br_ballot(member && Lcur == Lmin));
+      margins_of(g);
+      const int room = p.W > 0 ? p.W - __builtin_amdgcn_readlane(Lcur, g) : INT32_MAX;
+      int pos = 0, swin = 0;
+      if (!pick_single(room, pos, swin)) {
+        drop_worker(g, capmax);
+        continue;
+      }
+      bind(pos, g, __builtin_amdgcn_readlane(nn, g));
+      add_load(g, swin, 1);
+      ++stage1;
+    }
+
+    // ---- Stage 2: refined allocation over the workers that still have free slots
+    int lbit[6];
+#pragma unroll
+    for (int b = 0; b < 6; ++b) lbit[b] = (lane >> b) & 1;
+    const int lpop = __builtin_popcount(lane);
+    for (int it = 0; it < bound; ++it) {
+      if (n_alive <= 0) break;
+      const int capmax = br_wave_max(cap);
+      if (capmax <= 0) break;
+      // priority (free slots, horizon-min margin), lowest index on ties
+      const bool member = cap == capmax;
+      const int mine_m = lane_minm();
+      const int mm = br_wave_max(member ? mine_m : -1);
+      const int g = (int)__builtin_ctzll(br_ballot(member && mine_m == mm));
+      ++pops;
+      margins_of(g);
+      const int room = p.W > 0 ? p.W - __builtin_amdgcn_readlane(Lcur, g) : INT32_MAX;
+
+      // candidate window: the first min(R_max, |R_wait|) alive requests in sorted order
+      const int w = min(p.R_max, n_alive);
+      {
+        int base = 0;
+#pragma unroll
+        for (int j = 0; j < E; ++j) {
+          if (base < w && j * BR_WAVE < qn) {
+            const bool al = (alive >> j) & 1u;
+            const unsigned long long bal = br_ballot(al);
+            const int ar = base + br_rank_below(bal);
+            if (al && ar < w) win[ar] = (sv[j] << BR_IDX_BITS) | (j * BR_WAVE + lane);
+            base += __builtin_popcountll(bal);
+          }
+        }
+      }
+      br_wave_sync();
+      int wv[8], ws[8];
+      {
+        const int4 lo = *reinterpret_cast<const int4 *>(win);
+        const int4 hi = *reinterpret_cast<const int4 *>(win + 4);
+        wv[0] = lo.x, wv[1] = lo.y, wv[2] = lo.z, wv[3] = lo.w;
+        wv[4] = hi.x, wv[5] = hi.y, wv[6] = hi.z, wv[7] = hi.w;
+      }
+#pragma unroll
+      for (int b = 0; b < 8; ++b) ws[b] = b < w ? (wv[b] >> BR_IDX_BITS) : 0;
+      br_wave_sync();  // every lane holds the window before a later pop rewrites it
+
+      // exhaustive subset search: lane l of pass c stands for mask c*64 + l (ascending masks, a later
+      // one wins only if strictly better)
+      const int kmax = min(capmax, p.R_max);
+      const int nmask = 1 << w;
+      int bestmask = 0, bestkey = BR_KEY_NONE;
+      int dv[4];
+      bool okv[4];
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        int delta = (c & 1) * ws[6] + (c >> 1) * ws[7];
+#pragma unroll
+        for (int b = 0; b < 6; ++b)
+          if (b < w) delta += lbit[b] * ws[b];
+        const int mask = c * BR_WAVE + lane;
+        dv[c] = delta;
+        okv[c] = mask != 0 && mask < nmask && lpop + __builtin_popcount(c) <= kmax && delta <= room;
+      }
+      float Fv[4];
+      if (nmask <= BR_WAVE) {
+        const int d1[1] = {dv[0]};
+        float F1[1];
+        br_scoreh_long<1>(p.aD, p.beta, smg, sd, HS, d1, F1);
+        Fv[0] = F1[0], Fv[1] = 0.0f, Fv[2] = 0.0f, Fv[3] = 0.0f;
+      } else {
+        br_scoreh_long<4>(p.aD, p.beta, smg, sd, HS, dv, Fv);
+      }
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        if (c * BR_WAVE < nmask) {
+          const int key = okv[c] ? br_ord(Fv[c]) : BR_KEY_NONE;
+          const int km = br_wave_max(key);
+          if (km > bestkey) {
+            bestkey = km;
+            bestmask = c * BR_WAVE + (int)__builtin_ctzll(br_ballot(key == km));
+          }
+        }
+      }
+
+      if (bestmask == 0 || bestkey <= 0) {  // starvation guard: the single best request anyway
+        ++guard;
+        int pos = 0, swin = 0;
+        if (!pick_single(room, pos, swin)) {
+          drop_worker(g, capmax);
+          continue;
+        }
+        bind(pos, g, __builtin_amdgcn_readlane(nn, g));
+        add_load(g, swin, 1);
+      } else {
+        // lane b binds window entry b if chosen; slots follow the order of the window
+        const int slot = __builtin_amdgcn_readlane(nn, g);
+        const bool mine = lane < 8 && ((bestmask >> lane) & 1);
+        if (mine) {
+          const int me = lane == 0 ? wv[0] : lane == 1 ? wv[1] : lane == 2 ? wv[2] : lane == 3 ? wv[3]
+                       : lane == 4 ? wv[4] : lane == 5 ? wv[5] : lane == 6 ? wv[6] : wv[7];
+          adm[me & IDX_MASK] = (g << 16) | (slot + __builtin_popcount(bestmask & ((1 << lane) - 1)));
+        }
+        int delta = 0;
+#pragma unroll
+        for (int b = 0; b < 8; ++b)
+          if ((bestmask >> b) & 1) {
+            const int pb = wv[b] & IDX_MASK;
+            alive = (lane == (pb & 63)) ? (alive & ~(1u << (pb >> 6))) : alive;
+            delta += ws[b];
+          }
+        add_load(g, br_uniform(delta), __builtin_popcount(bestmask));
+      }
+    }
+  }
+  br_wave_sync();
+
+  BrRoundCounts rc;
+  rc.admitted = admitted;
+  rc.stage1 = stage1;
+  rc.pops = pops;
+  rc.guard = guard;
+  rc.wdrop = wdrop;
+  rc.I_before = I_before;
+  br_assign_epilogue<E>(inst, lane, q0, qn, cnt, skey, adm, who, Lcur, nn, rc, c0);
+  if constexpr (ADV) br_advance_cluster<4, true>(inst, lane, Lcur, nn);
+}
+
+template <int E>
+static void br_launch_assign_long_one(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st) {
+  const int HS = BR_HS(p.H);
+  const size_t lds = ((size_t)3 * E * BR_WAVE + BR_WAVE + 3 * (size_t)HS + (size_t)(p.H + 1) * BR_LSTRIDE) * sizeof(int);
+  const dim3 grid((unsigned)p.N), block(BR_WAVE);
+  if (p.adv_t > 0)
+    hipLaunchKernelGGL((br_k_assign_long<E, true>), grid, block, lds, st, p, a, o);
+  else
+    hipLaunchKernelGGL((br_k_assign_long<E, false>), grid, block, lds, st, p, a, o);
+}
+
+void br_launch_assign_long(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st) {
+  if (p.Q <= 256)
+    br_launch_assign_long_one<4>(p, a, o, st);
+  else if (p.Q <= 512)
+    br_launch_assign_long_one<8>(p, a, o, st);
+  else if (p.Q <= 1024)
+    br_launch_assign_long_one<16>(p, a, o, st);
+  else
+    br_launch_assign_long_one<32>(p, a, o, st);
+}

@@ -7,6 +7,8 @@
 
 #define BR_WAVE 64
 #define BR_HP 8          // horizon offsets h = 0..BR_HP are carried in registers
+#define BR_HL 128        // longest horizon; beyond BR_HP the per-offset state lives in LDS (the *_long kernels)
+#define BR_HS(H) (((H) + 4) & ~3)  // H + 1 offsets padded to whole 16-byte groups
 #define BR_LOW (-(1 << 30))  // "minus infinity" load of a lane that holds no worker
 #define BR_MAX_G_DEV 64
 #define BR_MAX_S_DEV 32768
@@ -27,6 +29,7 @@ struct BrParams {
   int32_t *Lh, *Mh, *mh, *minm;
   const int32_t *hist;      // sorted output lengths (pred_mode 2)
   const long long *hsum;    // their prefix sums
+  const float *dl;          // H > BR_HP: discount vector d[0..H], then zeros up to BR_HS(H) entries
 };
 
 struct BrArr {  // arrivals of one round (device pointers, may be null when none)
@@ -147,6 +150,30 @@ __device__ __forceinline__ float br_scoreh(const BrParams &p, const int (&m)[BR_
       pen = __fadd_rn(pen, __fmul_rn(p.d[h], (float)max(delta - m[h], 0)));
   }
   return __fsub_rn(__fmul_rn(p.aD, (float)delta), __fmul_rn(p.beta, pen));
+}
+
+// The same score for horizons beyond BR_HP, NV subset sums at a time: margins `m` and discounts `d` are
+// read from LDS, four offsets per load, the same address on every lane; entries from H + 1 up to the
+// padded length carry a zero discount and add exactly +0.  Rounding and order as above.
+template <int NV>
+__device__ __forceinline__ void br_scoreh_long(float aD, float beta, const int *m, const float *d, int HS,
+                                               const int (&delta)[NV], float (&F)[NV]) {
+  float pen[NV];
+#pragma unroll
+  for (int v = 0; v < NV; ++v) pen[v] = 0.0f;
+  for (int h = 0; h < HS; h += 4) {
+    const int4 m4 = *reinterpret_cast<const int4 *>(m + h);
+    const float4 d4 = *reinterpret_cast<const float4 *>(d + h);
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+      pen[v] = __fadd_rn(pen[v], __fmul_rn(d4.x, (float)max(delta[v] - m4.x, 0)));
+      pen[v] = __fadd_rn(pen[v], __fmul_rn(d4.y, (float)max(delta[v] - m4.y, 0)));
+      pen[v] = __fadd_rn(pen[v], __fmul_rn(d4.z, (float)max(delta[v] - m4.z, 0)));
+      pen[v] = __fadd_rn(pen[v], __fmul_rn(d4.w, (float)max(delta[v] - m4.w, 0)));
+    }
+  }
+#pragma unroll
+  for (int v = 0; v < NV; ++v) F[v] = __fsub_rn(__fmul_rn(aD, (float)delta[v]), __fmul_rn(beta, pen[v]));
 }
 
 template <bool BRH>

@@ -137,6 +137,73 @@ __global__ __launch_bounds__(256) void br_k_project_rows(BrParams p) {
   }
 }
 
+// Horizons beyond BR_HP (Appendix "Projected workload"): a request counts kv + h at the offsets
+// h <= c_hat, so one histogram of floor(c_hat) per worker (count and kv sum, in LDS) and its suffix sums
+// give L_g(k+h) = sum_{c >= h} kvsum[c] + h * sum_{c >= h} count[c] without a register per offset.
+// One wave per worker; integer sums, so the order of accumulation does not matter.
+__global__ __launch_bounds__(256) void br_k_project_long(BrParams p) {
+  __shared__ int hist_all[4][2 * (BR_HL + 4)];
+  const int wave = threadIdx.x >> 6, lane = br_lane();
+  const int64_t row = (int64_t)blockIdx.x * 4 + wave;
+  if (row >= (int64_t)p.N * p.G) return;  // whole waves leave; no block-wide barrier below
+  const int H = p.H, H1 = H + 1;
+  int *cnt = hist_all[wave], *kvs = cnt + BR_HL + 4;
+  for (int h = lane; h < H1; h += BR_WAVE) cnt[h] = 0, kvs[h] = 0;
+  br_wave_sync();
+  const int n = min(max(p.n[row], 0), p.B);
+  const int64_t base = row * p.Bs;
+  const float Hf = (float)H;
+  int topc = 0, topk = 0;  // requests that reach the last offset (the gate's anchor: the common case)
+  for (int j0 = 0; j0 < n; j0 += BR_WAVE) {
+    const int j = j0 + lane;
+    int kv = 0, hm = -1;
+    if (j < n) {
+      kv = p.kv[base + j];
+      float c = p.pred[(base + j) * p.P];  // pred_mode 1 and 2 keep c_hat first
+      c = c < 1.0f ? 1.0f : c;
+      c = c > Hf ? Hf : c;
+      if (c >= 0.0f) hm = min((int)c, H);  // offsets h with (float)h <= c_hat are 0..floor(c_hat); a NaN counts nowhere
+    }
+    const bool top = hm == H;
+    topc += __builtin_popcountll(br_ballot(top));
+    topk += br_wave_sum(top ? kv : 0);
+    if (hm >= 0 && !top) {
+      atomicAdd(&cnt[hm], 1);
+      atomicAdd(&kvs[hm], kv);
+    }
+  }
+  br_wave_sync();
+  if (lane == 0) cnt[H] += topc, kvs[H] += topk;
+  br_wave_sync();
+  // suffix sums: lane handles offsets lane, lane + 64, lane + 128
+  int C[3] = {0, 0, 0}, K[3] = {0, 0, 0};
+  for (int c = H; c >= 0; --c) {
+    const int cc = cnt[c], kk = kvs[c];
+#pragma unroll
+    for (int u = 0; u < 3; ++u) {
+      const bool in = c >= lane + u * BR_WAVE;
+      C[u] += in ? cc : 0;
+      K[u] += in ? kk : 0;
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < 3; ++u) {
+    const int h = lane + u * BR_WAVE;
+    if (h < H1) p.Lh[row * H1 + h] = K[u] + h * C[u];
+  }
+}
+
+// d = (1, gamma, ..., gamma^H) by repeated fp32 product (Sec. 4.1), zeros up to the padded length
+__global__ void br_k_discounts(BrParams p, float gamma) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  float *d = const_cast<float *>(p.dl);
+  float dh = 1.0f;
+  for (int h = 0; h < BR_HS(p.H); ++h) {
+    if (h > 0) dh = __fmul_rn(dh, gamma);
+    d[h] = h <= p.H ? dh : 0.0f;
+  }
+}
+
 // Part 2: envelope M_h = max_g L_g(k+h), margins m_{g,h} = (M_h - L_g(k+h))_+ and min_h m_{g,h};
 // one wave per cluster, lane g holds worker g.
 __global__ __launch_bounds__(256) void br_k_envelope(BrParams p) {
@@ -165,12 +232,16 @@ __global__ __launch_bounds__(256) void br_k_envelope(BrParams p) {
 // request) and, if asked, stages the 64 x G tile in LDS so that the matrix leaves in full-width
 // contiguous stores.  Pass B maps lanes to (request sub-slot, worker) and keeps a running best
 // request per worker, combined across lanes and waves at the end.
-template <bool BRH>
+// LONG (horizons beyond BR_HP): the margins keep BR_HS(H) entries per worker, the discounts sit in LDS next
+// to them and a score loops over the offsets (br_scoreh_long).
+template <bool BRH, bool LONG = false>
 __global__ __launch_bounds__(512) void br_k_score(BrParams p, BrArr a, BrOut o, int want_tile) {
   extern __shared__ int lds[];
   const int G = p.G;
-  int *sm = lds;                         // [G][BR_HP+1] margins
-  int *sL = sm + G * (BR_HP + 1);        // [G]
+  const int HS = LONG ? BR_HS(p.H) : BR_HP + 1;  // margins per worker
+  int *sm = lds;                         // [G][HS] margins
+  float *sd = (float *)(sm + G * HS);    // LONG: [HS] discounts
+  int *sL = sm + G * HS + (LONG ? HS : 0);  // [G]
   int *scap = sL + G;                    // [G]
   int *ss = scap + G;                    // [Q] prefill lengths of the waiting set
   int *cand = ss + p.Q;                  // [3][blockDim] candidates of pass B
@@ -190,10 +261,12 @@ __global__ __launch_bounds__(512) void br_k_score(BrParams p, BrArr a, BrOut o, 
     sL[tid] = p.L[(int64_t)inst * G + tid];
     scap[tid] = p.B - p.n[(int64_t)inst * G + tid];
   }
-  for (int e = tid; e < G * (BR_HP + 1); e += blockDim.x) {
-    const int g = e / (BR_HP + 1), h = e - g * (BR_HP + 1);
+  for (int e = tid; e < G * HS; e += blockDim.x) {
+    const int g = e / HS, h = e - g * HS;
     sm[e] = (BRH && h <= p.H) ? p.mh[((int64_t)inst * G + g) * (p.H + 1) + h] : 0;
   }
+  if constexpr (LONG)
+    for (int h = tid; h < HS; h += blockDim.x) sd[h] = p.dl[h];
   for (int i = tid; i < qn; i += blockDim.x) {
     int s = i < q0 ? p.qs[(int64_t)inst * p.Q + i] : a.s[(int64_t)inst * a.arr_cap + (i - q0)];
     ss[i] = min(max(s, 1), BR_MAX_S_DEV);
@@ -203,7 +276,7 @@ __global__ __launch_bounds__(512) void br_k_score(BrParams p, BrArr a, BrOut o, 
     if (tid < G) {
       int M = sL[0];
       for (int g = 1; g < G; ++g) M = max(M, sL[g]);
-      sm[tid * (BR_HP + 1)] = M - sL[tid];
+      sm[tid * HS] = M - sL[tid];
     }
     __syncthreads();
   }
@@ -216,10 +289,18 @@ __global__ __launch_bounds__(512) void br_k_score(BrParams p, BrArr a, BrOut o, 
     const int s = valid ? ss[i] : 1;
     int bk = BR_KEY_NONE, bg = -1;
     for (int g = 0; g < G; ++g) {
-      int m[BR_HP + 1];
+      int key;
+      if constexpr (LONG) {
+        const int dv[1] = {s};
+        float Fv[1];
+        br_scoreh_long<1>(p.aD, p.beta, sm + g * HS, sd, HS, dv, Fv);
+        key = br_ord(Fv[0]);
+      } else {
+        int m[BR_HP + 1];
 #pragma unroll
-      for (int h = 0; h <= BR_HP; ++h) m[h] = (BRH || h == 0) ? sm[g * (BR_HP + 1) + h] : 0;
-      const int key = br_score_key<BRH>(p, m, s);
+        for (int h = 0; h <= BR_HP; ++h) m[h] = (BRH || h == 0) ? sm[g * (BR_HP + 1) + h] : 0;
+        key = br_score_key<BRH>(p, m, s);
+      }
       if (want_tile) tile[lane * (G + 1) + g] = key;
       const bool ok = scap[g] > 0 && (p.W <= 0 || sL[g] + s <= p.W);
       if (ok && key > bk) {
@@ -251,13 +332,21 @@ __global__ __launch_bounds__(512) void br_k_score(BrParams p, BrArr a, BrOut o, 
     const bool act = gl < Gs && g < G;
     int m[BR_HP + 1];
 #pragma unroll
-    for (int h = 0; h <= BR_HP; ++h) m[h] = (act && (BRH || h == 0)) ? sm[g * (BR_HP + 1) + h] : 0;
+    for (int h = 0; h <= BR_HP; ++h) m[h] = (!LONG && act && (BRH || h == 0)) ? sm[g * (BR_HP + 1) + h] : 0;
     const int Lg = act ? sL[g] : 0;
     const bool free_slot = act && scap[g] > 0;
     int bk = BR_KEY_NONE, bs = 0, bi = -1;
     for (int i = wave * nsub + sub; i < qn; i += nw * nsub) {
       const int s = ss[i];
-      const int key = br_score_key<BRH>(p, m, s);
+      int key;
+      if constexpr (LONG) {  // lanes hold different workers: each reads its own row of margins
+        const int dv[1] = {s};
+        float Fv[1];
+        br_scoreh_long<1>(p.aD, p.beta, sm + (act ? g : 0) * HS, sd, HS, dv, Fv);
+        key = br_ord(Fv[0]);
+      } else {
+        key = br_score_key<BRH>(p, m, s);
+      }
       const bool ok = free_slot && (p.W <= 0 || Lg + s <= p.W);
       if (ok && (key > bk || (key == bk && s > bs))) {
         bk = key;
@@ -338,8 +427,14 @@ static void launch_project_rows(const BrParams &p, hipStream_t st) {
   hipLaunchKernelGGL((br_k_project_rows<NC, RW>), dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, st, p);
 }
 
+void br_launch_discounts(const BrParams &p, float gamma, hipStream_t st) {
+  hipLaunchKernelGGL(br_k_discounts, dim3(1), dim3(64), 0, st, p, gamma);
+}
+
 void br_launch_project(const BrParams &p, hipStream_t st) {
-  if (p.B <= 64)
+  if (p.H > BR_HP)
+    hipLaunchKernelGGL(br_k_project_long, dim3((unsigned)(((int64_t)p.N * p.G + 3) / 4)), dim3(256), 0, st, p);
+  else if (p.B <= 64)
     launch_project_rows<1, 4>(p, st);
   else if (p.B <= 128)
     launch_project_rows<2, 2>(p, st);
@@ -358,7 +453,8 @@ void br_launch_score(const BrParams &p, const BrArr &a, const BrOut &o, hipStrea
   int waves = (p.Q + 63) / 64;  // one wave per tile of 64 requests, at most 8 waves
   waves = waves < 1 ? 1 : (waves > 8 ? 8 : waves);
   const int want_tile = o.F != nullptr;
-  if (!want_tile && p.Q <= 512 && p.N >= BR_SCORE_WAVE_MIN_N) {  // many small clusters: one wave each
+  const bool longh = p.H > BR_HP;
+  if (!longh && !want_tile && p.Q <= 512 && p.N >= BR_SCORE_WAVE_MIN_N) {  // many small clusters: one wave each
     const dim3 grid((unsigned)((p.N + 3) / 4)), block(256);
     if (p.H > 0) {
       if (p.Q <= 256)
@@ -374,7 +470,8 @@ void br_launch_score(const BrParams &p, const BrArr &a, const BrOut &o, hipStrea
     return;
   }
   auto lds_words = [&](int w) {
-    size_t words = (size_t)p.G * (BR_HP + 1) + 2 * (size_t)p.G + (size_t)p.Q + 3 * 64 * (size_t)w;
+    const size_t HS = longh ? BR_HS(p.H) : BR_HP + 1;
+    size_t words = (size_t)p.G * HS + (longh ? HS : 0) + 2 * (size_t)p.G + (size_t)p.Q + 3 * 64 * (size_t)w;
     if (want_tile) words += (size_t)w * 64 * (size_t)(p.G + 1);
     return words;
   };
@@ -384,7 +481,9 @@ void br_launch_score(const BrParams &p, const BrArr &a, const BrOut &o, hipStrea
   int nsplit = 1;
   while (nsplit < 8 && nsplit * 2 <= p.G && (int64_t)p.N * nsplit * 2 <= 512 && p.Q > 64 * waves * nsplit) nsplit *= 2;
   const dim3 grid((unsigned)p.N, (unsigned)nsplit);
-  if (p.H > 0)
+  if (longh)
+    hipLaunchKernelGGL((br_k_score<true, true>), grid, dim3(64 * waves), lds, st, p, a, o, want_tile);
+  else if (p.H > 0)
     hipLaunchKernelGGL(br_k_score<true>, grid, dim3(64 * waves), lds, st, p, a, o, want_tile);
   else
     hipLaunchKernelGGL(br_k_score<false>, grid, dim3(64 * waves), lds, st, p, a, o, want_tile);

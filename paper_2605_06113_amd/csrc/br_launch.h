@@ -10,8 +10,12 @@ void br_launch_load_init(const BrParams &p, const int32_t *n, const int32_t *kv,
                          hipStream_t st);
 void br_launch_advance(const BrParams &p, int t, hipStream_t st);
 void br_launch_project(const BrParams &p, hipStream_t st);
+// horizons beyond BR_HP: fills the discount table p.dl (once per context)
+void br_launch_discounts(const BrParams &p, float gamma, hipStream_t st);
 void br_launch_score(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st);
 void br_launch_assign(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st);
+// horizons beyond BR_HP: per-offset state in LDS, one wave per cluster
+void br_launch_assign_long(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st);
 void br_launch_assign_br0(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st);
 // BR-0, Q <= 256: snapshot reductions and assignment of four clusters per block in one launch
 void br_launch_route4(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st);

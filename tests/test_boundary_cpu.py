@@ -36,7 +36,7 @@ def test_workspace_bytes_scale():
 
 
 @pytest.mark.parametrize("bad", [dict(G=0), dict(G=65), dict(B=0), dict(B=1025), dict(max_wait=0),
-                                 dict(max_wait=2049), dict(H=9), dict(H=-1), dict(R_max=0), dict(R_max=9),
+                                 dict(max_wait=2049), dict(H=9), dict(H=129, pred_mode=1), dict(H=-1), dict(R_max=0), dict(R_max=9),
                                  dict(n_inst=0), dict(token_watermark=-1), dict(pred_mode=2),
                                  dict(H=2, alpha=0.0), dict(H=2, gamma=0.0), dict(H=2, gamma=1.5)])
 def test_invalid_config_rejected(bad):
@@ -47,6 +47,16 @@ def test_invalid_config_rejected(bad):
     ctx = C.c_void_p()
     assert lib.br_init(C.byref(c), None, C.byref(ctx)) == binding.BR_EINVAL
     assert not ctx.value
+
+
+def test_long_horizon_config():
+    """Horizons up to 128 are accepted with a direct or maintained estimate (a hazard per offset only up to 8);
+    the workspace grows by the projection rows and the discount table."""
+    short = binding.workspace_bytes(wl.config("c3", H=8, pred_mode=1))
+    long_ = binding.workspace_bytes(wl.config("c3", H=80, pred_mode=1))
+    assert short > 0 and long_ > short
+    assert binding.workspace_bytes(wl.config("c3", H=128, pred_mode=1)) > long_
+    assert binding.workspace_bytes(wl.config("c3", H=80, pred_mode=0)) == 0
 
 
 def test_init_argument_errors():

@@ -63,6 +63,13 @@ CASES = [
     (16, 20, 256, 3, dict(pred_mode=1)),
     (16, 20, 256, 8, dict(gate_pfin=0.0, token_watermark=40000)),
     (6, 12, 64, 1, dict(gate_pfin=0.0, gamma=1.0)),
+    # horizons beyond 8: per-offset state in LDS (Sec. 6 deploys H = 80)
+    (8, 16, 96, 80, dict(pred_mode=1, R_max=4, gamma=0.97)),
+    (16, 20, 256, 9, dict(pred_mode=1)),
+    (33, 12, 600, 128, dict(pred_mode=1, R_max=8, gamma=0.99)),
+    (64, 10, 2048, 80, dict(pred_mode=1, R_max=4, gamma=0.95)),
+    (13, 30, 333, 63, dict(pred_mode=1, tie_heavy=True, token_watermark=40000)),
+    (6, 12, 1000, 64, dict(pred_mode=1, gamma=1.0, S_greedy=0)),
 ]
 
 
@@ -201,19 +208,22 @@ def test_random_shapes_equal_lengths_and_loads(seed):
         r.close()
 
 
-def test_random_shapes_horizon():
+@pytest.mark.parametrize("long_h", [False, True])
+def test_random_shapes_horizon(long_h):
     """Many small BR-H shapes drawn at random: every prediction mode (hazards, direct estimate, estimate kept
-    by the library with initial (estimate, age, phase) triples), gates, discounts, weights, thresholds."""
-    rng = np.random.default_rng(41)
-    for case in range(50):
+    by the library with initial (estimate, age, phase) triples), gates, discounts, weights, thresholds.
+    long_h: horizons 9..128 (direct or maintained estimate), the kernels that keep the offsets in LDS."""
+    rng = np.random.default_rng(43 if long_h else 41)
+    for case in range(30 if long_h else 50):
         G = int(rng.choice([2, 3, 8, 16, 31, 64]))
         Q = int(rng.choice([64, 100, 256, 300, 512, 700, 1024, 2048]))
         B = int(rng.integers(2, 50))
         N = int(rng.choice([3, 16, 64])) if Q < 1024 else 4
-        H = int(rng.integers(1, 9))
-        mode = int(rng.choice([0, 0, 1, 2]))
+        H = int(rng.choice([9, 12, 16, 33, 64, 65, 80, 127, 128])) if long_h else int(rng.integers(1, 9))
+        mode = int(rng.choice([1, 2])) if long_h else int(rng.choice([0, 0, 1, 2]))
         kw = dict(R_max=int(rng.choice([1, 2, 4, 4, 8])), gate_pfin=float(rng.choice([0.0, 0.3, 0.5])),
-                  gamma=float(rng.choice([0.64, 0.9, 1.0])), beta=float(rng.choice([-1.0, 14.67, 0.5, 2.0])),
+                  gamma=float(rng.choice([0.9, 0.97, 1.0] if long_h else [0.64, 0.9, 1.0])),
+                  beta=float(rng.choice([-1.0, 14.67, 0.5, 2.0])),
                   tie_heavy=bool(rng.integers(0, 2)), s_hi=int(rng.choice([64, 4096, 32768])),
                   fill=float(rng.choice([0.2, 0.6, 0.95])))
         if mode == 2:
@@ -435,7 +445,7 @@ def test_pool_bypass():
         r.close()
 
 
-@pytest.mark.parametrize("H,refresh,gate", [(4, 0, 0.0), (8, 3, 0.5), (8, 1, 0.0)])
+@pytest.mark.parametrize("H,refresh,gate", [(4, 0, 0.0), (8, 3, 0.5), (8, 1, 0.0), (80, 0, 0.5), (24, 5, 0.0)])
 def test_maintained_estimate_replay(H, refresh, gate):
     """pred_mode 2: c_hat kept by the library (empirical-survival estimator, periodic refresh, decrement,
     floor): replay with short outputs so that the estimate moves; slot tables incl. (c_hat, age, since)."""

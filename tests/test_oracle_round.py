@@ -325,23 +325,25 @@ def test_request_lifetime_loads(orc):
 
 # ---- horizon projection: Appendix "Short-horizon prediction interface" -----------------
 
-def test_projection_anchor_closed_form(orc):
-    """All c_hat = H (hazards zero): L_g(k+h) = L_g(k) + h * |A_g|; row h = 0 is the current load."""
-    cfg, init, _ = wl.random_case(4, N=3, G=6, B=12, max_wait=8, H=5)
-    init.pred[...] = 0.0
+@pytest.mark.parametrize("H,mode", [(5, 0), (80, 1)])
+def test_projection_anchor_closed_form(orc, H, mode):
+    """All c_hat = H (hazards zero, or the estimate given as H): L_g(k+h) = L_g(k) + h * |A_g|; row h = 0 is
+    the current load."""
+    cfg, init, _ = wl.random_case(4, N=3, G=6, B=12, max_wait=8, H=H, pred_mode=mode)
+    init.pred[...] = float(H) if mode else 0.0
     oc = _mk(orc, cfg, init)
     pr = oc.project()
-    h = np.arange(6)[None, None, :]
+    h = np.arange(H + 1)[None, None, :]
     assert (pr["Lh"] == oc.L[:, :, None] + h * oc.n[:, :, None]).all()
     assert (pr["Mh"] == pr["Lh"].max(axis=1)).all()
     assert (pr["mh"] == pr["Mh"][:, None, :] - pr["Lh"]).all() and (pr["mh"] >= 0).all()
     assert (pr["minm"] == pr["mh"].min(axis=2)).all()
 
 
-def test_projection_vs_true_future(orc):
+@pytest.mark.parametrize("H", [6, 80])
+def test_projection_vs_true_future(orc, H):
     """With c_hat = min(r, H) the projection equals the true future load except that a request is
     kept for one offset longer (at h = r <= H): the documented conservative index convention."""
-    H = 6
     cfg, init, _ = wl.random_case(9, N=2, G=4, B=16, max_wait=8, H=H, pred_mode=1)
     init.pred[..., 0] = np.minimum(init.rem, H)
     oc = _mk(orc, cfg, init)
