@@ -111,16 +111,26 @@ def latency_run(steps, device, deployed=False):
     return res
 
 
-def brh_run(device, steps=5, warmup=1, gate=None):
+def brh_run(device, steps=5, warmup=1, gate=None, deployed=False):
     """Batched BR-H round (horizon projection + scores + assignment) and decode step:
-    4096 clusters of the c3 shape (G=32, B=96, H=4), 76 active requests per worker, 256 waiting."""
+    4096 clusters of the c3 shape (G=32, B=96, H=4), 76 active requests per worker, 256 waiting.
+    deployed: 2048 clusters at the horizon and window of Sec. 6 (H=80, R_max=4, G=8; B=64, 48 active per
+    worker, 256 waiting), the estimate maintained by the library."""
     import torch
     from paper_2605_06113_amd import binding, workloads as wl
     over = {} if gate is None else dict(gate_pfin=gate)
-    cfg = wl.config("c3", n_inst=4096, **over, token_watermark=0, token_cap=0, init_active_per_worker=76, init_kv_lo=256, init_kv_hi=8192,
-                    init_rem_lo=1, init_rem_hi=1024, init_waiting=256)
+    per_worker = 48 if deployed else 76
+    if deployed:
+        cfg = wl.config("c3", n_inst=2048, G=8, B=64, max_wait=256, H=80, R_max=4, pred_mode=2, token_watermark=0,
+                        token_cap=0, init_active_per_worker=per_worker, init_kv_lo=256, init_kv_hi=8192, init_rem_lo=1,
+                        init_rem_hi=1024, init_waiting=256, seed=2100)
+        hist = wl.output_history(cfg, 8000)
+    else:
+        cfg = wl.config("c3", n_inst=4096, **over, token_watermark=0, token_cap=0, init_active_per_worker=per_worker,
+                        init_kv_lo=256, init_kv_hi=8192, init_rem_lo=1, init_rem_hi=1024, init_waiting=256)
+        hist = None
     init, arr = wl.initial_state(cfg), wl.initial_waiting(cfg)
-    routers = [binding.Router(cfg, init, device=device) for _ in range(steps + warmup)]
+    routers = [binding.Router(cfg, init, device=device, hist=hist) for _ in range(steps + warmup)]
     darr = binding.DeviceArrivals(arr, device, routers[0].Pq)
     out = routers[0].alloc_outputs(scores=True, matrix=False)
     torch.cuda.synchronize()
@@ -144,12 +154,12 @@ def brh_run(device, steps=5, warmup=1, gate=None):
             kern[k][1] += c
     for r in routers:
         r.close()
-    N, G, H, P = cfg.n_inst, cfg.G, cfg.H, cfg.H
-    active = N * G * 76
+    N, G, H, P = cfg.n_inst, cfg.G, cfg.H, routers[0].P
+    active = N * G * per_worker
     bytes_k = dict(project=active * (4 + 4 * P) + N * G * 4 + N * (H + 1) * 4 * (2 * G + 1) + N * G * 4,
                    advance=(active + admitted) * 16 + N * G * 16)
-    res = dict(workload="4096 clusters of the c3 shape: BR-H H=4, G=32, B=96, 76 active per worker, 256 waiting; "
-                        f"p_fin gate {cfg.gate_pfin}",
+    res = dict(workload=f"{N} clusters: BR-H H={H}, G={G}, B={cfg.B}, R_max={cfg.R_max}, {per_worker} active per worker, "
+                        f"256 waiting; p_fin gate {cfg.gate_pfin}" + ("; estimate maintained by the library" if deployed else ""),
                ms_per_step=elapsed / steps * 1e3, pairs_per_s=qn * G * steps / elapsed,
                decisions_per_s=admitted * steps / elapsed, kernels={})
     for k, (ms, c) in kern.items():
@@ -389,6 +399,7 @@ def main():
     if not args.no_brh:
         res["brh_batched"] = brh_run(device)
         res["brh_batched_gate_off"] = brh_run(device, gate=0.0)   # hazards live: no request counts at the last offset
+        res["brh_batched_h80"] = brh_run(device, deployed=True)
         res["bypass"] = bypass_run(device, cfg, init, arr)
         res["replay_batched"] = replay_run(device)
     if args.latency_steps > 0:

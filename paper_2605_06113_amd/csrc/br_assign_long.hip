@@ -2,10 +2,11 @@
 // carries (Appendix, Alg. BR-H; H up to 128, the deployed value of Sec. 6 is 80), one wavefront per
 // cluster.
 //
-// The round is the plain loop of Alg. BR-H: Stage 1 gives the worker with the most free slots (then
-// the lightest, then the lowest index) its best single request while free capacity exceeds S_greedy;
-// Stage 2 pops workers by (free slots, horizon-min margin), searches the subsets of the top-R_max window
-// and falls back to the single best request when no subset scores above zero.
+// The round is the loop of Alg. BR-H: Stage 1 gives the worker with the most free slots (then the
+// lightest, then the lowest index) its best single request while free capacity exceeds S_greedy (taken a
+// level of equal free-slot counts at a time where that is provably the same, see below); Stage 2 pops
+// workers by (free slots, horizon-min margin), searches the subsets of the top-R_max window and falls
+// back to the single best request when no subset scores above zero.
 //
 // What differs from the short-horizon kernel is where the per-offset state lives:
 //   - the step-start projections L_g(k+h) stay in LDS, sL[h][g] (row stride 65 words, so that both
@@ -36,11 +37,12 @@ __global__ __launch_bounds__(64) void br_k_assign_long(BrParams p, BrArr a, BrOu
   int *skey = lds;                  // [NP] sorted keys (s << 11 | 2047 - arrival position)
   int *adm = lds + NP;              // [NP] by sorted position: worker << 16 | slot, or -1
   int *who = lds + 2 * NP;          // [NP] by arrival position: worker, or -1
-  int *win = lds + 3 * NP;          // [8]  Stage-2 candidate window (16-byte aligned), padded to 64
+  int *win = lds + 3 * NP;          // [64] Stage-1 level: k-th alive request (s << 11 | sorted position);
+                                    //      Stage 2: the candidate window, same packing (16-byte aligned)
   int *sM = win + BR_WAVE;          // [HS] envelope M_h
-  int *smg = sM + HS;               // [HS] margins of the worker in hand
-  float *sd = (float *)(smg + HS);  // [HS] discounts, zero beyond H
-  int *sL = smg + 2 * HS;           // [H1][65] step-start projections
+  float *smg = (float *)(sM + HS);  // [HS] margins of the worker in hand, as floats
+  float *sd = smg + HS;             // [HS] discounts, zero beyond H
+  int *sL = sM + 3 * HS;            // [HS][65] step-start projections (rows beyond H: "no worker")
 
   const int lane = br_lane();
   const int G = p.G;
@@ -65,13 +67,13 @@ __global__ __launch_bounds__(64) void br_k_assign_long(BrParams p, BrArr a, BrOu
     if (h < HS) {
       sM[h] = h < H1 ? p.Mh[(int64_t)inst * H1 + h] : 0;
       sd[h] = p.dl[h];
-      smg[h] = 0;
+      smg[h] = 0.0f;
     }
   }
-  for (int g = 0; g < BR_WAVE; ++g) {  // rows of workers beyond G read as "no worker"
-    for (int h0 = 0; h0 < H1; h0 += BR_WAVE) {
+  for (int g = 0; g < BR_WAVE; ++g) {  // workers beyond G and offsets beyond H read as "no worker"
+    for (int h0 = 0; h0 < HS; h0 += BR_WAVE) {
       const int h = h0 + lane;
-      if (h < H1) sL[h * BR_LSTRIDE + g] = g < G ? p.Lh[((int64_t)inst * G + g) * H1 + h] : BR_LOW;
+      if (h < HS) sL[h * BR_LSTRIDE + g] = (g < G && h < H1) ? p.Lh[((int64_t)inst * G + g) * H1 + h] : BR_LOW;
     }
   }
   int S_tot = br_wave_sum(cap);
@@ -122,16 +124,22 @@ __global__ __launch_bounds__(64) void br_k_assign_long(BrParams p, BrArr a, BrOu
     const int ag = __builtin_amdgcn_readlane(add, g);
     for (int h0 = 0; h0 < H1; h0 += BR_WAVE) {
       const int h = h0 + lane;
-      if (h < H1) smg[h] = max(sM[h] - (sL[h * BR_LSTRIDE + g] + ag), 0);
+      if (h < H1) smg[h] = (float)max(sM[h] - (sL[h * BR_LSTRIDE + g] + ag), 0);
     }
     br_wave_sync();
   };
 
   // horizon-min margin of the worker each lane holds
-  auto lane_minm = [&]() {
+  auto lane_minm = [&]() {  // four offsets per trip (padded offsets: envelope 0 against "no worker")
     int mn = INT32_MAX;
-    for (int h = 0; h < H1; ++h) mn = min(mn, max(sM[h] - (sL[h * BR_LSTRIDE + lane] + add), 0));
-    return mn;
+    const int *row = sL + lane;
+    for (int h = 0; h < HS; h += 4) {
+      const int4 M4 = *reinterpret_cast<const int4 *>(sM + h);
+      const int l0 = row[(h + 0) * BR_LSTRIDE], l1 = row[(h + 1) * BR_LSTRIDE];
+      const int l2 = row[(h + 2) * BR_LSTRIDE], l3 = row[(h + 3) * BR_LSTRIDE];
+      mn = min(mn, min(min(M4.x - l0, M4.y - l1), min(M4.z - l2, M4.w - l3)));
+    }
+    return max(mn - add, 0);  // min_h (M_h - sL_h) - add, clamped once: the same as clamping every offset
   };
 
   // argmax_i F_g({i}) over alive, admissible requests against the margins in smg (lowest sorted
@@ -196,24 +204,76 @@ __global__ __launch_bounds__(64) void br_k_assign_long(BrParams p, BrArr a, BrOu
   if (run) {
     const int bound = qn + G + 1;  // every iteration admits a request or sets a worker aside
 
-    // ---- Stage 1: greedy fill while free capacity is abundant
+    // ---- Stage 1: greedy fill while free capacity is abundant.  Taken a level at a time: the workers that
+    // share the largest free-slot count are picked once each in order of (load, index) before any other
+    // worker can reach that count.  While the largest waiting request fits the next worker's horizon-min
+    // margin (and the watermark), every penalty term of eq. (brh-Fscore) is zero for it, its score alpha D s
+    // is the largest one, and the envelope does not move: the k-th lightest worker of the level takes the
+    // k-th largest waiting request, all in one step.  The rest of the level goes one worker at a time.
     for (int it = 0; it < bound; ++it) {
       if (!(S_tot > p.S_greedy && n_alive > 0)) break;
       const int capmax = br_wave_max(cap);
       if (capmax <= 0) break;
       const bool member = cap == capmax;
-      const int Lmin = br_wave_min(member ? Lcur : INT32_MAX);
-      const int g = (int)__builtin_ctzll(br_ballot(member && Lcur == Lmin));
-      margins_of(g);
-      const int room = p.W > 0 ? p.W - __builtin_amdgcn_readlane(Lcur, g) : INT32_MAX;
-      int pos = 0, swin = 0;
-      if (!pick_single(room, pos, swin)) {
-        drop_worker(g, capmax);
-        continue;
+      const int wkey = member ? (int)(((unsigned)Lcur << 6) | (unsigned)lane) : INT32_MAX;
+      int rank = 0;
+      for (int g0 = 0; g0 < G; g0 += 4) {  // lanes beyond G hold INT32_MAX and never count
+#pragma unroll
+        for (int u = 0; u < 4; ++u) rank += (__builtin_amdgcn_readlane(wkey, g0 + u) < wkey) ? 1 : 0;
       }
-      bind(pos, g, __builtin_amdgcn_readlane(nn, g));
-      add_load(g, swin, 1);
-      ++stage1;
+      const int level = __builtin_popcountll(br_ballot(member));
+      const int kmaxp = min(level, min(S_tot - p.S_greedy, n_alive));
+      {  // the first kmaxp alive requests, by rank, through LDS
+        int base = 0;
+#pragma unroll
+        for (int j = 0; j < E; ++j) {
+          if (base < kmaxp && j * BR_WAVE < qn) {
+            const bool al = (alive >> j) & 1u;
+            const unsigned long long bal = br_ballot(al);
+            const int ar = base + br_rank_below(bal);
+            if (al && ar < kmaxp) win[ar] = (sv[j] << BR_IDX_BITS) | (j * BR_WAVE + lane);
+            base += __builtin_popcountll(bal);
+          }
+        }
+      }
+      br_wave_sync();
+      const bool cand = member && rank < kmaxp;
+      const int mine = cand ? win[rank] : 0;
+      const int s_k = mine >> BR_IDX_BITS, pos_k = mine & IDX_MASK;
+      int lim = lane_minm();
+      if (p.W > 0) lim = min(lim, p.W - Lcur);
+      const int k0 = br_wave_min((cand && s_k > lim) ? rank : kmaxp);
+      if (k0 > 0) {
+        const bool take = cand && rank < k0;
+        if (take) adm[pos_k] = (lane << 16) | nn;
+        add += take ? s_k : 0;
+        Lcur += take ? s_k : 0;
+        nn += take ? 1 : 0;
+        cap -= take ? 1 : 0;
+        const int pstar = br_uniform(win[k0 - 1] & IDX_MASK);  // last position taken; everything alive before it went too
+        const int jf = pstar >> 6, lf = pstar & 63;
+        const unsigned clear = ((1u << jf) - 1u) | ((lane <= lf) ? (1u << jf) : 0u);
+        alive &= ~clear;
+        S_tot -= k0;
+        n_alive -= k0;
+        admitted += k0;
+        stage1 += k0;
+      }
+      br_wave_sync();
+      for (int r = k0; r < level; ++r) {
+        if (!(S_tot > p.S_greedy && n_alive > 0)) break;
+        const int g = (int)__builtin_ctzll(br_ballot(member && rank == r));
+        margins_of(g);
+        const int room = p.W > 0 ? p.W - __builtin_amdgcn_readlane(Lcur, g) : INT32_MAX;
+        int pos = 0, swin = 0;
+        if (!pick_single(room, pos, swin)) {
+          drop_worker(g, capmax);
+          continue;
+        }
+        bind(pos, g, __builtin_amdgcn_readlane(nn, g));
+        add_load(g, swin, 1);
+        ++stage1;
+      }
     }
 
     // ---- Stage 2: refined allocation over the workers that still have free slots
@@ -345,7 +405,7 @@ __global__ __launch_bounds__(64) void br_k_assign_long(BrParams p, BrArr a, BrOu
 template <int E>
 static void br_launch_assign_long_one(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st) {
   const int HS = BR_HS(p.H);
-  const size_t lds = ((size_t)3 * E * BR_WAVE + BR_WAVE + 3 * (size_t)HS + (size_t)(p.H + 1) * BR_LSTRIDE) * sizeof(int);
+  const size_t lds = ((size_t)3 * E * BR_WAVE + BR_WAVE + 3 * (size_t)HS + (size_t)HS * BR_LSTRIDE) * sizeof(int);
   const dim3 grid((unsigned)p.N), block(BR_WAVE);
   if (p.adv_t > 0)
     hipLaunchKernelGGL((br_k_assign_long<E, true>), grid, block, lds, st, p, a, o);

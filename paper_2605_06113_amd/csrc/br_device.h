@@ -152,28 +152,38 @@ __device__ __forceinline__ float br_scoreh(const BrParams &p, const int (&m)[BR_
   return __fsub_rn(__fmul_rn(p.aD, (float)delta), __fmul_rn(p.beta, pen));
 }
 
-// The same score for horizons beyond BR_HP, NV subset sums at a time: margins `m` and discounts `d` are
-// read from LDS, four offsets per load, the same address on every lane; entries from H + 1 up to the
-// padded length carry a zero discount and add exactly +0.  Rounding and order as above.
+// The same score for horizons beyond BR_HP, NV subset sums at a time: margins `m` (as floats) and
+// discounts `d` are read from LDS, four offsets per load, the same address on every lane; entries from
+// H + 1 up to the padded length carry a zero discount and add exactly +0.  Rounding and order as above.
+// The excess (Delta - m)_+ is formed in fp32: Delta <= 2^18 and, wherever Delta > m, m are exact floats and
+// so is their difference; where Delta <= m the rounded margin is still >= Delta and the term is zero, as in
+// integers.
+// The group after the one in use is requested first, so that the LDS latency hides under the arithmetic:
+// both arrays are read up to four entries beyond HS (the callers keep other LDS data there; the values are
+// not used).
 template <int NV>
-__device__ __forceinline__ void br_scoreh_long(float aD, float beta, const int *m, const float *d, int HS,
+__device__ __forceinline__ void br_scoreh_long(float aD, float beta, const float *m, const float *d, int HS,
                                                const int (&delta)[NV], float (&F)[NV]) {
-  float pen[NV];
+  float pen[NV], fd[NV];
 #pragma unroll
-  for (int v = 0; v < NV; ++v) pen[v] = 0.0f;
+  for (int v = 0; v < NV; ++v) pen[v] = 0.0f, fd[v] = (float)delta[v];
+  float4 m4 = *reinterpret_cast<const float4 *>(m);
+  float4 d4 = *reinterpret_cast<const float4 *>(d);
   for (int h = 0; h < HS; h += 4) {
-    const int4 m4 = *reinterpret_cast<const int4 *>(m + h);
-    const float4 d4 = *reinterpret_cast<const float4 *>(d + h);
+    const float4 mn = *reinterpret_cast<const float4 *>(m + h + 4);
+    const float4 dn = *reinterpret_cast<const float4 *>(d + h + 4);
 #pragma unroll
     for (int v = 0; v < NV; ++v) {
-      pen[v] = __fadd_rn(pen[v], __fmul_rn(d4.x, (float)max(delta[v] - m4.x, 0)));
-      pen[v] = __fadd_rn(pen[v], __fmul_rn(d4.y, (float)max(delta[v] - m4.y, 0)));
-      pen[v] = __fadd_rn(pen[v], __fmul_rn(d4.z, (float)max(delta[v] - m4.z, 0)));
-      pen[v] = __fadd_rn(pen[v], __fmul_rn(d4.w, (float)max(delta[v] - m4.w, 0)));
+      pen[v] = __fadd_rn(pen[v], __fmul_rn(d4.x, fmaxf(__fsub_rn(fd[v], m4.x), 0.0f)));
+      pen[v] = __fadd_rn(pen[v], __fmul_rn(d4.y, fmaxf(__fsub_rn(fd[v], m4.y), 0.0f)));
+      pen[v] = __fadd_rn(pen[v], __fmul_rn(d4.z, fmaxf(__fsub_rn(fd[v], m4.z), 0.0f)));
+      pen[v] = __fadd_rn(pen[v], __fmul_rn(d4.w, fmaxf(__fsub_rn(fd[v], m4.w), 0.0f)));
     }
+    m4 = mn;
+    d4 = dn;
   }
 #pragma unroll
-  for (int v = 0; v < NV; ++v) F[v] = __fsub_rn(__fmul_rn(aD, (float)delta[v]), __fmul_rn(beta, pen[v]));
+  for (int v = 0; v < NV; ++v) F[v] = __fsub_rn(__fmul_rn(aD, fd[v]), __fmul_rn(beta, pen[v]));
 }
 
 template <bool BRH>

@@ -263,7 +263,8 @@ __global__ __launch_bounds__(512) void br_k_score(BrParams p, BrArr a, BrOut o, 
   }
   for (int e = tid; e < G * HS; e += blockDim.x) {
     const int g = e / HS, h = e - g * HS;
-    sm[e] = (BRH && h <= p.H) ? p.mh[((int64_t)inst * G + g) * (p.H + 1) + h] : 0;
+    const int m = (BRH && h <= p.H) ? p.mh[((int64_t)inst * G + g) * (p.H + 1) + h] : 0;
+    sm[e] = LONG ? __float_as_int((float)m) : m;  // br_scoreh_long takes the margins as floats
   }
   if constexpr (LONG)
     for (int h = tid; h < HS; h += blockDim.x) sd[h] = p.dl[h];
@@ -293,7 +294,7 @@ __global__ __launch_bounds__(512) void br_k_score(BrParams p, BrArr a, BrOut o, 
       if constexpr (LONG) {
         const int dv[1] = {s};
         float Fv[1];
-        br_scoreh_long<1>(p.aD, p.beta, sm + g * HS, sd, HS, dv, Fv);
+        br_scoreh_long<1>(p.aD, p.beta, (const float *)(sm + g * HS), sd, HS, dv, Fv);
         key = br_ord(Fv[0]);
       } else {
         int m[BR_HP + 1];
@@ -342,7 +343,7 @@ __global__ __launch_bounds__(512) void br_k_score(BrParams p, BrArr a, BrOut o, 
       if constexpr (LONG) {  // lanes hold different workers: each reads its own row of margins
         const int dv[1] = {s};
         float Fv[1];
-        br_scoreh_long<1>(p.aD, p.beta, sm + (act ? g : 0) * HS, sd, HS, dv, Fv);
+        br_scoreh_long<1>(p.aD, p.beta, (const float *)(sm + (act ? g : 0) * HS), sd, HS, dv, Fv);
         key = br_ord(Fv[0]);
       } else {
         key = br_score_key<BRH>(p, m, s);
