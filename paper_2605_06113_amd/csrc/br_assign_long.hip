@@ -16,7 +16,8 @@
 //   - the envelope M_h and the margins of the worker in hand are LDS arrays maintained with lanes
 //     mapped to offsets;
 //   - a score walks the offsets in order with margins and discounts broadcast from LDS, four per load,
-//     for four waiting requests (or four subset sums) per lane at a time (br_scoreh_long).
+//     for four waiting requests (or four subset sums) per lane at a time, and skips the groups of offsets
+//     whose margins no request in question reaches (exact zeros; br_long_active, br_scoreh_long_act).
 // Waiting set, sticky binding, epilogue and the optional decode steps are those of the short-horizon
 // kernel (br_sort.h, br_assign_common.h).
 #include "br_device.h"
@@ -145,13 +146,20 @@ __global__ __launch_bounds__(64) void br_k_assign_long(BrParams p, BrArr a, BrOu
   // argmax_i F_g({i}) over alive, admissible requests against the margins in smg (lowest sorted
   // position on ties); false when no request is admissible
   auto pick_single = [&](int room, int &pos, int &swin) -> bool {
+    int smax = 0;  // the longest request in question: offsets whose margin it does not reach add nothing
+#pragma unroll
+    for (int j = 0; j < E; ++j) smax = max(smax, (((alive >> j) & 1u) && sv[j] <= room) ? sv[j] : 0);
+    smax = br_wave_max(smax);
+    if (smax == 0) return false;
+    unsigned long long act[3];
+    br_long_active(smg, HS, lane, smax, act);
     int bk = BR_KEY_NONE, bp = INT32_MAX;
 #pragma unroll
     for (int j0 = 0; j0 < E; j0 += 4) {
       if (j0 * BR_WAVE < qn) {
         const int dv[4] = {sv[j0], sv[j0 + 1], sv[j0 + 2], sv[j0 + 3]};
         float Fv[4];
-        br_scoreh_long<4>(p.aD, p.beta, smg, sd, HS, dv, Fv);
+        br_scoreh_long_act<4>(p.aD, p.beta, smg, sd, act, dv, Fv);
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
           const int j = j0 + u;
@@ -338,14 +346,22 @@ __global__ __launch_bounds__(64) void br_k_assign_long(BrParams p, BrArr a, BrOu
         dv[c] = delta;
         okv[c] = mask != 0 && mask < nmask && lpop + __builtin_popcount(c) <= kmax && delta <= room;
       }
-      float Fv[4];
-      if (nmask <= BR_WAVE) {
-        const int d1[1] = {dv[0]};
-        float F1[1];
-        br_scoreh_long<1>(p.aD, p.beta, smg, sd, HS, d1, F1);
-        Fv[0] = F1[0], Fv[1] = 0.0f, Fv[2] = 0.0f, Fv[3] = 0.0f;
-      } else {
-        br_scoreh_long<4>(p.aD, p.beta, smg, sd, HS, dv, Fv);
+      float Fv[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+      int dmax = 0;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) dmax = max(dmax, okv[c] ? dv[c] : 0);
+      dmax = br_wave_max(dmax);
+      if (dmax > 0) {  // else no subset is admissible
+        unsigned long long act[3];
+        br_long_active(smg, HS, lane, dmax, act);
+        if (nmask <= BR_WAVE) {
+          const int d1[1] = {dv[0]};
+          float F1[1];
+          br_scoreh_long_act<1>(p.aD, p.beta, smg, sd, act, d1, F1);
+          Fv[0] = F1[0];
+        } else {
+          br_scoreh_long_act<4>(p.aD, p.beta, smg, sd, act, dv, Fv);
+        }
       }
 #pragma unroll
       for (int c = 0; c < 4; ++c) {

@@ -186,6 +186,49 @@ __device__ __forceinline__ void br_scoreh_long(float aD, float beta, const float
   for (int v = 0; v < NV; ++v) F[v] = __fsub_rn(__fmul_rn(aD, fd[v]), __fmul_rn(beta, pen[v]));
 }
 
+// Offsets whose margin lies below `maxdelta`, as one bit per offset (lanes stand for offsets; every lane of
+// the wave must call).  For every Delta <= maxdelta the other offsets contribute exactly +0 to the penalty
+// sum, which leaves it as it is: br_scoreh_long_act walks only the four-offset groups that hold a set bit,
+// in ascending order, and returns the same bits as the full walk.
+__device__ __forceinline__ void br_long_active(const float *m, int HS, int lane, int maxdelta,
+                                               unsigned long long (&act)[3]) {
+  const float fmx = (float)maxdelta;
+#pragma unroll
+  for (int c = 0; c < 3; ++c) {
+    const int h = c * BR_WAVE + lane;
+    act[c] = br_ballot(h < HS && m[h] < fmx);
+  }
+}
+
+template <int NV>
+__device__ __forceinline__ void br_scoreh_long_act(float aD, float beta, const float *m, const float *d,
+                                                   const unsigned long long (&act)[3], const int (&delta)[NV],
+                                                   float (&F)[NV]) {
+  float pen[NV], fd[NV];
+#pragma unroll
+  for (int v = 0; v < NV; ++v) pen[v] = 0.0f, fd[v] = (float)delta[v];
+#pragma unroll
+  for (int c = 0; c < 3; ++c) {
+    unsigned long long g = act[c];
+    g = (g | (g >> 1) | (g >> 2) | (g >> 3)) & 0x1111111111111111ull;  // bit 4k: group k of this chunk is needed
+    while (g != 0ull) {
+      const int h = c * BR_WAVE + (int)__builtin_ctzll(g);
+      g &= g - 1ull;
+      const float4 m4 = *reinterpret_cast<const float4 *>(m + h);
+      const float4 d4 = *reinterpret_cast<const float4 *>(d + h);
+#pragma unroll
+      for (int v = 0; v < NV; ++v) {
+        pen[v] = __fadd_rn(pen[v], __fmul_rn(d4.x, fmaxf(__fsub_rn(fd[v], m4.x), 0.0f)));
+        pen[v] = __fadd_rn(pen[v], __fmul_rn(d4.y, fmaxf(__fsub_rn(fd[v], m4.y), 0.0f)));
+        pen[v] = __fadd_rn(pen[v], __fmul_rn(d4.z, fmaxf(__fsub_rn(fd[v], m4.z), 0.0f)));
+        pen[v] = __fadd_rn(pen[v], __fmul_rn(d4.w, fmaxf(__fsub_rn(fd[v], m4.w), 0.0f)));
+      }
+    }
+  }
+#pragma unroll
+  for (int v = 0; v < NV; ++v) F[v] = __fsub_rn(__fmul_rn(aD, fd[v]), __fmul_rn(beta, pen[v]));
+}
+
 template <bool BRH>
 __device__ __forceinline__ int br_score_key(const BrParams &p, const int (&m)[BR_HP + 1], int delta) {
   if constexpr (BRH) return br_ord(br_scoreh(p, m, delta));
