@@ -46,7 +46,7 @@ extern "C" {
 
 #define ORC_MAX_G 64
 #define ORC_MAX_H 128
-#define ORC_MAX_RMAX 8
+#define ORC_MAX_RMAX 16
 #define ORC_NSTATS 16
 #define ORC_MAX_S 32768
 

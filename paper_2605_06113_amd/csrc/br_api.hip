@@ -30,6 +30,7 @@ bool config_ok(const br_config *c) {
   if (c->token_watermark < 0 || c->token_cap < 0) return false;
   if (c->pred_mode < 0 || c->pred_mode > 2) return false;
   if (c->H > BR_HP && c->pred_mode == 0) return false;  // a hazard per offset is carried for short horizons only
+  if (c->H > BR_HP && c->R_max > 8) return false;        // windows beyond 8 requests: short horizons only
   if (c->pred_mode == 2) {
     if (c->H == 0 || !c->hist || !c->hist_sum || c->hist_n < 1 || c->hist_n > (1 << 20) || c->refresh_period < 1)
       return false;
@@ -243,11 +244,14 @@ static int32_t route(br_ctx *ctx, const br_arrivals *in, const br_step_out *out,
     o.best_i = out->best_i;
   }
   BrParams p = ctx->p;
-  p.adv_t = adv_t;
+  // windows beyond 8 requests have no fused instantiation: the decode steps follow as their own launch
+  const bool split_adv = adv_t > 0 && p.R_max > 8;
+  p.adv_t = split_adv ? 0 : adv_t;
   int32_t rc = BR_OK;
   if (p.H > 0) rc = enqueue(ctx, BR_K_PROJECT, [&] { br_launch_project(p, ctx->st); });
   // large batches of BR-0 clusters with short queues: the reductions ride along in the assignment launch
-  const bool together = (o.best_g || o.best_i) && !o.F && p.H == 0 && p.Q <= 256 && p.N >= BR_SCORE_WAVE_MIN_N;
+  const bool together =
+      (o.best_g || o.best_i) && !o.F && p.H == 0 && p.Q <= 256 && p.N >= BR_SCORE_WAVE_MIN_N && p.R_max <= 8;
   if (rc == BR_OK && !together && (o.F || o.best_g || o.best_i))
     rc = enqueue(ctx, BR_K_SCORE, [&] { br_launch_score(p, a, o, ctx->st); });
   if (rc == BR_OK) {
@@ -256,6 +260,7 @@ static int32_t route(br_ctx *ctx, const br_arrivals *in, const br_step_out *out,
     else
       rc = enqueue(ctx, BR_K_ASSIGN, [&] { br_launch_assign(p, a, o, ctx->st); });
   }
+  if (rc == BR_OK && split_adv) rc = enqueue(ctx, BR_K_ADVANCE, [&] { br_launch_advance(p, adv_t, ctx->st); });
   return rc;
 }
 

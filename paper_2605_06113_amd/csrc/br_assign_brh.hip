@@ -5,6 +5,8 @@
 void br_launch_assign(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st) {
   if (p.H > BR_HP)
     br_launch_assign_long(p, a, o, st);
+  else if (p.R_max > 8)
+    br_launch_assign_bigr(p, a, o, st);
   else if (p.H > 0)
     br_launch_assign_sized<true>(p, a, o, st);
   else

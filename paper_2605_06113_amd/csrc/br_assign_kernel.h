@@ -51,7 +51,7 @@ struct Log2E {
 // One cluster's round on one wave.  `lds`: this wave's 3*E*64 + 72 words.  COOP (queues of up to 2048):
 // the block has four waves; all of them sort the waiting set together (br_sort_desc_block4), wave 0 runs
 // the round alone with the sorted keys read back from LDS, and all four share the epilogue and the decode step.
-template <int E, bool BRH, bool ADV, bool COOP = false>
+template <int E, bool BRH, bool ADV, bool COOP = false, bool BIGR = false>
 __device__ __forceinline__ void br_assign_body(const BrParams &p, const BrArr &a, const BrOut &o, int *lds, int inst,
                                                int w = 0) {
   static_assert(!COOP || E == 32, "the four-wave sort covers 4 x 512 keys");
@@ -67,7 +67,8 @@ __device__ __forceinline__ void br_assign_body(const BrParams &p, const BrArr &a
   int *adm = lds + NP;        // [NP] by sorted position: worker << 16 | slot, or -1
   int *who = lds + 2 * NP;    // [NP] by arrival position: worker, or -1
   int *slots = lds + 3 * NP;  // [64] k-th alive request of a Stage-1 level: s << 11 | sorted position
-  int *win = slots + BR_WAVE; // [8]  Stage-2 candidate window, same packing (16-byte aligned)
+  int *win = slots + BR_WAVE; // [8]  Stage-2 candidate window, same packing (16-byte aligned); BIGR: [16]
+  int *hitab = win + 16;      // BIGR: [1024] sums of the window entries 6.. selected by the upper mask bits
 
   const int lane = br_lane();
   const int G = p.G;
@@ -604,7 +605,43 @@ __device__ __forceinline__ void br_assign_body(const BrParams &p, const BrArr &a
       }
       int wv[8], ws[8];
       int bestmask = 0, bestkey = BR_KEY_NONE;
-      if (!guard_sure) {
+      if constexpr (BIGR) {
+        // Windows of up to 16 requests: lane l keeps the lower six mask bits, the upper bits c run over
+        // 2^(w-6) passes whose partial sums come from a table built here, 64 entries at a time.  A lane sees
+        // its masks in ascending order and keeps the first best; across lanes the lowest mask of the best
+        // score wins.
+#pragma unroll
+        for (int b = 0; b < 8; ++b) wv[b] = 0, ws[b] = 0;
+        if (!guard_sure) {
+          br_wave_sync();
+          const int nhi = w > 6 ? 1 << (w - 6) : 1;
+          for (int c0 = 0; c0 < nhi; c0 += BR_WAVE) {
+            const int c = c0 + lane;
+            int sum = 0;
+            for (int b = 6; b < w; ++b) sum += ((c >> (b - 6)) & 1) * (win[b] >> BR_IDX_BITS);
+            if (c < nhi) hitab[c] = sum;
+          }
+          int base = 0;
+          for (int b = 0; b < min(w, 6); ++b) base += ((lane >> b) & 1) * (win[b] >> BR_IDX_BITS);
+          br_wave_sync();
+          const int kmax = min(capmax, p.R_max);
+          const int nmask = 1 << w;
+          int bk = BR_KEY_NONE, bm = INT32_MAX;
+          for (int c = 0; c < nhi; ++c) {
+            const int delta = base + hitab[c];
+            const int mask = c * BR_WAVE + lane;
+            const bool ok = mask != 0 && mask < nmask && lpop + __builtin_popcount(c) <= kmax && delta <= room;
+            int key = br_score_key<BRH>(p, mg, delta);
+            key = ok ? key : BR_KEY_NONE;
+            if (key > bk) {
+              bk = key;
+              bm = mask;
+            }
+          }
+          bestkey = br_wave_max(bk);
+          bestmask = bestkey == BR_KEY_NONE ? 0 : br_wave_min(bk == bestkey ? bm : INT32_MAX);
+        }
+      } else if (!guard_sure) {
         br_wave_sync();
         {
           const int4 lo = *reinterpret_cast<const int4 *>(win);
@@ -677,21 +714,34 @@ __device__ __forceinline__ void br_assign_body(const BrParams &p, const BrArr &a
       } else {
         // lane b binds window entry b if chosen; slots follow the order of the window
         const int slot = __builtin_amdgcn_readlane(nn, g);
-        const bool mine = lane < 8 && ((bestmask >> lane) & 1);
-        if (mine) {
-          const int me = lane == 0 ? wv[0] : lane == 1 ? wv[1] : lane == 2 ? wv[2] : lane == 3 ? wv[3]
-                       : lane == 4 ? wv[4] : lane == 5 ? wv[5] : lane == 6 ? wv[6] : wv[7];
-          adm[me & IDX_MASK] = (g << 16) | (slot + __builtin_popcount(bestmask & ((1 << lane) - 1)));
-        }
         int delta = 0;
-#pragma unroll
-        for (int b = 0; b < 8; ++b)
-          if ((bestmask >> b) & 1) {
-            const int pb = wv[b] & IDX_MASK;
-            alive = (lane == (pb & 63)) ? (alive & ~(1u << (pb >> 6))) : alive;
-            tail_dirty |= pb == tail_pos;
-            delta += ws[b];
+        if constexpr (BIGR) {
+          if (lane < 16 && ((bestmask >> lane) & 1))
+            adm[win[lane] & IDX_MASK] = (g << 16) | (slot + __builtin_popcount(bestmask & ((1 << lane) - 1)));
+          for (int b = 0; b < w; ++b)
+            if ((bestmask >> b) & 1) {
+              const int e = win[b];
+              const int pb = e & IDX_MASK;
+              alive = (lane == (pb & 63)) ? (alive & ~(1u << (pb >> 6))) : alive;
+              tail_dirty |= pb == tail_pos;
+              delta += e >> BR_IDX_BITS;
+            }
+        } else {
+          const bool mine = lane < 8 && ((bestmask >> lane) & 1);
+          if (mine) {
+            const int me = lane == 0 ? wv[0] : lane == 1 ? wv[1] : lane == 2 ? wv[2] : lane == 3 ? wv[3]
+                         : lane == 4 ? wv[4] : lane == 5 ? wv[5] : lane == 6 ? wv[6] : wv[7];
+            adm[me & IDX_MASK] = (g << 16) | (slot + __builtin_popcount(bestmask & ((1 << lane) - 1)));
           }
+#pragma unroll
+          for (int b = 0; b < 8; ++b)
+            if ((bestmask >> b) & 1) {
+              const int pb = wv[b] & IDX_MASK;
+              alive = (lane == (pb & 63)) ? (alive & ~(1u << (pb >> 6))) : alive;
+              tail_dirty |= pb == tail_pos;
+              delta += ws[b];
+            }
+        }
         add_load(g, Lg, br_uniform(delta), __builtin_popcount(bestmask));
       }
     }
@@ -718,36 +768,43 @@ __device__ __forceinline__ void br_assign_body(const BrParams &p, const BrArr &a
 // every wave of the block owns one cluster and its own slice of LDS; waves never meet at a barrier
 // The BR-H kernel for queues of up to 512 needs one register more than lets four waves share a SIMD
 // (a batch of 4096 clusters is four waves per SIMD): it is asked to fit.
-template <int E, bool BRH, bool ADV>
-__global__ __launch_bounds__(256, (BRH && E == 8) ? 4 : 1) void br_k_assign(BrParams p, BrArr a, BrOut o) {
+// BIGR: candidate windows of 9..16 requests (R_max > 8); a separate instantiation so that the kernels for
+// the deployed window sizes keep their registers and code size.
+template <int E, bool BRH, bool ADV, bool BIGR = false>
+__global__ __launch_bounds__(256, (BRH && E == 8 && !BIGR) ? 4 : 1) void br_k_assign(BrParams p, BrArr a, BrOut o) {
   extern __shared__ int lds_all[];
+  constexpr int WORDS = 3 * E * BR_WAVE + BR_WAVE + (BIGR ? 16 + 1024 : 8);  // skey, adm, who, slots, win (+ table) per wave
   const int w = threadIdx.x >> 6;
   if constexpr (E == 32)  // one cluster per block, four waves for the sort
-    br_assign_body<E, BRH, ADV, true>(p, a, o, lds_all, (int)blockIdx.x, w);
+    br_assign_body<E, BRH, ADV, true, BIGR>(p, a, o, lds_all, (int)blockIdx.x, w);
   else
-    br_assign_body<E, BRH, ADV>(p, a, o, lds_all + w * (3 * E * BR_WAVE + BR_WAVE + 8), (int)(blockIdx.x * (blockDim.x >> 6)) + w);
+    br_assign_body<E, BRH, ADV, false, BIGR>(p, a, o, lds_all + w * WORDS, (int)(blockIdx.x * (blockDim.x >> 6)) + w);
 }
 
-template <int E, bool BRH>
+template <int E, bool BRH, bool BIGR = false>
 static void br_launch_assign_one(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st) {
   // several single-wave clusters share a block so that the chip's per-CU block slots do not cap residency
   const int wpb = E <= 8 ? 4 : 1;  // clusters per block
-  const size_t lds = (size_t)wpb * (3 * E * BR_WAVE + BR_WAVE + 8) * sizeof(int);  // skey, adm, who, slots, win per wave
+  const size_t lds = (size_t)wpb * (3 * E * BR_WAVE + BR_WAVE + (BIGR ? 16 + 1024 : 8)) * sizeof(int);
   const dim3 grid((unsigned)((p.N + wpb - 1) / wpb)), block(E == 32 ? 4 * BR_WAVE : BR_WAVE * wpb);
-  if (p.adv_t > 0)
-    hipLaunchKernelGGL((br_k_assign<E, BRH, true>), grid, block, lds, st, p, a, o);
-  else
-    hipLaunchKernelGGL((br_k_assign<E, BRH, false>), grid, block, lds, st, p, a, o);
+  if constexpr (BIGR) {  // no fused decode steps for these: the caller launches the decode kernel
+    hipLaunchKernelGGL((br_k_assign<E, BRH, false, true>), grid, block, lds, st, p, a, o);
+  } else {
+    if (p.adv_t > 0)
+      hipLaunchKernelGGL((br_k_assign<E, BRH, true>), grid, block, lds, st, p, a, o);
+    else
+      hipLaunchKernelGGL((br_k_assign<E, BRH, false>), grid, block, lds, st, p, a, o);
+  }
 }
 
-template <bool BRH>
+template <bool BRH, bool BIGR = false>
 static void br_launch_assign_sized(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st) {
   if (p.Q <= 256)
-    br_launch_assign_one<4, BRH>(p, a, o, st);
+    br_launch_assign_one<4, BRH, BIGR>(p, a, o, st);
   else if (p.Q <= 512)
-    br_launch_assign_one<8, BRH>(p, a, o, st);
+    br_launch_assign_one<8, BRH, BIGR>(p, a, o, st);
   else if (p.Q <= 1024)
-    br_launch_assign_one<16, BRH>(p, a, o, st);
+    br_launch_assign_one<16, BRH, BIGR>(p, a, o, st);
   else
-    br_launch_assign_one<32, BRH>(p, a, o, st);
+    br_launch_assign_one<32, BRH, BIGR>(p, a, o, st);
 }

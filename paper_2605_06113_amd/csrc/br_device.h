@@ -129,7 +129,7 @@ __device__ __forceinline__ float br_unord(int k) { return __int_as_float(k ^ ((k
 
 #define BR_KEY_NONE INT32_MIN
 
-// Sec. 3.1, eq. (br0-Fscore): F = Delta - G (Delta - m)_+ in exact int32.  Delta <= 8 * 32768 and
+// Sec. 3.1, eq. (br0-Fscore): F = Delta - G (Delta - m)_+ in exact int32.  Delta <= 16 * 32768 and
 // G <= 64, so both factors fit 24 bits; the masks say so and the product becomes one full-rate
 // 24-bit multiply-add instead of a quarter-rate 32-bit multiply.
 __device__ __forceinline__ int br_score0(int G, int m, int delta) {

@@ -16,6 +16,8 @@ void br_launch_score(const BrParams &p, const BrArr &a, const BrOut &o, hipStrea
 void br_launch_assign(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st);
 // horizons beyond BR_HP: per-offset state in LDS, one wave per cluster
 void br_launch_assign_long(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st);
+// candidate windows of 9..16 requests (H <= BR_HP); no fused decode steps
+void br_launch_assign_bigr(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st);
 void br_launch_assign_br0(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st);
 // BR-0, Q <= 256: snapshot reductions and assignment of four clusters per block in one launch
 void br_launch_route4(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st);

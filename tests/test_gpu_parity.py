@@ -70,6 +70,14 @@ CASES = [
     (64, 10, 2048, 80, dict(pred_mode=1, R_max=4, gamma=0.95)),
     (13, 30, 333, 63, dict(pred_mode=1, tie_heavy=True, token_watermark=40000)),
     (6, 12, 1000, 64, dict(pred_mode=1, gamma=1.0, S_greedy=0)),
+    # candidate windows of 9..16 requests (exhaustive search over up to 2^16 subsets per pop)
+    (16, 24, 256, 0, dict(R_max=12)),
+    (7, 12, 300, 0, dict(R_max=16, S_greedy=10 ** 6)),
+    (33, 40, 700, 0, dict(R_max=9, S_greedy=40, tie_heavy=True)),
+    (64, 20, 2048, 0, dict(R_max=10)),
+    (8, 24, 96, 4, dict(gate_pfin=0.0, R_max=16)),
+    (13, 30, 333, 8, dict(gate_pfin=0.3, R_max=11, tie_heavy=True)),
+    (16, 20, 1000, 3, dict(pred_mode=1, R_max=13, token_watermark=40000)),
 ]
 
 

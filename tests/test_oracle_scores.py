@@ -239,3 +239,42 @@ def test_subset_search_is_max_over_reachable_sums(orc, H):
             above = [d for d in sums if d > m[0]]
             probes = ([max(below)] if below else []) + ([min(above)] if above else [])
             assert best == max(scores[d] for d in probes)
+
+
+@pytest.mark.parametrize("H", [0, 6])
+def test_subset_search_matches_bitset_reduction(orc, H):
+    """Appendix "Bit-set subset selection": F_g(Q) depends on Q only through its sum, so the optimum over subsets of
+    at most k requests is the optimum of F over the sums reachable with 1..k requests.  The reachable sets are
+    built here by the shift-OR recurrence dp[j] |= dp[j-1] << s_i on Python integers (j descending), for windows
+    of up to 16 requests, and the exhaustive search must return that optimum with a subset that attains it."""
+    from paper_2605_06113_amd.workloads import RouteConfig
+    rng = np.random.default_rng(121 + H)
+    for _ in range(60):
+        G = int(rng.integers(2, 33))
+        R_max = int(rng.integers(9, 17))
+        cfg = RouteConfig(name="t", n_inst=1, G=G, B=32, max_wait=32, H=H, R_max=R_max, gamma=0.8)
+        P = orc.params_from(cfg)
+        w = int(rng.integers(R_max - 2, R_max + 1))
+        win = sorted(rng.integers(1, 2500, w).tolist(), reverse=True)
+        cap = int(rng.integers(1, 20))
+        kmax = min(cap, R_max)
+        m = rng.integers(0, 12000, H + 1)
+        dp = [0] * (kmax + 1)
+        dp[0] = 1
+        for s in win:
+            for j in range(kmax, 0, -1):
+                dp[j] |= dp[j - 1] << s
+        reach = 0
+        for j in range(1, kmax + 1):
+            reach |= dp[j]
+        sums = [b for b in range(reach.bit_length()) if reach >> b & 1]
+        if H == 0:
+            best = max(orc.score_br0(G, int(m[0]), d) for d in sums)
+        else:
+            best = max(orc.score_brh(H, cfg.alpha, cfg.beta_eff, cfg.gamma, m, d) for d in sums)
+        mask, f = orc.best_subset(P, m, 0, cap, win)
+        assert f == best
+        chosen = sum(win[b] for b in range(w) if mask >> b & 1)
+        assert reach >> chosen & 1 and 1 <= bin(mask).count("1") <= kmax
+        fc = orc.score_br0(G, int(m[0]), chosen) if H == 0 else orc.score_brh(H, cfg.alpha, cfg.beta_eff, cfg.gamma, m, chosen)
+        assert fc == best
