@@ -244,6 +244,41 @@ def bypass_run(device, cfg, init, arr, steps=6, warmup=2):
                 pairs_per_s=int(st[:, binding.ST["qlen"]].sum()) * cfg.G * steps / elapsed)
 
 
+def window_run(device, R_max=16, n_inst=1024, steps=4, warmup=1):
+    """Stage 2 with a wide candidate window: the c4 cluster shape with R_max = 16 and S_greedy = 64 as in the
+    main workload, so the last 64 free slots of a cluster (4 per worker) are filled by pops that search the
+    subsets of at most 4 out of 16 requests."""
+    import torch
+    from paper_2605_06113_amd import binding, workloads as wl
+    cfg = wl.config("c4", n_inst=n_inst, R_max=R_max, S_greedy=64)
+    init, arr = wl.initial_state(cfg), wl.initial_waiting(cfg)
+    routers = [binding.Router(cfg, init, device=device) for _ in range(steps + warmup)]
+    darr = binding.DeviceArrivals(arr, device, 0)
+    out = routers[0].alloc_outputs(scores=False)
+    for r in routers[:warmup]:
+        r.route_advance_device(darr, out, 1)
+    torch.cuda.synchronize()
+    for r in routers[warmup:]:
+        r.profile(True)
+    t0 = time.perf_counter()
+    for r in routers[warmup:]:
+        r.route_advance_device(darr, out, 1)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    st = out["stats"].cpu().numpy()
+    ms = cnt = 0
+    for r in routers[warmup:]:
+        m, c = r.profile_read()["assign"]
+        ms += m
+        cnt += c
+    for r in routers:
+        r.close()
+    pops, guard = int(st[:, binding.ST["stage2_pops"]].sum()), int(st[:, binding.ST["guard"]].sum())
+    return dict(workload=f"{n_inst} clusters of the c4 shape with R_max={R_max}, S_greedy=64: round + decode step",
+                ms_per_step=elapsed / steps * 1e3, assign_kernel_ms=ms / max(cnt, 1), stage2_pops=pops, guard_pops=guard,
+                decisions_per_s=int(st[:, binding.ST["admitted"]].sum()) * steps / elapsed)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -400,6 +435,7 @@ def main():
         res["brh_batched"] = brh_run(device)
         res["brh_batched_gate_off"] = brh_run(device, gate=0.0)   # hazards live: no request counts at the last offset
         res["brh_batched_h80"] = brh_run(device, deployed=True)
+        res["window16"] = window_run(device)
         res["bypass"] = bypass_run(device, cfg, init, arr)
         res["replay_batched"] = replay_run(device)
     if args.latency_steps > 0:

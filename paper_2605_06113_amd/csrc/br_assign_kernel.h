@@ -68,7 +68,7 @@ __device__ __forceinline__ void br_assign_body(const BrParams &p, const BrArr &a
   int *who = lds + 2 * NP;    // [NP] by arrival position: worker, or -1
   int *slots = lds + 3 * NP;  // [64] k-th alive request of a Stage-1 level: s << 11 | sorted position
   int *win = slots + BR_WAVE; // [8]  Stage-2 candidate window, same packing (16-byte aligned); BIGR: [16]
-  int *hitab = win + 16;      // BIGR: [1024] sums of the window entries 6.. selected by the upper mask bits
+  int *hitab = win + 16;      // BIGR: [1024] sums of the window entries 6.. selected by the upper mask bits (16-byte aligned)
 
   const int lane = br_lane();
   const int G = p.G;
@@ -627,16 +627,28 @@ __device__ __forceinline__ void br_assign_body(const BrParams &p, const BrArr &a
           const int kmax = min(capmax, p.R_max);
           const int nmask = 1 << w;
           int bk = BR_KEY_NONE, bm = INT32_MAX;
-          for (int c = 0; c < nhi; ++c) {
-            const int delta = base + hitab[c];
-            const int mask = c * BR_WAVE + lane;
-            const bool ok = mask != 0 && mask < nmask && lpop + __builtin_popcount(c) <= kmax && delta <= room;
-            int key = br_score_key<BRH>(p, mg, delta);
-            key = ok ? key : BR_KEY_NONE;
-            if (key > bk) {
-              bk = key;
-              bm = mask;
+          const int klim = kmax - lpop;         // bits the upper part of a mask may still add on this lane
+          const bool lane_ok = lane < nmask;    // (windows below six requests use the lower lanes only)
+          for (int c0 = 0; c0 < nhi; c0 += 4) {  // four passes per trip: one 16-byte table read, independent scores
+            if (__builtin_popcount(c0) > kmax) continue;  // c0 + u has at least the bits of c0: too many for every lane
+            const int4 h4 = *reinterpret_cast<const int4 *>(hitab + c0);
+            const int hd[4] = {h4.x, h4.y, h4.z, h4.w};
+            int key[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+              const int c = c0 + u;
+              const int delta = base + hd[u];
+              bool ok = lane_ok && c < nhi && __builtin_popcount(c) <= klim && delta <= room;
+              if (c == 0) ok = ok && lane != 0;  // the empty subset
+              const int k = br_score_key<BRH>(p, mg, ok ? delta : 0);
+              key[u] = ok ? k : BR_KEY_NONE;
             }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+              if (key[u] > bk) {
+                bk = key[u];
+                bm = (c0 + u) * BR_WAVE + lane;
+              }
           }
           bestkey = br_wave_max(bk);
           bestmask = bestkey == BR_KEY_NONE ? 0 : br_wave_min(bk == bestkey ? bm : INT32_MAX);
