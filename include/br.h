@@ -21,7 +21,7 @@
  *    nothing aborts.  Data-dependent conditions (a full waiting queue, a worker that
  *    can take nothing) are not errors: they are counted in the stats block.
  *  - Limits: G <= 64, B <= 1024, max_wait <= 2048, H <= 128 (H <= 8 with pred_mode 0),
- *    R_max <= 16 (<= 8 when H > 8), prefill length in [1, 32768] (values outside are clamped on arrival),
+ *    R_max <= 16, prefill length in [1, 32768] (values outside are clamped on arrival),
  *    per-worker load < 2^25.
  */
 #ifndef BR_H
@@ -89,7 +89,7 @@ typedef struct {
                               per-offset state moves from registers to on-chip memory (same results,
                               other kernels) and pred_mode must be 1 or 2 */
   int32_t S_greedy;        /* Stage 1 runs while total free slots > S_greedy; >= 0 */
-  int32_t R_max;           /* Stage-2 candidate window and subset size, 1..16 (1..8 when H > 8); every
+  int32_t R_max;           /* Stage-2 candidate window and subset size, 1..16; every
                               subset of the window is searched, exactly */
   int32_t token_watermark; /* 0 = off; else a request is admissible on g only if L_g + s <= watermark */
   int32_t token_cap;       /* 0 = off; reporting only (BR_ST_OVERCAP) */

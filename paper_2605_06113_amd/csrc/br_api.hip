@@ -30,7 +30,6 @@ bool config_ok(const br_config *c) {
   if (c->token_watermark < 0 || c->token_cap < 0) return false;
   if (c->pred_mode < 0 || c->pred_mode > 2) return false;
   if (c->H > BR_HP && c->pred_mode == 0) return false;  // a hazard per offset is carried for short horizons only
-  if (c->H > BR_HP && c->R_max > 8) return false;        // windows beyond 8 requests: short horizons only
   if (c->pred_mode == 2) {
     if (c->H == 0 || !c->hist || !c->hist_sum || c->hist_n < 1 || c->hist_n > (1 << 20) || c->refresh_period < 1)
       return false;

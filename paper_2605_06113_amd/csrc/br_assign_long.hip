@@ -44,6 +44,7 @@ __global__ __launch_bounds__(64) void br_k_assign_long(BrParams p, BrArr a, BrOu
   float *smg = (float *)(sM + HS);  // [HS] margins of the worker in hand, as floats
   float *sd = smg + HS;             // [HS] discounts, zero beyond H
   int *sL = sM + 3 * HS;            // [HS][65] step-start projections (rows beyond H: "no worker")
+  int *hitab = sL + ((HS * BR_LSTRIDE + 3) & ~3);  // R_max > 8: [1024] sums of window entries 6.. by upper mask bits
 
   const int lane = br_lane();
   const int G = p.G;
@@ -318,7 +319,65 @@ __global__ __launch_bounds__(64) void br_k_assign_long(BrParams p, BrArr a, BrOu
         }
       }
       br_wave_sync();
+      const int kmax = min(capmax, p.R_max);
+      const int nmask = 1 << w;
+      int bestmask = 0, bestkey = BR_KEY_NONE;
       int wv[8], ws[8];
+      if (p.R_max > 8) {
+        // Windows of up to 16 requests: lane l keeps the lower six mask bits, the upper bits run as passes
+        // over a table of their partial sums (built here, 64 entries per step), four passes per trip; trips
+        // whose upper bits alone exceed the cardinality limit are skipped.  A lane sees its masks in ascending
+        // order and keeps the first best; across lanes the lowest mask of the best score wins.
+#pragma unroll
+        for (int b = 0; b < 8; ++b) wv[b] = 0, ws[b] = 0;
+        const int nhi = w > 6 ? 1 << (w - 6) : 1;
+        for (int c0 = 0; c0 < nhi; c0 += BR_WAVE) {
+          const int c = c0 + lane;
+          int sum = 0;
+          for (int b = 6; b < w; ++b) sum += ((c >> (b - 6)) & 1) * (win[b] >> BR_IDX_BITS);
+          if (c < nhi) hitab[c] = sum;
+        }
+        int base = 0, top = 0;  // top: the largest sum any admissible subset can have (bound)
+        for (int b = 0; b < w; ++b) {
+          const int sb = win[b] >> BR_IDX_BITS;
+          if (b < 6) base += ((lane >> b) & 1) * sb;
+          if (b < kmax) top += sb;
+        }
+        top = min(top, room);
+        br_wave_sync();
+        unsigned long long act[3];
+        br_long_active(smg, HS, lane, top, act);
+        const int klim = kmax - lpop;
+        const bool lane_ok = lane < nmask;
+        int bk = BR_KEY_NONE, bm = INT32_MAX;
+        for (int c0 = 0; c0 < nhi; c0 += 4) {
+          if (__builtin_popcount(c0) > kmax) continue;
+          const int4 h4 = *reinterpret_cast<const int4 *>(hitab + c0);  // (entries beyond nhi: masks out of range)
+          const int hd[4] = {h4.x, h4.y, h4.z, h4.w};
+          int dv[4];
+          bool okv[4];
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            const int c = c0 + u;
+            const int delta = base + hd[u];
+            okv[u] = lane_ok && c < nhi && __builtin_popcount(c) <= klim && delta <= room && (c != 0 || lane != 0);
+            dv[u] = okv[u] ? delta : 0;
+          }
+          float Fv[4];
+          br_scoreh_long_act<4>(p.aD, p.beta, smg, sd, act, dv, Fv);
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            const int key = okv[u] ? br_ord(Fv[u]) : BR_KEY_NONE;
+            if (key > bk) {
+              bk = key;
+              bm = (c0 + u) * BR_WAVE + lane;
+            }
+          }
+        }
+        bestkey = br_wave_max(bk);
+        bestmask = bestkey == BR_KEY_NONE ? 0 : br_wave_min(bk == bestkey ? bm : INT32_MAX);
+        br_wave_sync();
+      } else {
       {
         const int4 lo = *reinterpret_cast<const int4 *>(win);
         const int4 hi = *reinterpret_cast<const int4 *>(win + 4);
@@ -331,9 +390,6 @@ __global__ __launch_bounds__(64) void br_k_assign_long(BrParams p, BrArr a, BrOu
 
       // exhaustive subset search: lane l of pass c stands for mask c*64 + l (ascending masks, a later
       // one wins only if strictly better)
-      const int kmax = min(capmax, p.R_max);
-      const int nmask = 1 << w;
-      int bestmask = 0, bestkey = BR_KEY_NONE;
       int dv[4];
       bool okv[4];
 #pragma unroll
@@ -375,6 +431,8 @@ __global__ __launch_bounds__(64) void br_k_assign_long(BrParams p, BrArr a, BrOu
         }
       }
 
+      }
+
       if (bestmask == 0 || bestkey <= 0) {  // starvation guard: the single best request anyway
         ++guard;
         int pos = 0, swin = 0;
@@ -387,20 +445,33 @@ __global__ __launch_bounds__(64) void br_k_assign_long(BrParams p, BrArr a, BrOu
       } else {
         // lane b binds window entry b if chosen; slots follow the order of the window
         const int slot = __builtin_amdgcn_readlane(nn, g);
-        const bool mine = lane < 8 && ((bestmask >> lane) & 1);
-        if (mine) {
-          const int me = lane == 0 ? wv[0] : lane == 1 ? wv[1] : lane == 2 ? wv[2] : lane == 3 ? wv[3]
-                       : lane == 4 ? wv[4] : lane == 5 ? wv[5] : lane == 6 ? wv[6] : wv[7];
-          adm[me & IDX_MASK] = (g << 16) | (slot + __builtin_popcount(bestmask & ((1 << lane) - 1)));
-        }
         int delta = 0;
-#pragma unroll
-        for (int b = 0; b < 8; ++b)
-          if ((bestmask >> b) & 1) {
-            const int pb = wv[b] & IDX_MASK;
-            alive = (lane == (pb & 63)) ? (alive & ~(1u << (pb >> 6))) : alive;
-            delta += ws[b];
+        if (p.R_max > 8) {
+          if (lane < 16 && ((bestmask >> lane) & 1))
+            adm[win[lane] & IDX_MASK] = (g << 16) | (slot + __builtin_popcount(bestmask & ((1 << lane) - 1)));
+          for (int b = 0; b < w; ++b)
+            if ((bestmask >> b) & 1) {
+              const int e = win[b];
+              const int pb = e & IDX_MASK;
+              alive = (lane == (pb & 63)) ? (alive & ~(1u << (pb >> 6))) : alive;
+              delta += e >> BR_IDX_BITS;
+            }
+          br_wave_sync();  // the window has been read before a later pop rewrites it
+        } else {
+          const bool mine = lane < 8 && ((bestmask >> lane) & 1);
+          if (mine) {
+            const int me = lane == 0 ? wv[0] : lane == 1 ? wv[1] : lane == 2 ? wv[2] : lane == 3 ? wv[3]
+                         : lane == 4 ? wv[4] : lane == 5 ? wv[5] : lane == 6 ? wv[6] : wv[7];
+            adm[me & IDX_MASK] = (g << 16) | (slot + __builtin_popcount(bestmask & ((1 << lane) - 1)));
           }
+#pragma unroll
+          for (int b = 0; b < 8; ++b)
+            if ((bestmask >> b) & 1) {
+              const int pb = wv[b] & IDX_MASK;
+              alive = (lane == (pb & 63)) ? (alive & ~(1u << (pb >> 6))) : alive;
+              delta += ws[b];
+            }
+        }
         add_load(g, br_uniform(delta), __builtin_popcount(bestmask));
       }
     }
@@ -421,7 +492,8 @@ __global__ __launch_bounds__(64) void br_k_assign_long(BrParams p, BrArr a, BrOu
 template <int E>
 static void br_launch_assign_long_one(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st) {
   const int HS = BR_HS(p.H);
-  const size_t lds = ((size_t)3 * E * BR_WAVE + BR_WAVE + 3 * (size_t)HS + (size_t)HS * BR_LSTRIDE) * sizeof(int);
+  const size_t lds = ((size_t)3 * E * BR_WAVE + BR_WAVE + 3 * (size_t)HS + (((size_t)HS * BR_LSTRIDE + 3) & ~(size_t)3) +
+                      (p.R_max > 8 ? 1024 : 0)) * sizeof(int);
   const dim3 grid((unsigned)p.N), block(BR_WAVE);
   if (p.adv_t > 0)
     hipLaunchKernelGGL((br_k_assign_long<E, true>), grid, block, lds, st, p, a, o);

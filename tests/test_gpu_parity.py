@@ -78,6 +78,8 @@ CASES = [
     (8, 24, 96, 4, dict(gate_pfin=0.0, R_max=16)),
     (13, 30, 333, 8, dict(gate_pfin=0.3, R_max=11, tie_heavy=True)),
     (16, 20, 1000, 3, dict(pred_mode=1, R_max=13, token_watermark=40000)),
+    (8, 16, 96, 80, dict(pred_mode=1, R_max=12, gamma=0.97)),
+    (5, 8, 600, 9, dict(pred_mode=1, R_max=16, S_greedy=10 ** 6)),
 ]
 
 
