@@ -137,59 +137,93 @@ __global__ __launch_bounds__(256) void br_k_project_rows(BrParams p) {
   }
 }
 
-// Horizons beyond BR_HP (Appendix "Projected workload"): a request counts kv + h at the offsets
-// h <= c_hat, so one histogram of floor(c_hat) per worker (count and kv sum, in LDS) and its suffix sums
-// give L_g(k+h) = sum_{c >= h} kvsum[c] + h * sum_{c >= h} count[c] without a register per offset.
-// One wave per worker; integer sums, so the order of accumulation does not matter.
+// Horizons beyond BR_HP (Appendix "Short-horizon prediction interface", eq. (wprofile-new)): a request counts
+// kv + h at the offsets h <= c_hat, so one histogram of floor(c_hat) per worker (count and kv sum, in LDS) and
+// its suffix sums give L_g(k+h) = sum_{c >= h} kvsum[c] + h * sum_{c >= h} count[c] without a register per
+// offset.  Integer sums, so the order of accumulation does not matter.  One block per cluster: each wave takes
+// every fourth worker list and leaves its row in an LDS tile as well; then, with threads mapped to offsets,
+// the envelope M_h = max_g L_g(k+h) and the margins, and with threads mapped to workers the horizon-min
+// margin (what br_k_envelope does for short horizons in a launch of its own).
 __global__ __launch_bounds__(256) void br_k_project_long(BrParams p) {
-  __shared__ int hist_all[4][2 * (BR_HL + 4)];
-  const int wave = threadIdx.x >> 6, lane = br_lane();
-  const int64_t row = (int64_t)blockIdx.x * 4 + wave;
-  if (row >= (int64_t)p.N * p.G) return;  // whole waves leave; no block-wide barrier below
-  const int H = p.H, H1 = H + 1;
-  int *cnt = hist_all[wave], *kvs = cnt + BR_HL + 4;
-  for (int h = lane; h < H1; h += BR_WAVE) cnt[h] = 0, kvs[h] = 0;
-  br_wave_sync();
-  const int n = min(max(p.n[row], 0), p.B);
-  const int64_t base = row * p.Bs;
+  extern __shared__ int lds[];
+  const int wave = threadIdx.x >> 6, lane = br_lane(), tid = threadIdx.x;
+  const int inst = blockIdx.x;
+  const int G = p.G, H = p.H, H1 = H + 1, HS = BR_HS(H);
+  int *tile = lds;                              // [G][HS] projections, then margins
+  int *cnt = lds + G * HS + wave * 2 * HS;      // this wave's histogram: requests whose last offset is c
+  int *kvs = cnt + HS;                          // ... and the sum of their kv
   const float Hf = (float)H;
-  int topc = 0, topk = 0;  // requests that reach the last offset (the gate's anchor: the common case)
-  for (int j0 = 0; j0 < n; j0 += BR_WAVE) {
-    const int j = j0 + lane;
-    int kv = 0, hm = -1;
-    if (j < n) {
-      kv = p.kv[base + j];
-      float c = p.pred[(base + j) * p.P];  // pred_mode 1 and 2 keep c_hat first
-      c = c < 1.0f ? 1.0f : c;
-      c = c > Hf ? Hf : c;
-      if (c >= 0.0f) hm = min((int)c, H);  // offsets h with (float)h <= c_hat are 0..floor(c_hat); a NaN counts nowhere
+  for (int g = wave; g < G; g += 4) {
+    const int64_t row = (int64_t)inst * G + g;
+    for (int h = lane; h < HS; h += BR_WAVE) cnt[h] = 0, kvs[h] = 0;
+    br_wave_sync();
+    const int n = min(max(p.n[row], 0), p.B);
+    const int64_t base = row * p.Bs;
+    int topc = 0, topk = 0;  // requests that reach the last offset (the gate's anchor: the common case)
+    for (int j0 = 0; j0 < n; j0 += BR_WAVE) {
+      const int j = j0 + lane;
+      int kv = 0, hm = -1;
+      if (j < n) {
+        kv = p.kv[base + j];
+        float c = p.pred[(base + j) * p.P];  // pred_mode 1 and 2 keep c_hat first
+        c = c < 1.0f ? 1.0f : c;
+        c = c > Hf ? Hf : c;
+        if (c >= 0.0f) hm = min((int)c, H);  // offsets h with (float)h <= c_hat are 0..floor(c_hat); a NaN counts nowhere
+      }
+      const bool top = hm == H;
+      topc += __builtin_popcountll(br_ballot(top));
+      topk += br_wave_sum(top ? kv : 0);
+      if (hm >= 0 && !top) {
+        atomicAdd(&cnt[hm], 1);
+        atomicAdd(&kvs[hm], kv);
+      }
     }
-    const bool top = hm == H;
-    topc += __builtin_popcountll(br_ballot(top));
-    topk += br_wave_sum(top ? kv : 0);
-    if (hm >= 0 && !top) {
-      atomicAdd(&cnt[hm], 1);
-      atomicAdd(&kvs[hm], kv);
+    br_wave_sync();
+    if (lane == 0) cnt[H] += topc, kvs[H] += topk;
+    br_wave_sync();
+    // suffix sums, four bins per trip: lane handles offsets lane, lane + 64, lane + 128
+    int C[3] = {0, 0, 0}, K[3] = {0, 0, 0};
+    for (int c4 = HS - 4; c4 >= 0; c4 -= 4) {
+      const int4 cc = *reinterpret_cast<const int4 *>(cnt + c4);
+      const int4 kk = *reinterpret_cast<const int4 *>(kvs + c4);
+      const int cv[4] = {cc.x, cc.y, cc.z, cc.w}, kv4[4] = {kk.x, kk.y, kk.z, kk.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+#pragma unroll
+        for (int u = 0; u < 3; ++u) {
+          const bool in = c4 + e >= lane + u * BR_WAVE;
+          C[u] += in ? cv[e] : 0;
+          K[u] += in ? kv4[e] : 0;
+        }
+      }
     }
-  }
-  br_wave_sync();
-  if (lane == 0) cnt[H] += topc, kvs[H] += topk;
-  br_wave_sync();
-  // suffix sums: lane handles offsets lane, lane + 64, lane + 128
-  int C[3] = {0, 0, 0}, K[3] = {0, 0, 0};
-  for (int c = H; c >= 0; --c) {
-    const int cc = cnt[c], kk = kvs[c];
 #pragma unroll
     for (int u = 0; u < 3; ++u) {
-      const bool in = c >= lane + u * BR_WAVE;
-      C[u] += in ? cc : 0;
-      K[u] += in ? kk : 0;
+      const int h = lane + u * BR_WAVE;
+      if (h < H1) {
+        const int v = K[u] + h * C[u];
+        p.Lh[row * H1 + h] = v;
+        tile[g * HS + h] = v;
+      }
+    }
+    br_wave_sync();  // the histogram is cleared again for this wave's next list
+  }
+  __syncthreads();
+  if (tid < H1) {  // thread = offset
+    int M = tile[tid];
+    for (int g = 1; g < G; ++g) M = max(M, tile[g * HS + tid]);
+    p.Mh[(int64_t)inst * H1 + tid] = M;
+    for (int g = 0; g < G; ++g) {
+      const int m = max(M - tile[g * HS + tid], 0);
+      p.mh[((int64_t)inst * G + g) * H1 + tid] = m;
+      tile[g * HS + tid] = m;
     }
   }
-#pragma unroll
-  for (int u = 0; u < 3; ++u) {
-    const int h = lane + u * BR_WAVE;
-    if (h < H1) p.Lh[row * H1 + h] = K[u] + h * C[u];
+  __syncthreads();
+  if (tid < G) {  // thread = worker
+    int mn = INT32_MAX;
+    for (int h = 0; h < H1; ++h) mn = min(mn, tile[tid * HS + h]);
+    p.minm[(int64_t)inst * G + tid] = mn;
   }
 }
 
@@ -433,9 +467,12 @@ void br_launch_discounts(const BrParams &p, float gamma, hipStream_t st) {
 }
 
 void br_launch_project(const BrParams &p, hipStream_t st) {
-  if (p.H > BR_HP)
-    hipLaunchKernelGGL(br_k_project_long, dim3((unsigned)(((int64_t)p.N * p.G + 3) / 4)), dim3(256), 0, st, p);
-  else if (p.B <= 64)
+  if (p.H > BR_HP) {  // projection, envelope and margins in one launch
+    const size_t lds = ((size_t)p.G + 8) * BR_HS(p.H) * sizeof(int);
+    hipLaunchKernelGGL(br_k_project_long, dim3((unsigned)p.N), dim3(256), lds, st, p);
+    return;
+  }
+  if (p.B <= 64)
     launch_project_rows<1, 4>(p, st);
   else if (p.B <= 128)
     launch_project_rows<2, 2>(p, st);
