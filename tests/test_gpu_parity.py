@@ -430,6 +430,53 @@ def test_brh_batched_bench_configuration(gate):
     r.close()
 
 
+def test_long_horizon_batched_bench_configuration():
+    """bench.py's batched leg at the paper's horizon and window (2048 clusters, H=80, G=8, R_max=4, estimate
+    maintained by the library) through the fused entry point: every instance."""
+    cfg = wl.config("c3", n_inst=2048, G=8, B=64, max_wait=256, H=80, R_max=4, pred_mode=2, token_watermark=0,
+                    token_cap=0, init_active_per_worker=48, init_kv_lo=256, init_kv_hi=8192, init_rem_lo=1,
+                    init_rem_hi=1024, init_waiting=256, seed=2100)
+    _say("H=80 batched full size")
+    hist = wl.output_history(cfg, 8000)
+    init, arr = wl.initial_state(cfg), wl.initial_waiting(cfg)
+    oc, r = br_oracle.OracleCluster(cfg, init, hist=hist), binding.Router(cfg, init, hist=hist)
+    ref = oc.route_step(arr, want_prep=True)
+    out = r.route_step(arr, matrix=False, advance=1)
+    from tests.parity import compare_prep
+    compare_prep(ref, r.state(), "h80 batch")
+    compare_outputs(ref, out, cfg, "h80 batch")
+    assert (ref["stats"][:, br_oracle.ST["admitted"]] == 128).all()
+    oc.advance(1)
+    compare_state(oc, r.state(), cfg, "h80 batch")
+    r.close()
+
+
+def test_wide_window_bench_configuration():
+    """bench.py's wide-window leg at full size (1024 clusters of the c4 shape, R_max=16, S_greedy=64) through the
+    fused entry point; the oracle enumerates 2^16 subsets per pop, so it checks 200 sampled clusters one by one
+    (clusters are independent), assignments, statistics and state."""
+    import dataclasses
+    cfg = wl.config("c4", n_inst=1024, R_max=16, S_greedy=64)
+    _say("wide window full size")
+    init, arr = wl.initial_state(cfg), wl.initial_waiting(cfg)
+    r = binding.Router(cfg, init)
+    out = r.route_step(arr, scores=False, advance=1)
+    st = r.state()
+    r.close()
+    pick = np.random.default_rng(5).choice(cfg.n_inst, 200, replace=False)
+    take = lambda obj: type(obj)(**{f.name: (None if getattr(obj, f.name) is None else getattr(obj, f.name)[pick])
+                                    for f in dataclasses.fields(obj)})
+    sub = dataclasses.replace(cfg, n_inst=len(pick))
+    oc = br_oracle.OracleCluster(sub, take(init))
+    ref = oc.route_step(take(arr), want_scores=False)
+    got = {k: out[k][pick] for k in ("assign", "assign_id", "stats")}
+    compare_outputs(ref, got, sub, "wide window")
+    assert (ref["stats"][:, br_oracle.ST["stage2_pops"]] > 8).all()
+    oc.advance(1)
+    compare_state(oc, {k: (v[pick] if isinstance(v, np.ndarray) and v.shape[:1] == (cfg.n_inst,) else v) for k, v in st.items()},
+                  sub, "wide window")
+
+
 def test_pool_bypass():
     """br_route_bypass against the oracle: placements, loads, slot tables, queue fallback, drops."""
     for seed, (G, B, Q, cap, fill, wm) in enumerate([(4, 8, 16, 40, 0.5, 0), (16, 144, 256, 256, 0.85, 0),
