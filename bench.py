@@ -57,7 +57,7 @@ def cpu_baseline(cfg, init, arr, min_seconds=10.0):
 
 def latency_run(steps, device, deployed=False):
     """Host wall-clock per round of one instance.  Default: the BR-H stress shape (G=64, H=8, queue cap 2048).
-    deployed: the setting of the paper's dispatch-overhead measurement (Sec. 5.4: G=8, R_max=4, H=80), the
+    deployed: the setting of the paper's dispatch-overhead measurement (Sec. 6.4: G=8, R_max=4, H=80), the
     estimate kept by the library with the empirical-survival estimator, workers near full."""
     import torch
     from paper_2605_06113_amd import binding, workloads as wl
@@ -105,7 +105,7 @@ def latency_run(steps, device, deployed=False):
         state = r.state()
         res["mean_us"] = float(lat.mean() * 1e6)
         res["final_active"] = int(state["n"].sum())
-        # context only: another machine, the production trace, a Python dispatcher (Sec. 5.4)
+        # context only: another machine, the production trace, a Python dispatcher (Sec. 6.4)
         res["paper_dispatch_ms"] = dict(p50=1.20, mean=1.34, p99=2.77)
     r.close()
     return res
