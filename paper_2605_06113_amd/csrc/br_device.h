@@ -235,49 +235,6 @@ __device__ __forceinline__ int br_score_key(const BrParams &p, const int (&m)[BR
   else return br_score0(p.G, m[0], delta);
 }
 
-// In-window contribution c_hat of one active request (Appendix "Short-horizon prediction
-// interface"): survival sum of the hazards = E[min(r, H)] (eq. (two-stage)/(composite)), the
-// p_fin gate and the floor of Appendix "Refresh logic", clip to [1, H].
-__device__ __forceinline__ float br_chat_vals(const BrParams &p, const float (&pr)[BR_HP]) {
-  const float Hf = (float)p.H;
-  float c;
-  if (p.pred_mode >= 1) {
-    c = pr[0];
-  } else {
-    float S = 1.0f;
-    c = 0.0f;
-#pragma unroll
-    for (int j = 0; j < BR_HP; ++j) {
-      if (j < p.H) {
-        c = __fadd_rn(c, S);
-        S = __fmul_rn(S, __fsub_rn(1.0f, pr[j]));
-      }
-    }
-    const float pfin = __fsub_rn(1.0f, S);
-    if (p.gate > 0.0f && pfin < p.gate) c = Hf;
-  }
-  c = c < 1.0f ? 1.0f : c;
-  c = c > Hf ? Hf : c;
-  return c;
-}
-
-// The P prediction inputs of one request, as wide loads when P is 4 or 8.
-__device__ __forceinline__ void br_load_pred(const BrParams &p, const float *src, float (&pr)[BR_HP]) {
-#pragma unroll
-  for (int j = 0; j < BR_HP; ++j) pr[j] = 0.0f;
-  if (p.P == 8) {
-    const float4 a = reinterpret_cast<const float4 *>(src)[0], b = reinterpret_cast<const float4 *>(src)[1];
-    pr[0] = a.x, pr[1] = a.y, pr[2] = a.z, pr[3] = a.w, pr[4] = b.x, pr[5] = b.y, pr[6] = b.z, pr[7] = b.w;
-  } else if (p.P == 4) {
-    const float4 a = reinterpret_cast<const float4 *>(src)[0];
-    pr[0] = a.x, pr[1] = a.y, pr[2] = a.z, pr[3] = a.w;
-  } else {
-#pragma unroll
-    for (int j = 0; j < BR_HP; ++j)
-      if (j < p.P) pr[j] = src[j];
-  }
-}
-
 // Empirical-survival estimate of the in-window contribution at age a (Appendix "Estimator
 // realizations"): with F the empirical CDF of the sorted output-length history,
 // p_fin = (F(a+H) - F(a)) / (1 - F(a)), mu_rem = mean of (o_j - a) over a < o_j <= a+H, then the

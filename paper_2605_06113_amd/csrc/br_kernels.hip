@@ -84,15 +84,25 @@ __global__ __launch_bounds__(256) void br_k_advance(BrParams p, int t) {
     }
   }
 }
-template <int NC, int RW>
+// The kernel is VALU-bound before it is HBM-bound (rocprofv3: ~500 vector instructions per wave with every
+// loop written for 8 offsets and run-time widths), so the horizon bucket HB (4 or 8 offsets beyond h = 0), EXACT
+// (H == HB: no per-offset conditions) and HAZ (a hazard per offset, else c_hat itself first in the row) are
+// compile-time.  c_hat of one active request (Appendix "Short-horizon prediction interface"): the survival sum
+// of the hazards = E[min(r, H)] (eq. (two-stage)/(composite)) in sequential fp32, the p_fin gate and the floor
+// of Appendix "Refresh logic", clip to [1, H]; or the supplied / maintained value, floored and clipped the
+// same way.  A request counts kv + h at the offsets
+// h <= floor(c_hat) (h is an integer, so that is (float)h <= c_hat; a NaN counts nowhere): per offset the kv
+// part is summed in a register and over the wave, the count comes from a ballot.
+template <int NC, int RW, int HB, bool EXACT, bool HAZ>
 __global__ __launch_bounds__(256) void br_k_project_rows(BrParams p) {
   const int64_t row0 = ((int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6)) * RW;
   const int64_t rows = (int64_t)p.N * p.G;
   if (row0 >= rows) return;
   const int lane = br_lane();
   const int H1 = p.H + 1;
+  const float Hf = (float)p.H;
   int n_g[RW], kv[RW][NC];
-  float pr[RW][NC][BR_HP];
+  float pr[RW][NC][HAZ ? HB : 1];
 #pragma unroll
   for (int r = 0; r < RW; ++r) n_g[r] = row0 + r < rows ? p.n[row0 + r] : 0;
 #pragma unroll
@@ -103,34 +113,62 @@ __global__ __launch_bounds__(256) void br_k_project_rows(BrParams p) {
       const int j = c * BR_WAVE + lane;
       const bool used = j < n_g[r];
       kv[r][c] = used ? p.kv[base + j] : 0;
-      if (used) {
-        br_load_pred(p, p.pred + (base + j) * p.P, pr[r][c]);
+      const float *src = p.pred + (base + j) * p.P;
+      if constexpr (!HAZ) {
+        pr[r][c][0] = used ? src[0] : 0.0f;
+      } else if constexpr (EXACT) {  // rows of HB floats: 16-byte loads
+#pragma unroll
+        for (int q = 0; q < HB; q += 4) {
+          const float4 v = used ? *reinterpret_cast<const float4 *>(src + q) : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+          pr[r][c][q] = v.x, pr[r][c][q + 1] = v.y, pr[r][c][q + 2] = v.z, pr[r][c][q + 3] = v.w;
+        }
       } else {
 #pragma unroll
-        for (int q = 0; q < BR_HP; ++q) pr[r][c][q] = 0.0f;
+        for (int q = 0; q < HB; ++q) pr[r][c][q] = (used && q < p.H) ? src[q] : 0.0f;
       }
     }
   }
 #pragma unroll
   for (int r = 0; r < RW; ++r) {
     if (row0 + r >= rows) break;
-    int acc[BR_HP + 1];
+    int acc[HB + 1], cnt[HB + 1];
 #pragma unroll
-    for (int h = 0; h <= BR_HP; ++h) acc[h] = 0;
+    for (int h = 0; h <= HB; ++h) acc[h] = 0, cnt[h] = 0;
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
       const int j = c * BR_WAVE + lane;
-      if (j < n_g[r]) {
-        const float ch = br_chat_vals(p, pr[r][c]);
+      float ch;
+      if constexpr (HAZ) {
+        float S = 1.0f;
+        ch = 0.0f;
 #pragma unroll
-        for (int h = 0; h <= BR_HP; ++h)
-          if (h <= p.H && (float)h <= ch) acc[h] += kv[r][c] + h;
+        for (int q = 0; q < HB; ++q) {
+          if (EXACT || q < p.H) {
+            ch = __fadd_rn(ch, S);
+            S = __fmul_rn(S, __fsub_rn(1.0f, pr[r][c][q]));
+          }
+        }
+        const float pfin = __fsub_rn(1.0f, S);
+        if (p.gate > 0.0f && pfin < p.gate) ch = Hf;
+      } else {
+        ch = pr[r][c][0];
+      }
+      ch = ch < 1.0f ? 1.0f : ch;
+      ch = ch > Hf ? Hf : ch;
+      const int hm = (j < n_g[r] && ch >= 1.0f) ? (int)ch : -1;  // last offset the request counts at
+#pragma unroll
+      for (int h = 0; h <= HB; ++h) {
+        if (EXACT || h <= p.H) {
+          const bool in = h <= hm;
+          acc[h] += in ? kv[r][c] : 0;
+          cnt[h] += __builtin_popcountll(br_ballot(in));
+        }
       }
     }
 #pragma unroll
-    for (int h = 0; h <= BR_HP; ++h) {
-      if (h <= p.H) {
-        const int v = br_wave_sum(acc[h]);
+    for (int h = 0; h <= HB; ++h) {
+      if (EXACT || h <= p.H) {
+        const int v = br_wave_sum(acc[h]) + h * cnt[h];
         if (lane == 0) p.Lh[(row0 + r) * H1 + h] = v;
       }
     }
@@ -456,10 +494,26 @@ void br_launch_advance(const BrParams &p, int t, hipStream_t st) {
     launch_advance<4, 2>(p, t, st);
 }
 
+template <int NC, int RW, int HB, bool EXACT>
+static void launch_project_rows_h(const BrParams &p, hipStream_t st) {
+  const int64_t waves = ((int64_t)p.N * p.G + RW - 1) / RW;
+  const dim3 grid((unsigned)((waves + 3) / 4)), block(256);
+  if (p.pred_mode == 0)
+    hipLaunchKernelGGL((br_k_project_rows<NC, RW, HB, EXACT, true>), grid, block, 0, st, p);
+  else
+    hipLaunchKernelGGL((br_k_project_rows<NC, RW, HB, EXACT, false>), grid, block, 0, st, p);
+}
+
 template <int NC, int RW>
 static void launch_project_rows(const BrParams &p, hipStream_t st) {
-  const int64_t waves = ((int64_t)p.N * p.G + RW - 1) / RW;
-  hipLaunchKernelGGL((br_k_project_rows<NC, RW>), dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, st, p);
+  if (p.H == 4)
+    launch_project_rows_h<NC, RW, 4, true>(p, st);
+  else if (p.H == 8)
+    launch_project_rows_h<NC, RW, 8, true>(p, st);
+  else if (p.H < 4)
+    launch_project_rows_h<NC, RW, 4, false>(p, st);
+  else
+    launch_project_rows_h<NC, RW, 8, false>(p, st);
 }
 
 void br_launch_discounts(const BrParams &p, float gamma, hipStream_t st) {
