@@ -114,6 +114,8 @@ def test_random_rounds(case):
     (33, 12, 100, 4, dict(gate_pfin=0.0)),
     (12, 6, 300, 8, dict(pred_mode=1)),
     (12, 10, 130, 3, dict(gate_pfin=0.5, gamma=0.64, beta=14.67, tie_heavy=True)),
+    (16, 12, 256, 0, dict(R_max=12)),                    # wide windows: reductions and round as separate launches
+    (8, 10, 100, 40, dict(pred_mode=1, gamma=0.97)),     # long horizon: block-per-cluster score kernel
 ])
 def test_many_small_clusters(G, B, Q, H, extra):
     """Batches of 2048 clusters and more with short queues take the one-wave-per-cluster score kernel
