@@ -87,7 +87,7 @@ typedef struct {
   int32_t max_wait;        /* capacity of the waiting queue per cluster, 1..2048 */
   int32_t H;               /* lookahead horizon, 0..128; 0 selects BR-0 (exact integers); beyond 8 the
                               per-offset state moves from registers to on-chip memory (same results,
-                              other kernels) and pred_mode must be 1 or 2 */
+                              other kernels) and pred_mode must not be 0 */
   int32_t S_greedy;        /* Stage 1 runs while total free slots > S_greedy; >= 0 */
   int32_t R_max;           /* Stage-2 candidate window and subset size, 1..16; every
                               subset of the window is searched, exactly */
@@ -97,7 +97,10 @@ typedef struct {
                               1 = one float per request holding c_hat directly,
                               2 = c_hat maintained by the library with the empirical-survival
                                   estimator and the refresh rules of Appendix "Refresh logic"
-                                  (arrivals carry no prediction inputs; needs hist below) */
+                                  (arrivals carry no prediction inputs; needs hist below),
+                              3 = two floats per request, the two stages (p_fin, mu_rem) of Appendix
+                                  "Short-horizon prediction interface": c_hat = (1 - p_fin) H + p_fin mu_rem
+                                  (eq. (composite)), gate on p_fin, floor 1, clip H */
   float alpha, beta, gamma; /* horizon score parameters, eq. (brh-Fscore); ignored when H == 0
                                (BR-0 is (1, G)); alpha > 0, beta >= 0, 0 < gamma <= 1 */
   float gate_pfin;          /* confidence gate on p_fin (Appendix "Refresh logic"); <= 0 disables */
@@ -116,7 +119,7 @@ typedef struct {
 /*
  * Optional active sets at step 0.  Dense lists: slots [0, n[i][g]) of worker g are used.
  * n [n_inst][G]; kv, rem [n_inst][G][B]; pred [n_inst][G][B][P] with P = H (pred_mode 0),
- * 1 (pred_mode 1) or 3 (pred_mode 2: c_hat, tokens generated so far, tokens since the last
+ * 1 (pred_mode 1), 2 (pred_mode 3) or 3 (pred_mode 2: c_hat, tokens generated so far, tokens since the last
  * estimator query), NULL when H == 0.  kv = current KV length (s_i + a_i), rem = decode
  * steps still to run (>= 1).  Copied into the workspace by br_init.
  */
@@ -130,7 +133,7 @@ typedef struct {
 /*
  * Requests that finished prefill since the previous round (they join R_wait in this order).
  * count [n_inst]; s, o, id [n_inst][arr_cap]; pred [n_inst][arr_cap][Pq] with Pq = H (pred_mode 0),
- * 1 (pred_mode 1) or 0 (pred_mode 2 and BR-0: pred is ignored).
+ * 1 (pred_mode 1), 2 (pred_mode 3) or 0 (pred_mode 2 and BR-0: pred is ignored).
  * s = prefill length s_i; o = output length o_i (never read by the routing decision, only
  * stored for br_advance_decode; values < 1 count as 1); id = caller's request handle
  * (NULL: the position within this batch is used).

@@ -82,7 +82,11 @@ float orc_chat(int32_t H, int32_t pred_mode, float gate_pfin, const float *p) {
   float c;
   float Hf = (float)H;
   if (H == 0) return 0.0f;
-  if (pred_mode >= 1) {
+  if (pred_mode == 3) { /* the two stages themselves: eq. (composite) on (p_fin, mu_rem), same gate */
+    float pfin = p[0], mu = p[1];
+    c = (1.0f - pfin) * Hf + pfin * mu;
+    if (gate_pfin > 0.0f && pfin < gate_pfin) c = Hf;
+  } else if (pred_mode >= 1) {
     c = p[0];
   } else {
     float S = 1.0f, pfin;
@@ -103,7 +107,7 @@ float orc_chat(int32_t H, int32_t pred_mode, float gate_pfin, const float *p) {
 /* floats kept per active request / per waiting request */
 static int32_t pred_width(const orc_params *P) {
   if (P->H == 0) return 0;
-  return P->pred_mode == 2 ? 3 : (P->pred_mode == 1 ? 1 : P->H);
+  return P->pred_mode == 2 ? 3 : (P->pred_mode == 3 ? 2 : (P->pred_mode == 1 ? 1 : P->H));
 }
 
 static int32_t queue_pred_width(const orc_params *P) { return P->pred_mode == 2 ? 0 : pred_width(P); }

@@ -71,7 +71,8 @@ typedef struct {
   int32_t R_max, S_greedy;
   int32_t token_watermark, token_cap;
   int32_t pred_mode; /* 0: per-step hazards p[1..H]; 1: direct c_hat (one float);
-                        2: empirical-survival estimator maintained per request (c_hat, age, since-refresh) */
+                        2: empirical-survival estimator maintained per request (c_hat, age, since-refresh);
+                        3: the two-stage pair (p_fin, mu_rem) per request, combined by eq. (composite) */
   int32_t force_float; /* evaluate the horizon score in fp32 even when H == 0 (reduction check) */
   float alpha, beta, gamma, gate_pfin;
   /* pred_mode 2: sorted history of output lengths, its prefix sums (hist_sum[k] = sum of the first k),

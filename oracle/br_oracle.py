@@ -146,7 +146,7 @@ class OracleCluster:
         self.params = params_from(cfg, force_float, hist)
         N, G, B, Q, H = cfg.n_inst, cfg.G, cfg.B, cfg.max_wait, cfg.H
         self.N, self.G, self.B, self.Q, self.H = N, G, B, Q, H
-        self.P = 0 if H == 0 else (3 if cfg.pred_mode == 2 else (1 if cfg.pred_mode == 1 else H))
+        self.P = 0 if H == 0 else {1: 1, 2: 3, 3: 2}.get(cfg.pred_mode, H)
         self.Pq = 0 if cfg.pred_mode == 2 else self.P
         self.use_float = H > 0 or force_float
         self.L = np.zeros((N, G), np.int64)

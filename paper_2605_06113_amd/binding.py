@@ -159,7 +159,7 @@ class Router:
         self.cfg = cfg
         self.device = torch.device(device)
         self.N, self.G, self.B, self.Q, self.H = cfg.n_inst, cfg.G, cfg.B, cfg.max_wait, cfg.H
-        self.P = 0 if cfg.H == 0 else (3 if cfg.pred_mode == 2 else (1 if cfg.pred_mode == 1 else cfg.H))
+        self.P = 0 if cfg.H == 0 else {1: 1, 2: 3, 3: 2}.get(cfg.pred_mode, cfg.H)
         self.Pq = 0 if cfg.pred_mode == 2 else self.P
         self._hist = None
         hargs = {}

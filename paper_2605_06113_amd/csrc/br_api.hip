@@ -18,7 +18,10 @@ struct EvPair {
 
 uint64_t align_up(uint64_t x) { return (x + 255u) & ~(uint64_t)255u; }
 
-int pred_width(const br_config &c) { return c.H == 0 ? 0 : (c.pred_mode == 2 ? 3 : (c.pred_mode == 1 ? 1 : c.H)); }
+int pred_width(const br_config &c) {
+  if (c.H == 0) return 0;
+  return c.pred_mode == 2 ? 3 : (c.pred_mode == 3 ? 2 : (c.pred_mode == 1 ? 1 : c.H));
+}
 
 int queue_pred_width(const br_config &c) { return c.pred_mode == 2 ? 0 : pred_width(c); }
 
@@ -28,7 +31,7 @@ bool config_ok(const br_config *c) {
   if (c->max_wait < 1 || c->max_wait > BR_MAX_WAIT || c->H < 0 || c->H > BR_MAX_H) return false;
   if (c->R_max < 1 || c->R_max > BR_MAX_RMAX || c->S_greedy < 0) return false;
   if (c->token_watermark < 0 || c->token_cap < 0) return false;
-  if (c->pred_mode < 0 || c->pred_mode > 2) return false;
+  if (c->pred_mode < 0 || c->pred_mode > 3) return false;
   if (c->H > BR_HP && c->pred_mode == 0) return false;  // a hazard per offset is carried for short horizons only
   if (c->pred_mode == 2) {
     if (c->H == 0 || !c->hist || !c->hist_sum || c->hist_n < 1 || c->hist_n > (1 << 20) || c->refresh_period < 1)

@@ -86,15 +86,16 @@ __global__ __launch_bounds__(256) void br_k_advance(BrParams p, int t) {
 }
 // The kernel is VALU-bound before it is HBM-bound (rocprofv3: ~500 vector instructions per wave with every
 // loop written for 8 offsets and run-time widths), so the horizon bucket HB (4 or 8 offsets beyond h = 0), EXACT
-// (H == HB: no per-offset conditions) and HAZ (a hazard per offset, else c_hat itself first in the row) are
-// compile-time.  c_hat of one active request (Appendix "Short-horizon prediction interface"): the survival sum
+// (H == HB: no per-offset conditions) and the kind of prediction row PK (0: a hazard per offset, 1: c_hat
+// itself first in the row, 2: the pair (p_fin, mu_rem)) are compile-time.  c_hat of one active request (Appendix "Short-horizon prediction interface"): the survival sum
 // of the hazards = E[min(r, H)] (eq. (two-stage)/(composite)) in sequential fp32, the p_fin gate and the floor
-// of Appendix "Refresh logic", clip to [1, H]; or the supplied / maintained value, floored and clipped the
-// same way.  A request counts kv + h at the offsets
+// of Appendix "Refresh logic", clip to [1, H]; or eq. (composite) on a supplied (p_fin, mu_rem) with the same gate;
+// or the supplied / maintained value itself; all floored and clipped the same way.  A request counts kv + h at the offsets
 // h <= floor(c_hat) (h is an integer, so that is (float)h <= c_hat; a NaN counts nowhere): per offset the kv
 // part is summed in a register and over the wave, the count comes from a ballot.
-template <int NC, int RW, int HB, bool EXACT, bool HAZ>
+template <int NC, int RW, int HB, bool EXACT, int PK>
 __global__ __launch_bounds__(256) void br_k_project_rows(BrParams p) {
+  constexpr bool HAZ = PK == 0;
   const int64_t row0 = ((int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6)) * RW;
   const int64_t rows = (int64_t)p.N * p.G;
   if (row0 >= rows) return;
@@ -102,7 +103,7 @@ __global__ __launch_bounds__(256) void br_k_project_rows(BrParams p) {
   const int H1 = p.H + 1;
   const float Hf = (float)p.H;
   int n_g[RW], kv[RW][NC];
-  float pr[RW][NC][HAZ ? HB : 1];
+  float pr[RW][NC][HAZ ? HB : (PK == 2 ? 2 : 1)];
 #pragma unroll
   for (int r = 0; r < RW; ++r) n_g[r] = row0 + r < rows ? p.n[row0 + r] : 0;
 #pragma unroll
@@ -114,7 +115,10 @@ __global__ __launch_bounds__(256) void br_k_project_rows(BrParams p) {
       const bool used = j < n_g[r];
       kv[r][c] = used ? p.kv[base + j] : 0;
       const float *src = p.pred + (base + j) * p.P;
-      if constexpr (!HAZ) {
+      if constexpr (PK == 2) {
+        const float2 v = used ? *reinterpret_cast<const float2 *>(src) : make_float2(0.0f, 0.0f);
+        pr[r][c][0] = v.x, pr[r][c][1] = v.y;
+      } else if constexpr (!HAZ) {
         pr[r][c][0] = used ? src[0] : 0.0f;
       } else if constexpr (EXACT) {  // rows of HB floats: 16-byte loads
 #pragma unroll
@@ -150,6 +154,10 @@ __global__ __launch_bounds__(256) void br_k_project_rows(BrParams p) {
         }
         const float pfin = __fsub_rn(1.0f, S);
         if (p.gate > 0.0f && pfin < p.gate) ch = Hf;
+      } else if constexpr (PK == 2) {
+        const float pf = pr[r][c][0], mu = pr[r][c][1];
+        ch = __fadd_rn(__fmul_rn(__fsub_rn(1.0f, pf), Hf), __fmul_rn(pf, mu));
+        if (p.gate > 0.0f && pf < p.gate) ch = Hf;
       } else {
         ch = pr[r][c][0];
       }
@@ -204,6 +212,11 @@ __global__ __launch_bounds__(256) void br_k_project_long(BrParams p) {
       if (j < n) {
         kv = p.kv[base + j];
         float c = p.pred[(base + j) * p.P];  // pred_mode 1 and 2 keep c_hat first
+        if (p.pred_mode == 3) {              // the pair (p_fin, mu_rem): eq. (composite) and the gate
+          const float pf = c, mu = p.pred[(base + j) * p.P + 1];
+          c = __fadd_rn(__fmul_rn(__fsub_rn(1.0f, pf), Hf), __fmul_rn(pf, mu));
+          if (p.gate > 0.0f && pf < p.gate) c = Hf;
+        }
         c = c < 1.0f ? 1.0f : c;
         c = c > Hf ? Hf : c;
         if (c >= 0.0f) hm = min((int)c, H);  // offsets h with (float)h <= c_hat are 0..floor(c_hat); a NaN counts nowhere
@@ -499,9 +512,11 @@ static void launch_project_rows_h(const BrParams &p, hipStream_t st) {
   const int64_t waves = ((int64_t)p.N * p.G + RW - 1) / RW;
   const dim3 grid((unsigned)((waves + 3) / 4)), block(256);
   if (p.pred_mode == 0)
-    hipLaunchKernelGGL((br_k_project_rows<NC, RW, HB, EXACT, true>), grid, block, 0, st, p);
+    hipLaunchKernelGGL((br_k_project_rows<NC, RW, HB, EXACT, 0>), grid, block, 0, st, p);
+  else if (p.pred_mode == 3)
+    hipLaunchKernelGGL((br_k_project_rows<NC, RW, HB, EXACT, 2>), grid, block, 0, st, p);
   else
-    hipLaunchKernelGGL((br_k_project_rows<NC, RW, HB, EXACT, false>), grid, block, 0, st, p);
+    hipLaunchKernelGGL((br_k_project_rows<NC, RW, HB, EXACT, 1>), grid, block, 0, st, p);
 }
 
 template <int NC, int RW>

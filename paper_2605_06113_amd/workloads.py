@@ -44,7 +44,7 @@ class RouteConfig:
     beta: float = -1.0          # -1 => float(G)
     gamma: float = 0.9
     gate_pfin: float = 0.5
-    pred_mode: int = 0          # 0 hazards p[1..H], 1 direct c_hat, 2 empirical-survival estimator
+    pred_mode: int = 0          # 0 hazards p[1..H], 1 direct c_hat, 2 empirical-survival estimator, 3 (p_fin, mu_rem)
     refresh_period: int = 0     # pred_mode 2: tokens between predictor refreshes (0 => max(H // 2, 1))
     steps: int = 1
     seed: int = 0
@@ -133,6 +133,11 @@ def hazards(rng, cfg: RouteConfig, size) -> np.ndarray:
         return np.zeros(tuple(np.atleast_1d(size)) + (0,), np.float32)
     if cfg.pred_mode == 1:
         return rng.uniform(0.0, cfg.H + 0.5, size=size).astype(np.float32)
+    if cfg.pred_mode == 3:   # a classifier's p_fin (mass at both ends) and a regressor's mu_rem
+        shape = tuple(np.atleast_1d(size))
+        pf = np.where(rng.random(shape) < 0.5, rng.beta(0.6, 0.6, size=shape), rng.beta(cfg.beta_a, cfg.beta_b, size=shape))
+        mu = rng.uniform(0.0, cfg.H + 0.5, size=shape)
+        return np.stack([pf, mu], axis=-1).astype(np.float32)
     shape = tuple(np.atleast_1d(size)) + (cfg.H,)
     return rng.beta(cfg.beta_a, cfg.beta_b, size=shape).astype(np.float32)
 
@@ -195,7 +200,7 @@ def slot_pred_width(cfg: RouteConfig) -> int:
     query) when the library maintains the estimate itself (pred_mode 2)."""
     if cfg.H == 0:
         return 0
-    return 3 if cfg.pred_mode == 2 else (1 if cfg.pred_mode == 1 else cfg.H)
+    return {1: 1, 2: 3, 3: 2}.get(cfg.pred_mode, cfg.H)
 
 
 def maintained_triples(rng, cfg: RouteConfig, size) -> np.ndarray:
@@ -214,7 +219,7 @@ def pred_width(cfg: RouteConfig) -> int:
     """Floats a waiting request / an arrival carries for the prediction interface."""
     if cfg.H == 0 or cfg.pred_mode == 2:
         return 0
-    return 1 if cfg.pred_mode == 1 else cfg.H
+    return {1: 1, 3: 2}.get(cfg.pred_mode, cfg.H)
 
 
 def output_history(cfg: RouteConfig, n: int = 4096) -> np.ndarray:

@@ -80,6 +80,10 @@ CASES = [
     (16, 20, 1000, 3, dict(pred_mode=1, R_max=13, token_watermark=40000)),
     (8, 16, 96, 80, dict(pred_mode=1, R_max=12, gamma=0.97)),
     (5, 8, 600, 9, dict(pred_mode=1, R_max=16, S_greedy=10 ** 6)),
+    # the two stages (p_fin, mu_rem) supplied per request
+    (16, 20, 256, 6, dict(pred_mode=3, gate_pfin=0.5)),
+    (32, 100, 512, 4, dict(pred_mode=3, gate_pfin=0.0)),
+    (8, 16, 96, 80, dict(pred_mode=3, gate_pfin=0.5, gamma=0.97)),
 ]
 
 
@@ -232,7 +236,7 @@ def test_random_shapes_horizon(long_h):
         B = int(rng.integers(2, 50))
         N = int(rng.choice([3, 16, 64])) if Q < 1024 else 4
         H = int(rng.choice([9, 12, 16, 33, 64, 65, 80, 127, 128])) if long_h else int(rng.integers(1, 9))
-        mode = int(rng.choice([1, 2])) if long_h else int(rng.choice([0, 0, 1, 2]))
+        mode = int(rng.choice([1, 2, 3])) if long_h else int(rng.choice([0, 0, 1, 2, 3]))
         kw = dict(R_max=int(rng.choice([1, 2, 4, 4, 8])), gate_pfin=float(rng.choice([0.0, 0.3, 0.5])),
                   gamma=float(rng.choice([0.9, 0.97, 1.0] if long_h else [0.64, 0.9, 1.0])),
                   beta=float(rng.choice([-1.0, 14.67, 0.5, 2.0])),

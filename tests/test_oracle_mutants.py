@@ -30,7 +30,11 @@ MUTANTS = [
     ("brh alpha and beta swapped", "return S->aD * (float)delta - S->beta * pen;", "return S->beta * (float)delta - S->aD * pen;"),
     # in-window contribution
     ("survival sum shifted by one", "c = c + S;\n      S = S * (1.0f - p[j - 1]);", "S = S * (1.0f - p[j - 1]);\n      c = c + S;"),
-    ("gate inverted", "pfin < gate_pfin) c = Hf;", "pfin > gate_pfin) c = Hf;"),
+    ("gate inverted", "pfin = 1.0f - S;\n    if (gate_pfin > 0.0f && pfin < gate_pfin) c = Hf;",
+     "pfin = 1.0f - S;\n    if (gate_pfin > 0.0f && pfin > gate_pfin) c = Hf;"),
+    ("pair: regressor term unweighted", "c = (1.0f - pfin) * Hf + pfin * mu;", "c = (1.0f - pfin) * Hf + mu;"),
+    ("pair: gate inverted", "c = (1.0f - pfin) * Hf + pfin * mu;\n    if (gate_pfin > 0.0f && pfin < gate_pfin) c = Hf;",
+     "c = (1.0f - pfin) * Hf + pfin * mu;\n    if (gate_pfin > 0.0f && pfin > gate_pfin) c = Hf;"),
     ("floor dropped", "  if (c < 1.0f) c = 1.0f;\n  if (c > Hf) c = Hf;\n  return c;\n}\n\n/* floats kept", "  if (c > Hf) c = Hf;\n  return c;\n}\n\n/* floats kept"),
     # projection, envelope, margins
     ("projection cut one offset early", "if ((float)h <= c) R->Lh[g][h] += kv + h;", "if ((float)h < c) R->Lh[g][h] += kv + h;"),

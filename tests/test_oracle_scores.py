@@ -174,6 +174,26 @@ def test_chat_equals_two_stage_composite(orc):
         assert abs(c - max(ref, 1.0)) <= 1e-5 * H
 
 
+def test_chat_from_two_stage_pair(orc):
+    """pred_mode 3: eq. (composite) on a supplied (p_fin, mu_rem): c_hat = (1 - p_fin) H + p_fin mu_rem, gate on
+    p_fin, floor 1, clip H; against fp64 and at the corners."""
+    rng = np.random.default_rng(14)
+    for _ in range(3000):
+        H = int(rng.integers(1, 129))
+        pf, mu = float(np.float32(rng.uniform(0, 1))), float(np.float32(rng.uniform(0, H + 1)))
+        c = orc.chat(H, 3, 0.0, [pf, mu])
+        ref = min(max((1.0 - pf) * H + pf * mu, 1.0), float(H))
+        assert abs(c - ref) <= 1e-5 * H
+        gate = 0.5
+        cg = orc.chat(H, 3, gate, [pf, mu])
+        assert cg == (float(H) if pf < gate else c)
+    assert orc.chat(80, 3, 0.0, [0.0, 7.0]) == 80.0          # surely not finishing in the window: the anchor H
+    assert orc.chat(80, 3, 0.0, [1.0, 7.0]) == 7.0           # surely finishing: the regressor's value
+    assert orc.chat(80, 3, 0.0, [1.0, 0.25]) == 1.0          # floor
+    assert orc.chat(80, 3, 0.0, [0.5, 200.0]) == 80.0        # clip
+    assert orc.chat(80, 3, 0.5, [0.5, 10.0]) == 45.0         # at the gate the estimate is used: 0.5 * 80 + 0.5 * 10
+
+
 def test_chat_special_cases(orc):
     for H in [1, 2, 4, 8, 80]:
         assert orc.chat(H, 0, 0.0, np.zeros(H)) == float(H)            # never finishes in window
