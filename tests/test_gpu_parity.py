@@ -84,6 +84,8 @@ CASES = [
     (16, 20, 256, 6, dict(pred_mode=3, gate_pfin=0.5)),
     (32, 100, 512, 4, dict(pred_mode=3, gate_pfin=0.0)),
     (8, 16, 96, 80, dict(pred_mode=3, gate_pfin=0.5, gamma=0.97)),
+    # the largest LDS footprint: longest queue, longest horizon, widest window
+    (3, 6, 2048, 128, dict(pred_mode=1, R_max=16, gamma=0.99)),
 ]
 
 
