@@ -251,13 +251,15 @@ static int32_t route(br_ctx *ctx, const br_arrivals *in, const br_step_out *out,
   p.adv_t = split_adv ? 0 : adv_t;
   int32_t rc = BR_OK;
   if (p.H > 0) rc = enqueue(ctx, BR_K_PROJECT, [&] { br_launch_project(p, ctx->st); });
-  // large batches of BR-0 clusters with short queues: the reductions ride along in the assignment launch
-  const bool together =
-      (o.best_g || o.best_i) && !o.F && p.H == 0 && p.Q <= 256 && p.N >= BR_SCORE_WAVE_MIN_N && p.R_max <= 8;
+  // large batches of clusters with short queues: the reductions ride along in the assignment launch
+  const bool together = (o.best_g || o.best_i) && !o.F && p.N >= BR_SCORE_WAVE_MIN_N && p.R_max <= 8 &&
+                        (p.H == 0 ? p.Q <= 256 : (p.H <= BR_HP && p.Q <= 512));
   if (rc == BR_OK && !together && (o.F || o.best_g || o.best_i))
     rc = enqueue(ctx, BR_K_SCORE, [&] { br_launch_score(p, a, o, ctx->st); });
   if (rc == BR_OK) {
-    if (together)
+    if (together && p.H > 0)
+      rc = enqueue(ctx, BR_K_ASSIGN, [&] { br_launch_route_h(p, a, o, ctx->st); });
+    else if (together)
       rc = enqueue(ctx, BR_K_ASSIGN, [&] { br_launch_route4(p, a, o, ctx->st); });
     else
       rc = enqueue(ctx, BR_K_ASSIGN, [&] { br_launch_assign(p, a, o, ctx->st); });

@@ -21,4 +21,6 @@ void br_launch_assign_bigr(const BrParams &p, const BrArr &a, const BrOut &o, hi
 void br_launch_assign_br0(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st);
 // BR-0, Q <= 256: snapshot reductions and assignment of four clusters per block in one launch
 void br_launch_route4(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st);
+// BR-H (H <= BR_HP), Q <= 512: the same in one launch per four clusters
+void br_launch_route_h(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st);
 void br_launch_bypass(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st);
