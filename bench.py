@@ -29,8 +29,8 @@ HBM_PEAK_GBS = 8000.0
 ALU_INT_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 # HBM KiB per launch on this workload from rocprofv3 --pmc (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, see
 # profiles/bench_c4_kernels.md); an entry is None when its kernel changed after the counters were taken
-TRAFFIC_KIB = {"assign+advance": 2.0 * 43722.7 + 92332.9,   # br_k_route4<true>: reductions + round + decode step
-               "assign": 2.0 * 6773.5 + 21800.7, "advance": 2.0 * 37923.1 + 74528.2}
+TRAFFIC_KIB = {"assign+advance": 2.0 * 43722.3 + 92350.7,   # br_k_route4<true>: reductions + round + decode step
+               "assign": 2.0 * 6773.5 + 21800.9, "advance": 2.0 * 37922.3 + 74527.8}
 
 
 def cpu_baseline(cfg, init, arr, min_seconds=10.0):
