@@ -29,6 +29,8 @@ HBM_PEAK_GBS = 8000.0
 ALU_INT_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 # HBM KiB per launch on this workload from rocprofv3 --pmc (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, see
 # profiles/bench_c4_kernels.md); an entry is None when its kernel changed after the counters were taken
+LDS_PEAK_GBS = 256 * 128 * 2.4          # 256 CUs x 128 B per clock x 2.4 GHz
+LDS_INSTS_PER_WAVE = 236.1              # br_k_route4 (c4), rocprofv3 --pmc SQ_INSTS_LDS / SQ_WAVES
 TRAFFIC_KIB = {"assign+advance": 2.0 * 43722.3 + 92350.7,   # br_k_route4<true>: reductions + round + decode step
                "assign": 2.0 * 6773.5 + 21800.9, "advance": 2.0 * 37922.3 + 74527.8}
 
@@ -410,6 +412,13 @@ def main():
     kib = args.traffic_kib if args.traffic_kib is not None else TRAFFIC_KIB.get(dom + ("+advance" if fused else ""))
     roofline["traffic"] = None if kib is None else kib * 1024.0
     roofline["avg_launch_ms"] = d["avg_ms"]
+    if dom == "assign":
+        # LDS traffic of the round kernel: instructions per wave from rocprofv3 --pmc SQ_INSTS_LDS (profiles/), taken
+        # as 64 lanes x 4 B each, against 128 B per clock and CU; the dependent chain lives in registers and DPP
+        lds_bytes = LDS_INSTS_PER_WAVE * 64 * 4 * cfg.n_inst
+        lds_gbs = lds_bytes / (d["avg_ms"] * 1e-3) / 1e9
+        roofline["lds"] = dict(achieved_GBs=lds_gbs, peak_GBs=LDS_PEAK_GBS, frac=lds_gbs / LDS_PEAK_GBS,
+                               insts_per_wave=LDS_INSTS_PER_WAVE)
     step_bytes = bytes_advance + bytes_score + bytes_assign
     ms_per_step = elapsed / K * 1e3
 
