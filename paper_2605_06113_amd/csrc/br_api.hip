@@ -45,7 +45,7 @@ bool config_ok(const br_config *c) {
 
 // `dl`: byte offset of the discount table that horizons beyond BR_HP keep in the workspace (after the
 // arrays of the public layout), or 0
-void make_layout(const br_config &c, br_layout *l, uint64_t *dl = nullptr) {
+void make_layout(const br_config &c, br_layout *l, uint64_t *dl = nullptr, uint64_t *score_scratch = nullptr) {
   const uint64_t N = (uint64_t)c.n_inst, G = (uint64_t)c.G, Q = (uint64_t)c.max_wait, H1 = (uint64_t)c.H + 1;
   const uint64_t P = (uint64_t)pred_width(c), Pq = (uint64_t)queue_pred_width(c);
   const uint64_t Bs = ((uint64_t)c.B + 3u) & ~(uint64_t)3u;
@@ -71,6 +71,9 @@ void make_layout(const br_config &c, br_layout *l, uint64_t *dl = nullptr) {
   l->minm = take(N * G);
   const uint64_t dl_at = c.H > BR_HP ? take((uint64_t)BR_HS(c.H)) : 0;
   if (dl) *dl = dl_at;
+  const uint64_t ss_bytes = br_score_scratch_bytes(c.n_inst, c.max_wait, c.G);
+  const uint64_t ss_at = ss_bytes ? take(ss_bytes / 4) : 0;  // partial results of the tiled score path (private)
+  if (score_scratch) *score_scratch = ss_at;
   l->total_bytes = off;
   l->B_stride = (int32_t)Bs;
   l->P = (int32_t)P;
@@ -84,6 +87,7 @@ struct br_ctx {
   br_config cfg;
   br_layout lay;
   BrParams p;
+  int *score_scratch;
   hipStream_t st;
   int32_t last_hip;
   bool prof;
@@ -143,8 +147,8 @@ int32_t br_init(const br_config *cfg, const br_init_state *init, br_ctx **out) {
   if (!out || !config_ok(cfg) || !cfg->workspace) return BR_EINVAL;
   if (((uintptr_t)cfg->workspace & 255u) != 0) return BR_EINVAL;
   br_layout l;
-  uint64_t dl_at = 0;
-  make_layout(*cfg, &l, &dl_at);
+  uint64_t dl_at = 0, ss_at = 0;
+  make_layout(*cfg, &l, &dl_at, &ss_at);
   if (cfg->workspace_bytes < l.total_bytes) return BR_ENOMEM;
   const int P = pred_width(*cfg);
   if (init && (!init->n || !init->kv || !init->rem || (P > 0 && !init->pred))) return BR_EINVAL;
@@ -210,6 +214,7 @@ int32_t br_init(const br_config *cfg, const br_init_state *init, br_ctx **out) {
   p.mh = (int32_t *)(base + l.mh);
   p.minm = (int32_t *)(base + l.minm);
   p.dl = dl_at ? (const float *)(base + dl_at) : nullptr;
+  ctx->score_scratch = ss_at ? (int *)(base + ss_at) : nullptr;
 
   int32_t rc = enqueue(ctx, BR_K_INIT, [&] { br_launch_clear(p, ctx->st); });
   if (rc == BR_OK && p.dl) rc = enqueue(ctx, BR_K_INIT, [&] { br_launch_discounts(p, cfg->gamma, ctx->st); });
@@ -255,7 +260,7 @@ static int32_t route(br_ctx *ctx, const br_arrivals *in, const br_step_out *out,
   const bool together = (o.best_g || o.best_i) && !o.F && p.N >= BR_SCORE_WAVE_MIN_N && p.R_max <= 8 &&
                         (p.H == 0 ? p.Q <= 256 : (p.H <= BR_HP && p.Q <= 512));
   if (rc == BR_OK && !together && (o.F || o.best_g || o.best_i))
-    rc = enqueue(ctx, BR_K_SCORE, [&] { br_launch_score(p, a, o, ctx->st); });
+    rc = enqueue(ctx, BR_K_SCORE, [&] { br_launch_score(p, a, o, ctx->score_scratch, ctx->st); });
   if (rc == BR_OK) {
     if (together && p.H > 0)
       rc = enqueue(ctx, BR_K_ASSIGN, [&] { br_launch_route_h(p, a, o, ctx->st); });

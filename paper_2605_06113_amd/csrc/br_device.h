@@ -13,6 +13,7 @@
 #define BR_MAX_G_DEV 64
 #define BR_MAX_S_DEV 32768
 #define BR_IDX_BITS 11   // queue positions fit 11 bits (max_wait <= 2048)
+#define BR_SCORE_TILES_MAX_N 16    // up to this many clusters, long queues are scored a wave per (request tile, worker group)
 #define BR_SCORE_WAVE_MIN_N 2048  // from this many clusters on (two waves per SIMD), short queues are scored one wave per cluster
 
 struct BrParams {

@@ -462,6 +462,146 @@ __global__ __launch_bounds__(512) void br_k_score(BrParams p, BrArr a, BrOut o, 
   }
 }
 
+// K2 + K3 for a few clusters with long queues (single-instance serving): the block-per-cluster kernel above
+// leaves most of the chip idle and its two passes score every pair twice.  Here one wave takes a tile of 64
+// requests against a quarter of the workers (grid: tiles x 4 worker groups x clusters), scores each pair
+// once, keeps the best worker of its group per request in registers and finds the best request of its tile per
+// worker by three wave reductions (score, then length, then arrival position: the tie rule of br_k_score).
+// The partial results go to a scratch area of the workspace; br_k_score_combine folds them (groups in
+// ascending worker order, tiles in ascending request order, so ties resolve as in the one-block kernel).
+// Scratch per cluster: pg_key, pg_g [WGN][Q]; pi_key, pi_s, pi_i [T][G].
+#define BR_TILE_WORKERS 16  // most workers in a group (64 workers in 4 groups)
+#define BR_TILE_GROUPS 4
+__host__ __device__ inline size_t br_score_scratch_words(int Q, int G) {
+  const size_t T = (size_t)(Q + BR_WAVE - 1) / BR_WAVE;
+  return 2 * BR_TILE_GROUPS * (size_t)Q + 3 * T * (size_t)G;
+}
+
+template <bool BRH, bool LONG>
+__global__ __launch_bounds__(64) void br_k_score_tiles(BrParams p, BrArr a, int *scratch, int wpg) {
+  extern __shared__ int lds[];
+  const int tile = blockIdx.x, wg = blockIdx.y, inst = blockIdx.z;
+  const int T = gridDim.x, WGN = gridDim.y;
+  const int lane = br_lane(), G = p.G;
+  const int g0 = wg * wpg, gn = min(wpg, G - g0);  // wpg <= BR_TILE_WORKERS workers per group
+  const int HS = LONG ? BR_HS(p.H) : BR_HP + 1;
+  int *sm = lds;                                      // [16][HS] margins of the group's workers (LONG: as floats)
+  float *sd = (float *)(sm + BR_TILE_WORKERS * HS);   // LONG: [HS] discounts (+ 4 words read ahead)
+  int *sL = sm + BR_TILE_WORKERS * HS + (LONG ? HS + 4 : 0);  // [16] loads, then [16] free slots
+  int *scap = sL + BR_TILE_WORKERS;
+  int *sc = scratch + (size_t)inst * br_score_scratch_words(p.Q, G);
+  int *pg_key = sc, *pg_g = sc + (size_t)WGN * p.Q;
+  int *pi_key = sc + 2 * (size_t)WGN * p.Q, *pi_s = pi_key + (size_t)T * G, *pi_i = pi_s + (size_t)T * G;
+
+  const int q0 = min(max(p.qlen[inst], 0), p.Q);
+  int cnt = a.count ? a.count[inst] : 0;
+  cnt = min(max(cnt, 0), a.arr_cap);
+  const int qn = q0 + min(cnt, p.Q - q0);
+
+  // worker state of the group; BR-0 margins need the envelope over all workers
+  const int Lall = lane < G ? p.L[(int64_t)inst * G + lane] : BR_LOW;
+  const int M = br_wave_max(Lall);
+  if (lane < gn) {
+    sL[lane] = p.L[(int64_t)inst * G + g0 + lane];
+    scap[lane] = p.B - p.n[(int64_t)inst * G + g0 + lane];
+  }
+  for (int e = lane; e < gn * HS; e += BR_WAVE) {
+    const int gl = e / HS, h = e - gl * HS;
+    int m = 0;
+    if (BRH) {
+      if (h <= p.H) m = p.mh[((int64_t)inst * G + g0 + gl) * (p.H + 1) + h];
+    } else if (h == 0) {
+      m = M - p.L[(int64_t)inst * G + g0 + gl];
+    }
+    sm[e] = LONG ? __float_as_int((float)m) : m;
+  }
+  if constexpr (LONG)
+    for (int h = lane; h < HS + 4; h += BR_WAVE) sd[h] = h < HS ? p.dl[h] : 0.0f;
+  br_wave_sync();
+
+  const int i = tile * BR_WAVE + lane;
+  const bool valid = i < qn;
+  int s = 1;
+  if (valid) s = i < q0 ? p.qs[(int64_t)inst * p.Q + i] : a.s[(int64_t)inst * a.arr_cap + (i - q0)];
+  s = min(max(s, 1), BR_MAX_S_DEV);
+  int bk = BR_KEY_NONE, bg = -1;
+  for (int gl = 0; gl < gn; ++gl) {
+    int key;
+    if constexpr (LONG) {
+      const int dv[1] = {s};
+      float Fv[1];
+      br_scoreh_long<1>(p.aD, p.beta, (const float *)(sm + gl * HS), sd, HS, dv, Fv);
+      key = br_ord(Fv[0]);
+    } else {
+      int m[BR_HP + 1];
+#pragma unroll
+      for (int h = 0; h <= BR_HP; ++h) m[h] = (BRH || h == 0) ? sm[gl * HS + h] : 0;
+      key = br_score_key<BRH>(p, m, s);
+    }
+    const bool ok = valid && scap[gl] > 0 && (p.W <= 0 || sL[gl] + s <= p.W);
+    if (ok && key > bk) {  // workers in ascending order: the first best stays
+      bk = key;
+      bg = g0 + gl;
+    }
+    // best request of this tile for worker g: score, then the longer request, then the earlier arrival
+    const int kk = ok ? key : BR_KEY_NONE;
+    const int km = br_wave_max(kk);
+    int sbest = 0, ibest = -1;
+    if (km != BR_KEY_NONE) {
+      sbest = br_wave_max(kk == km ? s : -1);
+      ibest = br_wave_min((kk == km && s == sbest) ? i : INT32_MAX);
+    }
+    if (lane == 0) {
+      const size_t at = (size_t)tile * G + g0 + gl;
+      pi_key[at] = km, pi_s[at] = sbest, pi_i[at] = ibest;
+    }
+  }
+  if (i < p.Q) {
+    pg_key[(size_t)wg * p.Q + i] = bk;
+    pg_g[(size_t)wg * p.Q + i] = bg;
+  }
+}
+
+// Blocks [0, QB) fold the per-group best workers of 256 requests each; the others take four workers each, one
+// wave per worker with lanes mapped to tiles (at most 32), and fold the per-tile best requests by the same three
+// reductions.  All partial results are requested at once: nothing here waits on a load more than once.
+__global__ __launch_bounds__(256) void br_k_score_combine(BrParams p, BrOut o, const int *scratch, int T, int WGN, int QB) {
+  const int inst = blockIdx.y, tid = threadIdx.x, G = p.G;
+  const int *sc = scratch + (size_t)inst * br_score_scratch_words(p.Q, G);
+  const int *pg_key = sc, *pg_g = sc + (size_t)WGN * p.Q;
+  const int *pi_key = sc + 2 * (size_t)WGN * p.Q, *pi_s = pi_key + (size_t)T * G, *pi_i = pi_s + (size_t)T * G;
+  if ((int)blockIdx.x < QB) {
+    const int i = blockIdx.x * 256 + tid;
+    if (!o.best_g || i >= p.Q) return;
+    int k[4], gg[4];
+#pragma unroll
+    for (int wg = 0; wg < 4; ++wg) {
+      k[wg] = wg < WGN ? pg_key[(size_t)wg * p.Q + i] : BR_KEY_NONE;
+      gg[wg] = wg < WGN ? pg_g[(size_t)wg * p.Q + i] : -1;
+    }
+    int bk = BR_KEY_NONE, bg = -1;
+#pragma unroll
+    for (int wg = 0; wg < 4; ++wg)
+      if (k[wg] > bk) bk = k[wg], bg = gg[wg];
+    o.best_g[(int64_t)inst * p.Q + i] = bg;
+  } else {
+    const int g = ((int)blockIdx.x - QB) * 4 + (tid >> 6), lane = br_lane();
+    if (!o.best_i || g >= G) return;  // whole waves leave
+    const bool in = lane < T;
+    const int i = in ? pi_i[(size_t)lane * G + g] : -1;
+    const int k = in ? pi_key[(size_t)lane * G + g] : BR_KEY_NONE;
+    const int s = in ? pi_s[(size_t)lane * G + g] : 0;
+    const int kk = i >= 0 ? k : BR_KEY_NONE;
+    const int km = br_wave_max(kk);
+    int bi = -1;
+    if (km != BR_KEY_NONE) {
+      const int sbest = br_wave_max(kk == km ? s : -1);
+      bi = br_wave_min((kk == km && s == sbest) ? i : INT32_MAX);
+    }
+    if (lane == 0) o.best_i[(int64_t)inst * G + g] = bi;
+  }
+}
+
 // K2 + K3, one wave per cluster (br_score_wave.h)
 template <int E, bool BRH>
 __global__ __launch_bounds__(256) void br_k_score_wave(BrParams p, BrArr a, BrOut o) {
@@ -556,11 +696,34 @@ void br_launch_project(const BrParams &p, hipStream_t st) {
   hipLaunchKernelGGL(br_k_envelope, dim3((unsigned)((p.N + 3) / 4)), dim3(256), 0, st, p);
 }
 
-void br_launch_score(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st) {
+size_t br_score_scratch_bytes(int N, int Q, int G) {
+  return N <= BR_SCORE_TILES_MAX_N ? (size_t)N * br_score_scratch_words(Q, G) * sizeof(int) : 0;
+}
+
+void br_launch_score(const BrParams &p, const BrArr &a, const BrOut &o, int *scratch, hipStream_t st) {
   int waves = (p.Q + 63) / 64;  // one wave per tile of 64 requests, at most 8 waves
   waves = waves < 1 ? 1 : (waves > 8 ? 8 : waves);
   const int want_tile = o.F != nullptr;
   const bool longh = p.H > BR_HP;
+  {  // few clusters, long queues, no matrix: a wave per (tile of requests, group of workers), then a combine
+    const int T = (p.Q + BR_WAVE - 1) / BR_WAVE;
+    const int wpg = (p.G + BR_TILE_GROUPS - 1) / BR_TILE_GROUPS, WGN = (p.G + wpg - 1) / wpg;  // at most 4 groups
+    if (scratch && !want_tile && p.N <= BR_SCORE_TILES_MAX_N && T * WGN >= 8) {
+      const dim3 grid((unsigned)T, (unsigned)WGN, (unsigned)p.N), block(BR_WAVE);
+      const int HS = longh ? BR_HS(p.H) : BR_HP + 1;
+      const size_t lds = ((size_t)BR_TILE_WORKERS * HS + (longh ? HS + 4 : 0) + 2 * BR_TILE_WORKERS) * sizeof(int);
+      if (longh)
+        hipLaunchKernelGGL((br_k_score_tiles<true, true>), grid, block, lds, st, p, a, scratch, wpg);
+      else if (p.H > 0)
+        hipLaunchKernelGGL((br_k_score_tiles<true, false>), grid, block, lds, st, p, a, scratch, wpg);
+      else
+        hipLaunchKernelGGL((br_k_score_tiles<false, false>), grid, block, lds, st, p, a, scratch, wpg);
+      const int QB = (p.Q + 255) / 256;
+      hipLaunchKernelGGL(br_k_score_combine, dim3((unsigned)(QB + (p.G + 3) / 4), (unsigned)p.N), dim3(256), 0, st, p, o,
+                         (const int *)scratch, T, WGN, QB);
+      return;
+    }
+  }
   if (!longh && !want_tile && p.Q <= 512 && p.N >= BR_SCORE_WAVE_MIN_N) {  // many small clusters: one wave each
     const dim3 grid((unsigned)((p.N + 3) / 4)), block(256);
     if (p.H > 0) {
