@@ -141,16 +141,21 @@ __device__ __forceinline__ int br_score0(int G, int m, int delta) {
 // operation rounded on its own, penalty accumulated from h = 0 upwards.  Offsets beyond H carry
 // a zero discount and add exactly +0.
 __device__ __forceinline__ float br_scoreh(const BrParams &p, const int (&m)[BR_HP + 1], int delta) {
+  // The excess (Delta - m)_+ is formed in fp32, one operation less per offset than in integers and the same
+  // value: Delta <= 2^19 is an exact float; a margin below Delta is one too and so is the difference; a margin
+  // at or above Delta stays so after rounding and the term is zero either way.  (The conversions of the margins
+  // do not depend on Delta: where one worker is scored against many requests they are done once.)
+  const float fd = (float)delta;
   float pen = 0.0f;
 #pragma unroll
   for (int h = 0; h <= BR_HP / 2; ++h)
-    pen = __fadd_rn(pen, __fmul_rn(p.d[h], (float)max(delta - m[h], 0)));
+    pen = __fadd_rn(pen, __fmul_rn(p.d[h], fmaxf(__fsub_rn(fd, (float)m[h]), 0.0f)));
   if (p.H > BR_HP / 2) {  // short horizons: the remaining terms are +0 and leave the sum as it is
 #pragma unroll
     for (int h = BR_HP / 2 + 1; h <= BR_HP; ++h)
-      pen = __fadd_rn(pen, __fmul_rn(p.d[h], (float)max(delta - m[h], 0)));
+      pen = __fadd_rn(pen, __fmul_rn(p.d[h], fmaxf(__fsub_rn(fd, (float)m[h]), 0.0f)));
   }
-  return __fsub_rn(__fmul_rn(p.aD, (float)delta), __fmul_rn(p.beta, pen));
+  return __fsub_rn(__fmul_rn(p.aD, fd), __fmul_rn(p.beta, pen));
 }
 
 // The same score for horizons beyond BR_HP, NV subset sums at a time: margins `m` (as floats) and
