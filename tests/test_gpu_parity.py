@@ -545,6 +545,45 @@ def test_maintained_estimate_replay(H, refresh, gate):
     r.close()
 
 
+@pytest.mark.parametrize("name,over", [("c2", dict(arrival_rate=12.0)), ("c3", dict(gate_pfin=0.5)),
+                                       ("c3", dict(H=80, pred_mode=3, G=8, max_wait=256, arrival_rate=10.0))])
+def test_graph_capture_and_replay(name, over):
+    """The entry points only enqueue kernels (no allocation, no synchronisation, no memset): one step of the
+    serving loop (br_route_advance) is captured into a graph once and replayed for 40 steps, the arrivals of
+    each step copied into the captured buffers beforehand (eager work between the replays); every replay is
+    checked against the oracle, the whole state every tenth."""
+    import torch
+    cfg = wl.config(name, **over)
+    steps = 40
+    _say(f"graph replay {name} {over}")
+    tr = wl.arrival_trace(cfg, steps)
+    torch.cuda.synchronize()
+    oc, r = br_oracle.OracleCluster(cfg), binding.Router(cfg, stream=torch.cuda.Stream())   # capture needs a stream of its own
+    darr = binding.DeviceArrivals(tr.step(0), r.device, r.Pq)     # the buffers the graph reads
+    out = r.alloc_outputs(scores=True, matrix=False)
+    graph = torch.cuda.CUDAGraph()
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph, stream=r.stream):
+        r.route_advance_device(darr, out, 1)
+    # capture only records: the state is still the initial one
+    for k in range(steps):
+        a = tr.step(k)
+        nxt = binding.DeviceArrivals(a, r.device, r.Pq)
+        with torch.cuda.stream(r.stream):
+            darr.count.copy_(nxt.count), darr.s.copy_(nxt.s), darr.o.copy_(nxt.o), darr.id.copy_(nxt.id)
+            if darr.pred is not None:
+                darr.pred.copy_(nxt.pred)
+            graph.replay()
+        r.stream.synchronize()
+        ref = oc.route_step(a, want_scores=True)
+        oc.advance(1)
+        got = {kk: out[kk].cpu().numpy() for kk in ("assign", "assign_id", "stats", "best_g", "best_i")}
+        compare_outputs({kk: ref[kk] for kk in got}, got, cfg, f"graph {name} step {k}")
+        if k % 10 == 9:
+            compare_state(oc, r.state(), cfg, f"graph {name} step {k}")
+    r.close()
+
+
 def test_determinism():
     cfg, init, arr = wl.random_case(31, N=16, G=16, B=24, max_wait=256, H=4, gate_pfin=0.0, tie_heavy=True)
     outs = []
