@@ -31,8 +31,8 @@ ALU_INT_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 # profiles/bench_c4_kernels.md); an entry is None when its kernel changed after the counters were taken
 LDS_PEAK_GBS = 256 * 128 * 2.4          # 256 CUs x 128 B per clock x 2.4 GHz
 LDS_INSTS_PER_WAVE = 236.1              # br_k_route4 (c4), rocprofv3 --pmc SQ_INSTS_LDS / SQ_WAVES
-TRAFFIC_KIB = {"assign+advance": 2.0 * 43722.3 + 92350.7,   # br_k_route4<true>: reductions + round + decode step
-               "assign": 2.0 * 6773.5 + 21800.9, "advance": 2.0 * 37922.3 + 74527.8}
+TRAFFIC_KIB = {"assign+advance": 2.0 * 43722.6 + 92343.4,   # br_k_route4<true>: reductions + round + decode step
+               "assign": 2.0 * 6773.5 + 21800.9, "advance": 2.0 * 37923.5 + 74527.1}
 
 
 def cpu_baseline(cfg, init, arr, min_seconds=10.0):
