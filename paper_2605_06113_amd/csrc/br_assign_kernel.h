@@ -50,7 +50,8 @@ struct Log2E {
 
 // One cluster's round on one wave.  `lds`: this wave's 3*E*64 + 72 words.  COOP (queues of up to 2048):
 // the block has four waves; all of them sort the waiting set together (br_sort_desc_block4), wave 0 runs
-// the round alone with the sorted keys read back from LDS, and all four share the epilogue and the decode step.
+// the round with the sorted keys read back from LDS and hands every full search over the waiting set
+// (argmax_i F_g({i})) to all four, 512 sorted positions each; all four share the epilogue and the decode step.
 template <int E, bool BRH, bool ADV, bool COOP = false, bool BIGR = false>
 __device__ __forceinline__ void br_assign_body(const BrParams &p, const BrArr &a, const BrOut &o, int *lds, int inst,
                                                int w = 0) {
@@ -69,6 +70,10 @@ __device__ __forceinline__ void br_assign_body(const BrParams &p, const BrArr &a
   int *slots = lds + 3 * NP;  // [64] k-th alive request of a Stage-1 level: s << 11 | sorted position
   int *win = slots + BR_WAVE; // [8]  Stage-2 candidate window, same packing (16-byte aligned); BIGR: [16]
   int *hitab = win + 16;      // BIGR: [1024] sums of the window entries 6.. selected by the upper mask bits (16-byte aligned)
+  // COOP: mailbox of the searches that wave 0 hands to all four waves (one per 512 sorted positions)
+  int *svc = win + (BIGR ? 16 + 1024 : 8);  // [16] 0: 1 = search, 0 = round over; 1..9: margins; 10: room
+  int *salive = svc + 16;                   // [64] wave 0's alive bits, one word per lane
+  int *sres = salive + BR_WAVE;             // [8]  per wave: best key, its lowest sorted position
 
   const int lane = br_lane();
   const int G = p.G;
@@ -110,7 +115,34 @@ __device__ __forceinline__ void br_assign_body(const BrParams &p, const BrArr &a
 #pragma unroll
     for (int j = 0; j < 8; ++j) skey[w * 512 + j * BR_WAVE + lane] = (int)x8[j];
     __syncthreads();
-    if (w != 0) {  // waves 1-3 wait for the round, then take their share of the epilogue and the decode step
+    if (w != 0) {  // waves 1-3 serve wave 0's searches during the round, then take their share of the epilogue and the decode step
+      int sv8[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) sv8[j] = (int)(x8[j] >> BR_IDX_BITS);
+      for (;;) {  // one pass per search; every wave of the block meets at both barriers, wave 0 ends the loop
+        __syncthreads();
+        if (svc[0] == 0) break;
+        int mgq[BR_HP + 1];
+#pragma unroll
+        for (int h = 0; h <= BR_HP; ++h) mgq[h] = svc[1 + h];
+        const int roomq = svc[2 + BR_HP];
+        const unsigned al = (unsigned)salive[lane] >> (8 * w);
+        int bk = BR_KEY_NONE, bp = INT32_MAX;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const bool ok = ((al >> j) & 1u) && sv8[j] <= roomq;
+          int key = br_score_key<BRH>(p, mgq, sv8[j]);
+          key = ok ? key : BR_KEY_NONE;
+          if (key > bk) {
+            bk = key;
+            bp = w * 512 + j * BR_WAVE + lane;
+          }
+        }
+        const int km = br_wave_max(bk);
+        const int pm = km == BR_KEY_NONE ? INT32_MAX : br_wave_min(bk == km ? bp : INT32_MAX);
+        if (lane == 0) sres[2 * w] = km, sres[2 * w + 1] = pm;
+        __syncthreads();
+      }
       int Lw = 0, nw = 0;
       BrRoundCounts none = {};
       br_assign_epilogue_block4(inst, lane, w, q0, qn, cnt, skey, adm, who, slots, Lw, nw, none, c0, ADV);
@@ -231,6 +263,36 @@ __device__ __forceinline__ void br_assign_body(const BrParams &p, const BrArr &a
         swin = sw;
         return true;
       }
+    } else if constexpr (COOP) {
+      // the four waves search 512 sorted positions each: the request goes out through LDS, every wave returns
+      // its best (score, lowest position), the best of the four wins (lower position on equal scores)
+#pragma unroll
+      for (int h = 0; h <= BR_HP; ++h) svc[1 + h] = mg[h];
+      svc[2 + BR_HP] = room;
+      salive[lane] = (int)alive;
+      svc[0] = 1;
+      __syncthreads();
+      int bk = BR_KEY_NONE, bp = INT32_MAX;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int s = sv[j];
+        const bool ok = ((alive >> j) & 1u) && s <= room;
+        int key = br_score_key<BRH>(p, mg, s);
+        key = ok ? key : BR_KEY_NONE;
+        if (key > bk) {
+          bk = key;
+          bp = j * BR_WAVE + lane;
+        }
+      }
+      int km = br_wave_max(bk);
+      pos = km == BR_KEY_NONE ? INT32_MAX : br_wave_min(bk == km ? bp : INT32_MAX);
+      __syncthreads();
+#pragma unroll
+      for (int u = 1; u < 4; ++u) {
+        const int ku = sres[2 * u], pu = sres[2 * u + 1];
+        if (ku > km) km = ku, pos = pu;  // positions of wave u lie above those of the waves before it
+      }
+      if (km == BR_KEY_NONE) return false;
     } else {
       int bk = BR_KEY_NONE, bp = INT32_MAX;
 #pragma unroll
@@ -768,6 +830,8 @@ __device__ __forceinline__ void br_assign_body(const BrParams &p, const BrArr &a
   rc.wdrop = wdrop;
   rc.I_before = I_before;
   if constexpr (COOP) {
+    svc[0] = 0;  // the round is over: the waves that served the searches go on to the epilogue
+    __syncthreads();
     int Lw = Lh[0];
     br_assign_epilogue_block4(inst, lane, 0, q0, qn, cnt, skey, adm, who, slots, Lw, nn, rc, c0, ADV);
     if constexpr (ADV) br_advance_cluster<4, BRH>(inst, lane, Lw, nn, 0, min((G + 3) >> 2, G));
@@ -785,7 +849,7 @@ __device__ __forceinline__ void br_assign_body(const BrParams &p, const BrArr &a
 template <int E, bool BRH, bool ADV, bool BIGR = false>
 __global__ __launch_bounds__(256, (BRH && E == 8 && !BIGR) ? 4 : 1) void br_k_assign(BrParams p, BrArr a, BrOut o) {
   extern __shared__ int lds_all[];
-  constexpr int WORDS = 3 * E * BR_WAVE + BR_WAVE + (BIGR ? 16 + 1024 : 8);  // skey, adm, who, slots, win (+ table) per wave
+  constexpr int WORDS = 3 * E * BR_WAVE + BR_WAVE + (BIGR ? 16 + 1024 : 8) + (E == 32 ? 96 : 0);  // skey, adm, who, slots, win (+ table, + mailbox) per wave
   const int w = threadIdx.x >> 6;
   if constexpr (E == 32)  // one cluster per block, four waves for the sort
     br_assign_body<E, BRH, ADV, true, BIGR>(p, a, o, lds_all, (int)blockIdx.x, w);
@@ -797,7 +861,7 @@ template <int E, bool BRH, bool BIGR = false>
 static void br_launch_assign_one(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st) {
   // several single-wave clusters share a block so that the chip's per-CU block slots do not cap residency
   const int wpb = E <= 8 ? 4 : 1;  // clusters per block
-  const size_t lds = (size_t)wpb * (3 * E * BR_WAVE + BR_WAVE + (BIGR ? 16 + 1024 : 8)) * sizeof(int);
+  const size_t lds = (size_t)wpb * (3 * E * BR_WAVE + BR_WAVE + (BIGR ? 16 + 1024 : 8) + (E == 32 ? 96 : 0)) * sizeof(int);
   const dim3 grid((unsigned)((p.N + wpb - 1) / wpb)), block(E == 32 ? 4 * BR_WAVE : BR_WAVE * wpb);
   if constexpr (BIGR) {  // no fused decode steps for these: the caller launches the decode kernel
     hipLaunchKernelGGL((br_k_assign<E, BRH, false, true>), grid, block, lds, st, p, a, o);
