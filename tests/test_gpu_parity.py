@@ -307,6 +307,33 @@ def test_edge_cases():
     r.close()
 
 
+def test_edge_cases_long_horizon_and_wide_window():
+    """The same degenerate inputs through the kernels for horizons beyond 8 and windows beyond 8 requests."""
+    for tag, kw in (("H=80", dict(H=80, pred_mode=1)), ("H=128 pair", dict(H=128, pred_mode=3, gate_pfin=0.5)),
+                    ("R_max=16", dict(H=0, R_max=16)), ("H=33 R_max=12", dict(H=33, pred_mode=1, R_max=12))):
+        _say(f"edge long/wide: {tag}")
+        cfg, init, arr = wl.random_case(15, N=3, G=4, B=8, max_wait=32, **kw)
+        oc, r = br_oracle.OracleCluster(cfg, init), binding.Router(cfg, init)
+        compare_outputs(oc.route_step(None), r.route_step(None), cfg, f"{tag} null")       # no arrivals at all
+        compare_state(oc, r.state(), cfg, f"{tag} null")
+        arrx = wl.Arrivals(np.full_like(arr.count, arr.s.shape[1]), arr.s, arr.o, arr.id, arr.pred)
+        for k in range(3):                                                                 # overflow, then nothing free
+            compare_outputs(oc.route_step(arrx), r.route_step(arrx, advance=k % 2), cfg, f"{tag} overflow{k}")
+            if k % 2:
+                oc.advance(1)
+            compare_state(oc, r.state(), cfg, f"{tag} overflow{k}")
+        r.close()
+        cfg, init, arr = wl.random_case(16, N=2, G=4, B=8, max_wait=32, fill=1.0, **kw)    # all workers full
+        oc, r = run_pair(cfg, init, arr, tag=f"{tag} full")
+        r.close()
+        cfg, init, arr = wl.random_case(18, N=2, G=3, B=4, max_wait=64, fill=0.0, n_wait=64, **kw)   # empty cluster
+        oc, r = run_pair(cfg, init, arr, tag=f"{tag} empty")
+        r.close()
+        cfg, init, arr = wl.random_case(19, N=2, G=1, B=3, max_wait=5, fill=0.4, n_wait=5, **kw)     # one worker
+        oc, r = run_pair(cfg, init, arr, tag=f"{tag} G=1")
+        r.close()
+
+
 def test_advance_many_steps_closed_form():
     """n decode steps in one call equal n single steps of the oracle (requests leave mid-way)."""
     for H in (0, 4):
