@@ -42,6 +42,38 @@ def test_c1_single_step():
     r.close()
 
 
+def test_brh_rounds_against_stored_values():
+    """The HIP path against tests/golden/brh_rounds.txt (the oracle's stored results for a short- and a
+    long-horizon round): assignments, reductions, statistics, loads, projection rows and score bit patterns."""
+    import importlib.util
+    import os
+    here = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+    spec = importlib.util.spec_from_file_location("make_brh_golden", os.path.join(here, "make_brh_golden.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    gold = {}
+    for line in open(os.path.join(here, "brh_rounds.txt")):
+        if not line.startswith("#"):
+            k, *v = line.split()
+            gold[k] = [int(x) for x in v]
+    for tag, kw in mod.CASES:
+        _say(f"stored BR-H round {tag}")
+        cfg, init, arr = mod.case_inputs(kw)
+        r = binding.Router(cfg, init)
+        out = r.route_step(arr)
+        st = r.state()
+        assert out["assign"].ravel().tolist() == gold[f"{tag}.assign"]
+        assert out["best_g"].ravel().tolist() == gold[f"{tag}.best_g"] and out["best_i"].ravel().tolist() == gold[f"{tag}.best_i"]
+        assert out["stats"][:, :12].ravel().tolist() == gold[f"{tag}.stats"]
+        assert st["L"].ravel().tolist() == gold[f"{tag}.L"] and st["n"].ravel().tolist() == gold[f"{tag}.n"]
+        assert st["Lh"][0].ravel().tolist() == gold[f"{tag}.Lh0"]
+        assert np.asarray(out["F"][0, 0], np.float32).view(np.int32).tolist() == gold[f"{tag}.F0bits"]
+        r.advance(1)
+        st = r.state()
+        assert st["L"].ravel().tolist() == gold[f"{tag}.L1"] and st["n"].ravel().tolist() == gold[f"{tag}.n1"]
+        r.close()
+
+
 CASES = [
     # (G, B, Q, H, extra)                        spans every register layout (Q<=256/512/1024/2048)
     (4, 16, 32, 0, {}),

@@ -436,3 +436,17 @@ def test_c1_matches_stored_round(orc):
     mod = importlib.util.module_from_spec(spec)
     spec.loader.exec_module(mod)
     assert mod.compute() == open(os.path.join(here, "c1_round.txt")).read()
+
+
+def test_brh_matches_stored_rounds(orc):
+    """Two small BR-H rounds (H = 4 with hazards and gate; H = 80 with the two-stage pair) against
+    tests/golden/brh_rounds.txt (written by tests/golden/make_brh_golden.py from the oracle alone): assignments,
+    statistics, loads, the projection of one cluster and fp32 scores as bit patterns.  A change of the oracle's
+    fp32 arithmetic, of its tie rules or of the input generators shows up here."""
+    import importlib.util
+    import os
+    here = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+    spec = importlib.util.spec_from_file_location("make_brh_golden", os.path.join(here, "make_brh_golden.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    assert mod.compute() == open(os.path.join(here, "brh_rounds.txt")).read()
