@@ -27,7 +27,9 @@
  * Pins (tests/test_oracle_*.py): closed form of the BR-0 score at its breakpoints;
  * score == drop of the imbalance G*M - sum(L); BR-H at H=0,(alpha,beta)=(1,G) == BR-0;
  * discounted-imbalance identity of the horizon score; survival-sum == two-stage
- * composite; subset enumeration == best over reachable sums; structural invariants
+ * composite; eq. (composite) on a supplied (p_fin, mu_rem) against fp64 and at its corners;
+ * subset enumeration == best over reachable sums (for windows of up to 16 requests the sums are
+ * built by the shift-OR recurrence of Appendix "Bit-set subset selection"); structural invariants
  * of a round (sticky, disjoint, slot limit, load conservation, work conservation,
  * telescoping of the imbalance); brute force over all assignments on tiny instances.
  *
