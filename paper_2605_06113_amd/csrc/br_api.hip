@@ -115,18 +115,33 @@ int32_t enqueue(br_ctx *ctx, int kid, Fn &&fn) {
       hipError_t e = hipEventCreate(&ev.a);
       if (e != hipSuccess) return fail_hip(ctx, e);
       e = hipEventCreate(&ev.b);
-      if (e != hipSuccess) return fail_hip(ctx, e);
+      if (e != hipSuccess) {
+        (void)hipEventDestroy(ev.a);
+        return fail_hip(ctx, e);
+      }
     }
     ev.kid = kid;
     hipError_t e = hipEventRecord(ev.a, ctx->st);
-    if (e != hipSuccess) return fail_hip(ctx, e);
+    if (e != hipSuccess) {
+      ctx->spare.push_back(ev);
+      return fail_hip(ctx, e);
+    }
   }
+  // an error left behind by an earlier, unrelated HIP call of this thread is not this launch's: clear it first,
+  // so that what is read after the launch is the launch's own result
+  (void)hipGetLastError();
   fn();
   hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return fail_hip(ctx, e);
+  if (e != hipSuccess) {
+    if (ctx->prof) ctx->spare.push_back(ev);
+    return fail_hip(ctx, e);
+  }
   if (ctx->prof) {
     e = hipEventRecord(ev.b, ctx->st);
-    if (e != hipSuccess) return fail_hip(ctx, e);
+    if (e != hipSuccess) {
+      ctx->spare.push_back(ev);
+      return fail_hip(ctx, e);
+    }
     ctx->pending.push_back(ev);
   }
   return BR_OK;
@@ -232,6 +247,7 @@ int32_t br_init(const br_config *cfg, const br_init_state *init, br_ctx **out) {
 static int32_t route(br_ctx *ctx, const br_arrivals *in, const br_step_out *out, int32_t adv_t) {
   if (!ctx || adv_t < 0) return BR_EINVAL;
   BrArr a{};
+  if (in && in->arr_cap < 0) return BR_EINVAL;
   if (in && in->count && in->arr_cap > 0) {
     if (!in->s || !in->o || (ctx->p.Pq > 0 && !in->pred)) return BR_EINVAL;
     a.count = in->count;
@@ -281,7 +297,8 @@ int32_t br_route_advance(br_ctx *ctx, const br_arrivals *in, const br_step_out *
 
 int32_t br_route_bypass(br_ctx *ctx, const br_arrivals *in, const br_step_out *out) {
   if (!ctx || ctx->p.H != 0) return BR_EINVAL;
-  if (!in || !in->count || in->arr_cap <= 0) return BR_OK;  // nothing to place
+  if (in && in->arr_cap < 0) return BR_EINVAL;
+  if (!in || !in->count || in->arr_cap == 0) return BR_OK;  // nothing to place
   if (in->arr_cap > BR_MAX_WAIT || !in->s || !in->o) return BR_EINVAL;
   BrArr a{};
   a.count = in->count;

@@ -478,7 +478,7 @@ __host__ __device__ inline size_t br_score_scratch_words(int Q, int G) {
 }
 
 template <bool BRH, bool LONG>
-__global__ __launch_bounds__(64) void br_k_score_tiles(BrParams p, BrArr a, int *scratch, int wpg) {
+__global__ __launch_bounds__(64) void br_k_score_tiles(BrParams p, BrArr a, int *partials, int wpg) {
   extern __shared__ int lds[];
   const int tile = blockIdx.x, wg = blockIdx.y, inst = blockIdx.z;
   const int T = gridDim.x, WGN = gridDim.y;
@@ -489,7 +489,7 @@ __global__ __launch_bounds__(64) void br_k_score_tiles(BrParams p, BrArr a, int 
   float *sd = (float *)(sm + BR_TILE_WORKERS * HS);   // LONG: [HS] discounts (+ 4 words read ahead)
   int *sL = sm + BR_TILE_WORKERS * HS + (LONG ? HS + 4 : 0);  // [16] loads, then [16] free slots
   int *scap = sL + BR_TILE_WORKERS;
-  int *sc = scratch + (size_t)inst * br_score_scratch_words(p.Q, G);
+  int *sc = partials + (size_t)inst * br_score_scratch_words(p.Q, G);
   int *pg_key = sc, *pg_g = sc + (size_t)WGN * p.Q;
   int *pi_key = sc + 2 * (size_t)WGN * p.Q, *pi_s = pi_key + (size_t)T * G, *pi_i = pi_s + (size_t)T * G;
 
@@ -565,9 +565,9 @@ __global__ __launch_bounds__(64) void br_k_score_tiles(BrParams p, BrArr a, int 
 // Blocks [0, QB) fold the per-group best workers of 256 requests each; the others take four workers each, one
 // wave per worker with lanes mapped to tiles (at most 32), and fold the per-tile best requests by the same three
 // reductions.  All partial results are requested at once: nothing here waits on a load more than once.
-__global__ __launch_bounds__(256) void br_k_score_combine(BrParams p, BrOut o, const int *scratch, int T, int WGN, int QB) {
+__global__ __launch_bounds__(256) void br_k_score_combine(BrParams p, BrOut o, const int *partials, int T, int WGN, int QB) {
   const int inst = blockIdx.y, tid = threadIdx.x, G = p.G;
-  const int *sc = scratch + (size_t)inst * br_score_scratch_words(p.Q, G);
+  const int *sc = partials + (size_t)inst * br_score_scratch_words(p.Q, G);
   const int *pg_key = sc, *pg_g = sc + (size_t)WGN * p.Q;
   const int *pi_key = sc + 2 * (size_t)WGN * p.Q, *pi_s = pi_key + (size_t)T * G, *pi_i = pi_s + (size_t)T * G;
   if ((int)blockIdx.x < QB) {
@@ -700,7 +700,39 @@ size_t br_score_scratch_bytes(int N, int Q, int G) {
   return N <= BR_SCORE_TILES_MAX_N ? (size_t)N * br_score_scratch_words(Q, G) * sizeof(int) : 0;
 }
 
-void br_launch_score(const BrParams &p, const BrArr &a, const BrOut &o, int *scratch, hipStream_t st) {
+// The same partial results for callers that cannot allocate (br_route_step_static): a fixed device array in
+// place of the workspace area, large enough for the most the tiled path ever needs (BR_SCORE_TILES_MAX_N
+// clusters with the longest queue and the most workers: 1.4 MB).  Every GPU holds its own copy until the
+// process ends.  Host code never uses the array by name: its address on a device comes from
+// hipGetSymbolAddress, once per device, and the kernels get that pointer as an argument like any other buffer.
+// Both kernels write every entry they later read, so nothing has to be cleared between calls; calls that
+// overlap on one GPU (two streams) would race on it.
+#define BR_STATIC_SCRATCH_WORDS (BR_SCORE_TILES_MAX_N * (2 * BR_TILE_GROUPS * 2048 + 3 * 32 * 64))
+static __device__ __align__(256) __attribute__((used)) int scratch[BR_STATIC_SCRATCH_WORDS];
+
+#define BR_MAX_DEVICES 64
+static int *g_static_scratch[BR_MAX_DEVICES];  // device address of `scratch` per device, once resolved
+
+size_t br_static_scratch_bytes() { return (size_t)BR_STATIC_SCRATCH_WORDS * sizeof(int); }
+
+// Address of this library's static scratch array on the CURRENT device (resolved once per device).
+hipError_t br_static_scratch_resolve(int **out) {
+  *out = nullptr;
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= BR_MAX_DEVICES) return hipErrorInvalidDevice;
+  if (!g_static_scratch[dev]) {
+    void *ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    g_static_scratch[dev] = (int *)ptr;
+  }
+  *out = g_static_scratch[dev];
+  return hipSuccess;
+}
+
+void br_launch_score(const BrParams &p, const BrArr &a, const BrOut &o, int *partials, hipStream_t st) {
   int waves = (p.Q + 63) / 64;  // one wave per tile of 64 requests, at most 8 waves
   waves = waves < 1 ? 1 : (waves > 8 ? 8 : waves);
   const int want_tile = o.F != nullptr;
@@ -708,19 +740,19 @@ void br_launch_score(const BrParams &p, const BrArr &a, const BrOut &o, int *scr
   {  // few clusters, long queues, no matrix: a wave per (tile of requests, group of workers), then a combine
     const int T = (p.Q + BR_WAVE - 1) / BR_WAVE;
     const int wpg = (p.G + BR_TILE_GROUPS - 1) / BR_TILE_GROUPS, WGN = (p.G + wpg - 1) / wpg;  // at most 4 groups
-    if (scratch && !want_tile && p.N <= BR_SCORE_TILES_MAX_N && T * WGN >= 8) {
+    if (partials && !want_tile && p.N <= BR_SCORE_TILES_MAX_N && T * WGN >= 8) {
       const dim3 grid((unsigned)T, (unsigned)WGN, (unsigned)p.N), block(BR_WAVE);
       const int HS = longh ? BR_HS(p.H) : BR_HP + 1;
       const size_t lds = ((size_t)BR_TILE_WORKERS * HS + (longh ? HS + 4 : 0) + 2 * BR_TILE_WORKERS) * sizeof(int);
       if (longh)
-        hipLaunchKernelGGL((br_k_score_tiles<true, true>), grid, block, lds, st, p, a, scratch, wpg);
+        hipLaunchKernelGGL((br_k_score_tiles<true, true>), grid, block, lds, st, p, a, partials, wpg);
       else if (p.H > 0)
-        hipLaunchKernelGGL((br_k_score_tiles<true, false>), grid, block, lds, st, p, a, scratch, wpg);
+        hipLaunchKernelGGL((br_k_score_tiles<true, false>), grid, block, lds, st, p, a, partials, wpg);
       else
-        hipLaunchKernelGGL((br_k_score_tiles<false, false>), grid, block, lds, st, p, a, scratch, wpg);
+        hipLaunchKernelGGL((br_k_score_tiles<false, false>), grid, block, lds, st, p, a, partials, wpg);
       const int QB = (p.Q + 255) / 256;
       hipLaunchKernelGGL(br_k_score_combine, dim3((unsigned)(QB + (p.G + 3) / 4), (unsigned)p.N), dim3(256), 0, st, p, o,
-                         (const int *)scratch, T, WGN, QB);
+                         (const int *)partials, T, WGN, QB);
       return;
     }
   }

@@ -12,9 +12,13 @@ void br_launch_advance(const BrParams &p, int t, hipStream_t st);
 void br_launch_project(const BrParams &p, hipStream_t st);
 // horizons beyond BR_HP: fills the discount table p.dl (once per context)
 void br_launch_discounts(const BrParams &p, float gamma, hipStream_t st);
-// `scratch`: br_score_scratch_bytes() of device memory for the partial results of the tiled path, or null
-void br_launch_score(const BrParams &p, const BrArr &a, const BrOut &o, int *scratch, hipStream_t st);
+// `partials`: br_score_scratch_bytes() of device memory for the partial results of the tiled path, or null
+void br_launch_score(const BrParams &p, const BrArr &a, const BrOut &o, int *partials, hipStream_t st);
 size_t br_score_scratch_bytes(int N, int Q, int G);
+// the library's fixed scratch array (for the entry point that may not use workspace scratch): its size, and its
+// device address on the current device
+size_t br_static_scratch_bytes();
+hipError_t br_static_scratch_resolve(int **out);
 void br_launch_assign(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st);
 // horizons beyond BR_HP: per-offset state in LDS, one wave per cluster
 void br_launch_assign_long(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st);
