@@ -41,12 +41,15 @@ extern "C" {
 #define BR_MAX_S 32768
 #define BR_NSTATS 16
 #define BR_NKERNELS 6
+#define BR_STATIC_MAX_INST 16          /* most clusters br_route_step_static serves */
+#define BR_STATIC_SCRATCH_BYTES 1441792 /* device memory the library holds per GPU for it, until the process ends */
 
 enum {
   BR_OK = 0,
   BR_EINVAL = -1, /* null pointer, limit exceeded, inconsistent sizes */
   BR_ENOMEM = -2, /* workspace smaller than br_workspace_bytes() */
-  BR_EHIP = -3    /* a HIP call failed; code kept for br_last_hip_error() */
+  BR_EHIP = -3,   /* a HIP call failed; code kept for br_last_hip_error() */
+  BR_ELIMIT = -4  /* br_route_step_static: the context is larger than the fixed scratch array serves */
 };
 
 /* Slots of the per-instance stats block (int64 each). */
@@ -222,6 +225,24 @@ int32_t br_advance_decode(br_ctx *ctx, int32_t n_steps);
  * br_route_step), BR_EINVAL otherwise.
  */
 int32_t br_route_advance(br_ctx *ctx, const br_arrivals *in, const br_step_out *out, int32_t n_steps);
+
+/*
+ * br_route_step for callers that cannot allocate and cannot hand the library scratch space of their own choosing:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, outputs and
+ * workspace contents afterwards as br_route_step (inputs and outputs are still the caller's buffers).  The one
+ * difference: the partial results of the stage-one reductions for a few clusters with long queues (per-group best
+ * worker per request, per-tile best request per worker) go to a fixed device array inside the library
+ * (BR_STATIC_SCRATCH_BYTES; every GPU the library runs on holds its own copy until the process ends) instead of the
+ * private tail of the workspace.  The call makes no hipMalloc / hipFree, creates no event (launches are not
+ * bracketed even while br_profile_enable is on) and allocates no host memory.
+ * Limit: contexts of at most BR_STATIC_MAX_INST clusters (any G, max_wait, H within the library's limits);
+ * larger ones return BR_ELIMIT and nothing is enqueued.  BR_EHIP if the array's address could not be resolved
+ * when the context was created (br_last_hip_error has the code).
+ * All contexts on one GPU share the array: calls that may overlap on that GPU (different streams, different
+ * threads) race on it and must be serialised by the caller; successive calls on one stream are safe, and nothing
+ * needs clearing between them (every entry that is read is written first by the same call).
+ */
+int32_t br_route_step_static(br_ctx *ctx, const br_arrivals *in, const br_step_out *out);
 
 /*
  * Pool-bypass dispatch for BR-0 (Appendix "Pool-bypass deployment path for BR-0"): instead of

@@ -21,9 +21,9 @@ NKERNELS = 6
 KERNEL_NAMES = ("project", "score", "assign", "advance", "init", "bypass")
 ST = dict(admitted=0, deferred=1, dropped=2, stage1=3, stage2_pops=4, guard=5, overcap=6,
           I_before=7, I_after=8, spread=9, qlen=10, workers_dropped=11)
-BR_OK, BR_EINVAL, BR_ENOMEM, BR_EHIP = 0, -1, -2, -3
+BR_OK, BR_EINVAL, BR_ENOMEM, BR_EHIP, BR_ELIMIT = 0, -1, -2, -3, -4
 
-EXPORTS = ("br_workspace_bytes", "br_init", "br_route_step", "br_route_advance", "br_route_bypass", "br_advance_decode", "br_free",
+EXPORTS = ("br_workspace_bytes", "br_init", "br_route_step", "br_route_step_static", "br_route_advance", "br_route_bypass", "br_advance_decode", "br_free",
            "br_last_hip_error", "br_get_layout", "br_profile_enable", "br_profile_read")
 
 _P = C.c_void_p
@@ -76,6 +76,8 @@ def load():
     lib.br_init.argtypes = [C.POINTER(Config), C.POINTER(InitState), C.POINTER(_P)]
     lib.br_route_step.restype = C.c_int32
     lib.br_route_step.argtypes = [_P, C.POINTER(Arrivals), C.POINTER(StepOut)]
+    lib.br_route_step_static.restype = C.c_int32
+    lib.br_route_step_static.argtypes = [_P, C.POINTER(Arrivals), C.POINTER(StepOut)]
     lib.br_route_advance.restype = C.c_int32
     lib.br_route_advance.argtypes = [_P, C.POINTER(Arrivals), C.POINTER(StepOut), C.c_int32]
     lib.br_route_bypass.restype = C.c_int32
@@ -229,6 +231,13 @@ class Router:
         o = self.out_struct(out)
         _check(self.lib.br_route_step(self.ctx, C.byref(a) if a is not None else None, C.byref(o)),
                "br_route_step", self.ctx)
+
+    def route_step_static_device(self, darr: Optional[DeviceArrivals], out) -> int:
+        """Enqueue one round through the entry point that uses the library's fixed scratch array; returns the
+        status code (BR_ELIMIT for contexts it does not serve) instead of raising."""
+        a = darr.struct() if darr is not None else None
+        o = self.out_struct(out)
+        return int(self.lib.br_route_step_static(self.ctx, C.byref(a) if a is not None else None, C.byref(o)))
 
     def route_advance_device(self, darr: Optional[DeviceArrivals], out, n_steps: int = 1) -> None:
         """Enqueue one round and n_steps decode steps as one launch; no synchronisation."""

@@ -88,6 +88,8 @@ struct br_ctx {
   br_layout lay;
   BrParams p;
   int *score_scratch;
+  int *static_scratch;     // the library's fixed scratch array on this context's device (br_route_step_static), or null
+  int32_t static_hip;      // why it is null: the hipError_t of the failed look-up
   hipStream_t st;
   int32_t last_hip;
   bool prof;
@@ -105,9 +107,10 @@ int32_t fail_hip(br_ctx *ctx, hipError_t e) {
 
 // Enqueue one kernel; with profiling on, bracket it with an event pair on the same stream.
 template <class Fn>
-int32_t enqueue(br_ctx *ctx, int kid, Fn &&fn) {
+int32_t enqueue(br_ctx *ctx, int kid, Fn &&fn, bool bracket = true) {
   EvPair ev{};
-  if (ctx->prof) {
+  const bool prof = ctx->prof && bracket;
+  if (prof) {
     if (!ctx->spare.empty()) {
       ev = ctx->spare.back();
       ctx->spare.pop_back();
@@ -133,10 +136,10 @@ int32_t enqueue(br_ctx *ctx, int kid, Fn &&fn) {
   fn();
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) {
-    if (ctx->prof) ctx->spare.push_back(ev);
+    if (prof) ctx->spare.push_back(ev);
     return fail_hip(ctx, e);
   }
-  if (ctx->prof) {
+  if (prof) {
     e = hipEventRecord(ev.b, ctx->st);
     if (e != hipSuccess) {
       ctx->spare.push_back(ev);
@@ -230,6 +233,10 @@ int32_t br_init(const br_config *cfg, const br_init_state *init, br_ctx **out) {
   p.minm = (int32_t *)(base + l.minm);
   p.dl = dl_at ? (const float *)(base + dl_at) : nullptr;
   ctx->score_scratch = ss_at ? (int *)(base + ss_at) : nullptr;
+  // set-up of the allocation-free entry point: the device address of the fixed scratch array, looked up once per
+  // device with the context's device current (the caller's, as for every launch on its stream)
+  ctx->static_scratch = nullptr;
+  ctx->static_hip = (int32_t)br_static_scratch_resolve(&ctx->static_scratch);
 
   int32_t rc = enqueue(ctx, BR_K_INIT, [&] { br_launch_clear(p, ctx->st); });
   if (rc == BR_OK && p.dl) rc = enqueue(ctx, BR_K_INIT, [&] { br_launch_discounts(p, cfg->gamma, ctx->st); });
@@ -244,8 +251,22 @@ int32_t br_init(const br_config *cfg, const br_init_state *init, br_ctx **out) {
 }
 
 // one round, optionally followed inside the assignment kernel by `adv_t` decode steps
-static int32_t route(br_ctx *ctx, const br_arrivals *in, const br_step_out *out, int32_t adv_t) {
+// fixed_scratch: the tiled score path keeps its partial results in the library's fixed device array instead of
+// the workspace, and no launch is bracketed by profiling events (creating one allocates)
+static int32_t route(br_ctx *ctx, const br_arrivals *in, const br_step_out *out, int32_t adv_t, bool fixed_scratch = false) {
   if (!ctx || adv_t < 0) return BR_EINVAL;
+  const bool br = !fixed_scratch;
+  int *partials = ctx->score_scratch;
+  if (fixed_scratch) {
+    if ((uint64_t)br_score_scratch_bytes(ctx->p.N, ctx->p.Q, ctx->p.G) > (uint64_t)br_static_scratch_bytes() ||
+        ctx->p.N > BR_STATIC_MAX_INST)
+      return BR_ELIMIT;
+    if (!ctx->static_scratch) {
+      ctx->last_hip = ctx->static_hip;
+      return BR_EHIP;
+    }
+    partials = ctx->static_scratch;
+  }
   BrArr a{};
   if (in && in->arr_cap < 0) return BR_EINVAL;
   if (in && in->count && in->arr_cap > 0) {
@@ -271,21 +292,21 @@ static int32_t route(br_ctx *ctx, const br_arrivals *in, const br_step_out *out,
   const bool split_adv = adv_t > 0 && p.R_max > 8;
   p.adv_t = split_adv ? 0 : adv_t;
   int32_t rc = BR_OK;
-  if (p.H > 0) rc = enqueue(ctx, BR_K_PROJECT, [&] { br_launch_project(p, ctx->st); });
+  if (p.H > 0) rc = enqueue(ctx, BR_K_PROJECT, [&] { br_launch_project(p, ctx->st); }, br);
   // large batches of clusters with short queues: the reductions ride along in the assignment launch
   const bool together = (o.best_g || o.best_i) && !o.F && p.N >= BR_SCORE_WAVE_MIN_N && p.R_max <= 8 &&
                         (p.H == 0 ? p.Q <= 256 : (p.H <= BR_HP && p.Q <= 512));
   if (rc == BR_OK && !together && (o.F || o.best_g || o.best_i))
-    rc = enqueue(ctx, BR_K_SCORE, [&] { br_launch_score(p, a, o, ctx->score_scratch, ctx->st); });
+    rc = enqueue(ctx, BR_K_SCORE, [&] { br_launch_score(p, a, o, partials, ctx->st); }, br);
   if (rc == BR_OK) {
     if (together && p.H > 0)
-      rc = enqueue(ctx, BR_K_ASSIGN, [&] { br_launch_route_h(p, a, o, ctx->st); });
+      rc = enqueue(ctx, BR_K_ASSIGN, [&] { br_launch_route_h(p, a, o, ctx->st); }, br);
     else if (together)
-      rc = enqueue(ctx, BR_K_ASSIGN, [&] { br_launch_route4(p, a, o, ctx->st); });
+      rc = enqueue(ctx, BR_K_ASSIGN, [&] { br_launch_route4(p, a, o, ctx->st); }, br);
     else
-      rc = enqueue(ctx, BR_K_ASSIGN, [&] { br_launch_assign(p, a, o, ctx->st); });
+      rc = enqueue(ctx, BR_K_ASSIGN, [&] { br_launch_assign(p, a, o, ctx->st); }, br);
   }
-  if (rc == BR_OK && split_adv) rc = enqueue(ctx, BR_K_ADVANCE, [&] { br_launch_advance(p, adv_t, ctx->st); });
+  if (rc == BR_OK && split_adv) rc = enqueue(ctx, BR_K_ADVANCE, [&] { br_launch_advance(p, adv_t, ctx->st); }, br);
   return rc;
 }
 
@@ -293,6 +314,10 @@ int32_t br_route_step(br_ctx *ctx, const br_arrivals *in, const br_step_out *out
 
 int32_t br_route_advance(br_ctx *ctx, const br_arrivals *in, const br_step_out *out, int32_t n_steps) {
   return route(ctx, in, out, n_steps);
+}
+
+int32_t br_route_step_static(br_ctx *ctx, const br_arrivals *in, const br_step_out *out) {
+  return route(ctx, in, out, 0, true);
 }
 
 int32_t br_route_bypass(br_ctx *ctx, const br_arrivals *in, const br_step_out *out) {

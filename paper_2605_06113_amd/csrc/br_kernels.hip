@@ -1,6 +1,7 @@
 // gfx950 kernels of the BalanceRoute route step, except the sequential assignment
 // (br_assign_kernel.h): state initialisation, decode step, horizon projection, and the
 // F-score matrix with its stage-one reductions.
+#include "br.h"
 #include "br_device.h"
 #include "br_launch.h"
 #include "br_score_wave.h"
@@ -708,7 +709,10 @@ size_t br_score_scratch_bytes(int N, int Q, int G) {
 // Both kernels write every entry they later read, so nothing has to be cleared between calls; calls that
 // overlap on one GPU (two streams) would race on it.
 #define BR_STATIC_SCRATCH_WORDS (BR_SCORE_TILES_MAX_N * (2 * BR_TILE_GROUPS * 2048 + 3 * 32 * 64))
-static __device__ __align__(256) __attribute__((used)) int scratch[BR_STATIC_SCRATCH_WORDS];
+static __device__ __align__(256) int scratch[BR_STATIC_SCRATCH_WORDS];
+static_assert(BR_STATIC_SCRATCH_WORDS * sizeof(int) == BR_STATIC_SCRATCH_BYTES && BR_SCORE_TILES_MAX_N == BR_STATIC_MAX_INST &&
+                  BR_MAX_WAIT == 2048 && BR_MAX_G == 64,
+              "the fixed scratch array covers the largest tiled score launch");
 
 #define BR_MAX_DEVICES 64
 static int *g_static_scratch[BR_MAX_DEVICES];  // device address of `scratch` per device, once resolved
