@@ -27,38 +27,162 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 # integer vector peak: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz, one int32 op per lane per clock
 ALU_INT_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
-# HBM KiB per launch on this workload from rocprofv3 --pmc (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, see
-# profiles/bench_c4_kernels.md); an entry is None when its kernel changed after the counters were taken
 LDS_PEAK_GBS = 256 * 128 * 2.4          # 256 CUs x 128 B per clock x 2.4 GHz
-LDS_INSTS_PER_WAVE = 236.1              # br_k_route4 (c4), rocprofv3 --pmc SQ_INSTS_LDS / SQ_WAVES
-TRAFFIC_KIB = {"assign+advance": 2.0 * 43722.6 + 92343.4,   # br_k_route4<true>: reductions + round + decode step
-               "assign": 2.0 * 6773.5 + 21800.9, "advance": 2.0 * 37923.5 + 74527.1}
+PROFILE_MD = os.path.join(ROOT, "profiles", "bench_c4_kernels.md")
 
 
-def cpu_baseline(cfg, init, arr, min_seconds=10.0):
-    """The oracle as it stands, single thread, on the same workload (repeated whole batches)."""
+def source_hash():
+    """sha256 over the kernel sources and the C header: counters in profiles/ are valid for exactly one value."""
+    import hashlib
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2605_06113_amd", "csrc")
+    for f in sorted(os.listdir(csrc)) + [os.path.join(ROOT, "include", "br.h")]:
+        path = f if os.path.isabs(f) else os.path.join(csrc, f)
+        h.update(os.path.basename(path).encode() + b"\0" + open(path, "rb").read())
+    return h.hexdigest()
+
+
+def profile_counters():
+    """Counter figures of the rocprofv3 summary (lines `counter <name> <kernel> = <value>` of its last section),
+    or {} when the sources have changed since they were collected (then they say nothing about these kernels)."""
+    vals, sha = {}, None
+    try:
+        for line in open(PROFILE_MD):
+            line = line.strip()
+            if line.startswith("sources_sha256 = "):
+                sha = line.split("=", 1)[1].strip()
+            elif line.startswith("counter "):
+                key, val = line[len("counter "):].rsplit("=", 1)
+                vals[key.strip()] = float(val)
+    except OSError:
+        return {}
+    return vals if sha == source_hash() else {}
+
+
+def host_info():
+    model = "unknown"
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                model = line.split(":", 1)[1].strip()
+                break
+    except OSError:
+        pass
+    try:
+        gcc = __import__("subprocess").check_output(["gcc", "--version"], text=True).splitlines()[0]
+    except Exception:
+        gcc = "gcc (version unknown)"
+    try:
+        usable = len(os.sched_getaffinity(0))
+    except AttributeError:
+        usable = os.cpu_count() or 1
+    return dict(nproc=os.cpu_count(), usable_cpus=usable, cpu_model=model,
+                compiler=gcc + " -O2 -ffp-contract=off (oracle/br_oracle.c, one thread per instance stream)")
+
+
+def _take_instances(obj, lo, hi):
+    import dataclasses
+    return type(obj)(**{f.name: (None if getattr(obj, f.name) is None else getattr(obj, f.name)[lo:hi])
+                        for f in dataclasses.fields(obj)})
+
+
+_PARTS = None
+
+
+def _oracle_batch(c, i, a):
     from oracle import br_oracle
-    pairs = 0
-    decisions = 0
+    oc = br_oracle.OracleCluster(c, i)
+    t0 = time.perf_counter()
+    out = oc.route_step(a, want_scores=True)
+    oc.advance(1)
+    dt = time.perf_counter() - t0
+    return dt, int(out["stats"][:, br_oracle.ST["qlen"]].sum()) * c.G, int(out["stats"][:, br_oracle.ST["admitted"]].sum())
+
+
+def _oracle_part(k):
+    return _oracle_batch(*_PARTS[k])
+
+
+def cpu_baseline(cfg, init, arr, min_seconds=8.0):
+    """The oracle as it stands on the host cores of this machine, same arrays as the GPU.  Primary figure: the
+    single-threaded oracle fanned over the usable cores, one slice of the instances per thread (instances are
+    independent; the C code runs outside the interpreter lock).  Beside it the single-thread rate, and the oracle's
+    per-step latency on the one-instance configurations."""
+    import dataclasses
+    from oracle import br_oracle
+    from paper_2605_06113_amd import workloads as wl
+    info = host_info()
+
+    batch = _oracle_batch
+    # (i) one thread, whole batches
+    pairs = decisions = reps = 0
     elapsed = 0.0
-    reps = 0
     while elapsed < min_seconds and reps < 50:
-        oc = br_oracle.OracleCluster(cfg, init)
-        t0 = time.perf_counter()
-        out = oc.route_step(arr, want_scores=True)
-        oc.advance(1)
-        elapsed += time.perf_counter() - t0
-        pairs += int(out["stats"][:, br_oracle.ST["qlen"]].sum()) * cfg.G
-        decisions += int(out["stats"][:, br_oracle.ST["admitted"]].sum())
+        dt, p, d = batch(cfg, init, arr)
+        elapsed += dt
+        pairs += p
+        decisions += d
         reps += 1
-    return dict(value=pairs / elapsed, unit="pairs/s", cores=1, kind="oracle",
-                sample=f"{reps} x the full batch of {cfg.n_inst} instances (route + decode step), "
-                       f"{elapsed:.1f} s of single-thread CPU time",
-                decisions_per_s=decisions / elapsed)
+    single = dict(value=pairs / elapsed, unit="pairs/s", cores=1, decisions_per_s=decisions / elapsed,
+                  us_per_instance_step=elapsed / (reps * cfg.n_inst) * 1e6,
+                  sample=f"{reps} x the full batch of {cfg.n_inst} instances (route + decode step), {elapsed:.1f} s")
+
+    # (ii) all usable cores (the GPU box gives a one-GPU job 16): the same single-threaded oracle in T worker
+    # processes, one contiguous slice of the instances each (this process never touches the GPU, so it may fork)
+    import multiprocessing as mp
+    T = max(1, min(info["usable_cpus"], 16, cfg.n_inst))
+    cuts = [cfg.n_inst * k // T for k in range(T + 1)]
+    global _PARTS
+    _PARTS = [(dataclasses.replace(cfg, n_inst=cuts[k + 1] - cuts[k]), _take_instances(init, cuts[k], cuts[k + 1]),
+               _take_instances(arr, cuts[k], cuts[k + 1])) for k in range(T)]
+    pairs = decisions = reps = 0
+    wall = 0.0
+    with mp.get_context("fork").Pool(T) as pool:
+        pool.map(_oracle_part, range(T))          # untimed: workers start, the oracle library loads in each
+        while wall < min_seconds / 2 and reps < 200:
+            t0 = time.perf_counter()
+            res = pool.map(_oracle_part, range(T))
+            wall += time.perf_counter() - t0
+            pairs += sum(r[1] for r in res)
+            decisions += sum(r[2] for r in res)
+            reps += 1
+    allc = dict(value=pairs / wall, unit="pairs/s", cores=T, decisions_per_s=decisions / wall,
+                sample=f"{reps} x the full batch, instances split over {T} processes of one thread each, {wall:.1f} s wall")
+
+    # (iii) per-step latency of the oracle on the single-instance configurations (wall-clock of orc_route_step)
+    per_cfg = {}
+    for name, steps in (("c1", 1), ("c2", 2000), ("c3", 1000), ("c5", 3000)):
+        c = wl.config(name)
+        lat = []
+        if name == "c1":
+            i1, a1 = wl.initial_state(c), wl.initial_waiting(c)
+            for _ in range(200):
+                oc = br_oracle.OracleCluster(c, i1)
+                t0 = time.perf_counter()
+                oc.route_step(a1, want_scores=False)
+                lat.append(time.perf_counter() - t0)
+        else:
+            tr = wl.arrival_trace(c, steps)
+            oc = br_oracle.OracleCluster(c)
+            for k in range(steps):
+                a = tr.step(k)
+                t0 = time.perf_counter()
+                oc.route_step(a, want_scores=False)
+                lat.append(time.perf_counter() - t0)
+                oc.advance(1)
+        lat = np.array(lat) * 1e6
+        per_cfg[name] = dict(steps=len(lat), mean_us=float(lat.mean()), p50_us=float(np.percentile(lat, 50)),
+                             p99_us=float(np.percentile(lat, 99)),
+                             note="200 repeats of the one round" if name == "c1" else
+                             (f"first {steps} of {c.steps} decode steps" if steps < c.steps else "all decode steps"))
+    return dict(value=allc["value"], unit="pairs/s", cores=T, kind="oracle",
+                sample=allc["sample"] + "; workload: the bench's own batch (c4), route + decode step",
+                decisions_per_s=allc["decisions_per_s"], single_thread=single, per_step_latency=per_cfg, **info)
 
 
-def latency_run(steps, device, deployed=False):
-    """Host wall-clock per round of one instance.  Default: the BR-H stress shape (G=64, H=8, queue cap 2048).
+def latency_run(steps, device, deployed=False, name="c5"):
+    """Host wall-clock per round of one instance.  Default: the BR-H stress shape (G=64, H=8, queue cap 2048);
+    name: another of the single-instance replay configurations (c2, c3).
     deployed: the setting of the paper's dispatch-overhead measurement (Sec. 6.4: G=8, R_max=4, H=80), the
     estimate kept by the library with the empirical-survival estimator, workers near full."""
     import torch
@@ -72,8 +196,11 @@ def latency_run(steps, device, deployed=False):
         label = ("paper's dispatch-overhead setting: BR-H H=80, G=8, R_max=4, B=64, queue cap 256, estimate maintained "
                  "from an 8000-length history (refresh every 40 tokens, gate 0.5), MMPP arrivals 0.7/2.0, one instance")
     else:
-        cfg, hist, init = wl.config("c5"), None, None   # the paper's p_fin gate at its default
-        label = "c5 shape: BR-H H=8, G=64, B=96, queue cap 2048, MMPP arrivals 60/300, one instance"
+        cfg, hist, init = wl.config(name), None, None   # the paper's p_fin gate at its default
+        label = {"c5": "c5 shape: BR-H H=8, G=64, B=96, queue cap 2048, MMPP arrivals 60/300, one instance",
+                 "c3": "c3: BR-H H=4, G=32, B=96, queue cap 512, Poisson(80) arrivals, one instance",
+                 "c2": "c2: BR-0, G=16, B=96, queue cap 256, Poisson(40) arrivals, one instance"}[name]
+        steps = min(steps, cfg.steps)
     tr = wl.arrival_trace(cfg, steps)
     warm = binding.Router(cfg, init, device=device, hist=hist)   # untimed: loads the kernels this shape uses
     for k in range(3):
@@ -106,11 +233,10 @@ def latency_run(steps, device, deployed=False):
     steady = lat[steps // 2:]
     res = dict(workload=label,
                steps=steps, p50_us=float(np.percentile(lat, 50) * 1e6), p99_us=float(np.percentile(lat, 99) * 1e6),
-               max_us=float(lat.max() * 1e6), steady_p50_us=float(np.percentile(steady, 50) * 1e6),
+               mean_us=float(lat.mean() * 1e6), max_us=float(lat.max() * 1e6), steady_p50_us=float(np.percentile(steady, 50) * 1e6),
                steady_p99_us=float(np.percentile(steady, 99) * 1e6), final_qlen=int(st[0, binding.ST["deferred"]]))
     if deployed:
         state = r.state()
-        res["mean_us"] = float(lat.mean() * 1e6)
         res["final_active"] = int(state["n"].sum())
         # context only: another machine, the production trace, a Python dispatcher (Sec. 6.4)
         res["paper_dispatch_ms"] = dict(p50=1.20, mean=1.34, p99=2.77)
@@ -286,6 +412,66 @@ def window_run(device, R_max=16, n_inst=1024, steps=4, warmup=1):
                 decisions_per_s=int(st[:, binding.ST["admitted"]].sum()) * steps / elapsed)
 
 
+def c1_latency(device, reps=200):
+    """The single BR-0 round of c1 (one instance, G=4, 32 waiting), repeated on fresh contexts."""
+    import torch
+    from paper_2605_06113_amd import binding, workloads as wl
+    cfg = wl.config("c1")
+    init, arr = wl.initial_state(cfg), wl.initial_waiting(cfg)
+    darr = binding.DeviceArrivals(arr, device, 0)
+    lat = []
+    for k in range(reps + 3):
+        r = binding.Router(cfg, init, device=device)
+        out = r.alloc_outputs(scores=True, matrix=False)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        r.route_step_device(darr, out)
+        r.stream.synchronize()
+        if k >= 3:
+            lat.append(time.perf_counter() - t0)
+        r.close()
+    lat = np.array(lat) * 1e6
+    return dict(workload="c1: one BR-0 round, one instance, G=4, B=16, 20 active, 32 waiting", steps=reps,
+                mean_us=float(lat.mean()), p50_us=float(np.percentile(lat, 50)), p99_us=float(np.percentile(lat, 99)))
+
+
+def fmatrix_run(device, cfg, init, arr, steps=6, warmup=2):
+    """K2 with the score matrix materialised (the c4 batch): every (waiting request, worker) pair of the
+    step-start snapshot written to HBM, 4 B per pair, plus both reductions; the round follows as its own launch."""
+    import torch
+    from paper_2605_06113_amd import binding
+    routers = [binding.Router(cfg, init, device=device) for _ in range(steps + warmup)]
+    darr = binding.DeviceArrivals(arr, device, 0)
+    out = routers[0].alloc_outputs(scores=True, matrix=True)
+    for r in routers[:warmup]:
+        r.route_step_device(darr, out)
+    torch.cuda.synchronize()
+    for r in routers[warmup:]:
+        r.profile(True)
+    t0 = time.perf_counter()
+    for r in routers[warmup:]:
+        r.route_step_device(darr, out)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    st = out["stats"].cpu().numpy()
+    qn = int(st[:, binding.ST["qlen"]].sum())
+    ms = cnt = 0
+    for r in routers[warmup:]:
+        m, c = r.profile_read()["score"]
+        ms += m
+        cnt += c
+    for r in routers:
+        r.close()
+    avg = ms / max(cnt, 1)
+    N, G = cfg.n_inst, cfg.G
+    nbytes = qn * G * 4 + qn * 4 + qn * 4 + N * G * 12      # matrix; s read, best_g written; L, n read, best_i written
+    gbs = nbytes / (avg * 1e-3) / 1e9
+    return dict(workload="c4 batch, br_route_step with F requested: score matrix (4096 x 256 x 16 int32) + reductions, then the round",
+                kernel="br_k_score<false>", kernel_avg_ms=avg, launches=cnt, bytes_per_launch=nbytes, bound="hbm",
+                achieved_GBs=gbs, frac=gbs / HBM_PEAK_GBS, pairs_per_s=qn * G / (avg * 1e-3),
+                ms_per_round_with_matrix=elapsed / steps * 1e3)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -294,6 +480,9 @@ def main():
     ap.add_argument("--latency-steps", type=int, default=10000,
                     help="decode steps of the single-instance latency replay (the stress shape runs 10000)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-baseline-only", action="store_true",
+                    help="print only the oracle's timing (JSON); what the default run starts as a child process, so "
+                         "that the oracle's worker processes are forked from a process that never touched the GPU")
     ap.add_argument("--profile-every", type=int, default=4,
                     help="bracket the kernels of every n-th timed step with HIP events (per-kernel durations)")
     ap.add_argument("--two-calls", action="store_true",
@@ -309,6 +498,12 @@ def main():
         print("bench.py: this build measures one GPU only (instances shard across GPUs with no exchange); "
               "run with --gpus 1", file=sys.stderr)
         sys.exit(2)
+
+    if args.cpu_baseline_only:
+        from paper_2605_06113_amd import workloads as wl
+        cfg = wl.config("c4")
+        print(json.dumps(cpu_baseline(cfg, wl.initial_state(cfg), wl.initial_waiting(cfg))))
+        return
 
     import torch
     from paper_2605_06113_amd import binding, workloads as wl
@@ -372,13 +567,24 @@ def main():
     qn = int(stats[:, binding.ST["qlen"]].sum())
     pairs_per_step = qn * cfg.G
 
-    # algorithmic work per launch of each kernel
+    # Algorithmic work per launch (HBM bytes the step has to move, whatever the kernel does):
+    #   decode step (K5): 16 B per occupied slot (kv, rem read and written);
+    #   round (K4), per instance: 4 R (prefill lengths read) + 4 R (assignments written) + 16 G (L, n read and
+    #     written) + (8 + 4 H) per admission (kv, rem and prediction row of the new list entry), H = 0 here;
+    #   snapshot reductions (K2 + K3) without the matrix: their outputs, 4 R + 4 G per instance (inputs are K4's).
     N, G, B, Q = cfg.n_inst, cfg.G, cfg.B, cfg.max_wait
     occupied_after = N * G * 128 + admitted          # slots the decode step touches
-    bytes_advance = occupied_after * 16 + N * G * 16  # kv, rem read + written; L, n read + written
-    bytes_score = qn * 4 + qn * 4 + N * G * (8 + 4)   # s read, best_g written; L, n read, best_i written
-    bytes_assign = qn * (4 + 4 + 4 + 4 + 4) + admitted * 8 + N * G * 16 + N * 16 * 8
-    ops_assign = 4.0 * admitted * (Q)               # per admission: one score (4 int ops) per waiting slot
+    bytes_advance = occupied_after * 16
+    bytes_assign = qn * 4 + qn * 4 + N * G * 16 + admitted * 8
+    bytes_score = qn * 4 + N * G * 4
+    # side figure: integer operations of the method itself, 4 per score; every admission scores the requests still
+    # waiting at that moment (qn, qn - 1, ...), the snapshot scores every pair once
+    st_q = stats[:, binding.ST["qlen"]].astype(np.float64)
+    st_a = stats[:, binding.ST["admitted"]].astype(np.float64)
+    ops_assign = 4.0 * float((st_a * st_q - st_a * (st_a - 1) / 2).sum())
+    counters = profile_counters()
+    kname = {(True, "assign"): "br_k_route4<true>", (False, "assign"): "br_k_route4<false>",
+             (True, "advance"): "br_k_advance<1,2,false>", (False, "advance"): "br_k_advance<1,2,false>"}
 
     def kernel_table(kern, fused):
         tab = {}
@@ -387,43 +593,47 @@ def main():
                 continue
             avg = ms / c
             e = dict(avg_ms=avg, launches=c)
-            # on this workload the snapshot reductions ride in the assignment launch (br_k_route4); the fused
-            # launch also streams the lists
-            b_assign = bytes_assign + (qn * 4 + N * G * 4) + (bytes_advance if fused else 0)   # + outputs of the reductions
-            o_assign = ops_assign + 4.0 * pairs_per_step
             if k == "advance":
-                e.update(bound="hbm", achieved_GBs=bytes_advance / (avg * 1e-3) / 1e9,
-                         frac=bytes_advance / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS)
+                nb = bytes_advance
             elif k == "score":
-                e.update(bound="hbm", achieved_GBs=bytes_score / (avg * 1e-3) / 1e9,
-                         frac=bytes_score / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS)
+                nb = bytes_score + qn * 4 + N * G * 8
             elif k == "assign":
-                e.update(bound="alu", achieved_Tops=o_assign / (avg * 1e-3) / 1e12,
-                         frac=o_assign / (avg * 1e-3) / 1e12 / ALU_INT_PEAK_TOPS,
-                         hbm_GBs=b_assign / (avg * 1e-3) / 1e9, includes_snapshot_reductions=True,
-                         includes_decode_step=bool(fused))
+                # on this workload the snapshot reductions ride in the round's launch (br_k_route4); the fused
+                # launch also applies the decode step
+                nb = bytes_assign + bytes_score + (bytes_advance if fused else 0)
+                ops = ops_assign + 4.0 * pairs_per_step
+                e.update(alu=dict(achieved_Tops=ops / (avg * 1e-3) / 1e12, peak_Tops=ALU_INT_PEAK_TOPS,
+                                  frac=ops / (avg * 1e-3) / 1e12 / ALU_INT_PEAK_TOPS,
+                                  ops="4 per (admission, request still waiting) + 4 per snapshot pair"),
+                         includes_snapshot_reductions=True, includes_decode_step=bool(fused))
+            else:
+                tab[k] = e
+                continue
+            gbs = nb / (avg * 1e-3) / 1e9
+            e.update(bound="hbm", kernel=kname.get((bool(fused), k), k), bytes_per_launch=nb, achieved_GBs=gbs,
+                     frac=gbs / HBM_PEAK_GBS)
             tab[k] = e
         return tab
 
     per_kernel = kernel_table(kern, fused)
     dom = max((k for k in per_kernel if k != "init"), key=lambda k: per_kernel[k]["avg_ms"])
     d = per_kernel[dom]
-    if d["bound"] == "hbm":
-        roofline = dict(bound="hbm", kernel=dom, achieved=d["achieved_GBs"], peak=HBM_PEAK_GBS, unit="GB/s",
-                        frac=d["frac"])
-    else:
-        roofline = dict(bound="alu", kernel=dom, achieved=d["achieved_Tops"], peak=ALU_INT_PEAK_TOPS, unit="TOP/s",
-                        frac=d["frac"])
-    kib = args.traffic_kib if args.traffic_kib is not None else TRAFFIC_KIB.get(dom + ("+advance" if fused else ""))
-    roofline["traffic"] = None if kib is None else kib * 1024.0
-    roofline["avg_launch_ms"] = d["avg_ms"]
-    if dom == "assign":
+    roofline = dict(bound="hbm", kernel=d["kernel"], achieved=d["achieved_GBs"], peak=HBM_PEAK_GBS, unit="GB/s",
+                    frac=d["frac"], bytes_per_launch=d["bytes_per_launch"], avg_launch_ms=d["avg_ms"])
+    # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (profiles/); null once the sources changed
+    tb = args.traffic_kib * 1024.0 if args.traffic_kib is not None else counters.get("traffic_bytes " + d["kernel"])
+    roofline["traffic"] = tb
+    if "alu" in d:
+        roofline["alu"] = d["alu"]
         # LDS traffic of the round kernel: instructions per wave from rocprofv3 --pmc SQ_INSTS_LDS (profiles/), taken
         # as 64 lanes x 4 B each, against 128 B per clock and CU; the dependent chain lives in registers and DPP
-        lds_bytes = LDS_INSTS_PER_WAVE * 64 * 4 * cfg.n_inst
-        lds_gbs = lds_bytes / (d["avg_ms"] * 1e-3) / 1e9
-        roofline["lds"] = dict(achieved_GBs=lds_gbs, peak_GBs=LDS_PEAK_GBS, frac=lds_gbs / LDS_PEAK_GBS,
-                               insts_per_wave=LDS_INSTS_PER_WAVE)
+        lpw = counters.get("lds_insts_per_wave " + d["kernel"])
+        if lpw is not None:
+            lds_gbs = lpw * 64 * 4 * cfg.n_inst / (d["avg_ms"] * 1e-3) / 1e9
+            roofline["lds"] = dict(achieved_GBs=lds_gbs, peak_GBs=LDS_PEAK_GBS, frac=lds_gbs / LDS_PEAK_GBS,
+                                   insts_per_wave=lpw)
+        else:
+            roofline["lds"] = None
     step_bytes = bytes_advance + bytes_score + bytes_assign
     ms_per_step = elapsed / K * 1e3
 
@@ -446,6 +656,7 @@ def main():
         res["two_calls"] = dict(entry="br_route_step + br_advance_decode", ms_per_step=e2 / K * 1e3,
                                 pairs_per_s=pairs_per_step * K / e2, kernels=kernel_table(k2, False))
     if not args.no_brh:
+        res["fmatrix"] = fmatrix_run(device, cfg, init, arr)
         res["brh_batched"] = brh_run(device)
         res["brh_batched_gate_off"] = brh_run(device, gate=0.0)   # hazards live: no request counts at the last offset
         res["brh_batched_h80"] = brh_run(device, deployed=True)
@@ -454,9 +665,19 @@ def main():
         res["replay_batched"] = replay_run(device)
     if args.latency_steps > 0:
         res["latency"] = latency_run(args.latency_steps, device)
+        res["latency_c1"] = c1_latency(device)
+        res["latency_c2"] = latency_run(args.latency_steps, device, name="c2")
+        res["latency_c3"] = latency_run(args.latency_steps, device, name="c3")
         res["latency_deployed"] = latency_run(min(args.latency_steps, 4000), device, deployed=True)
     if not args.no_cpu_baseline:
-        res["cpu_baseline"] = cpu_baseline(cfg, init, arr)
+        import subprocess
+        torch.cuda.synchronize()
+        child = subprocess.run([sys.executable, os.path.abspath(__file__), "--cpu-baseline-only"], capture_output=True,
+                               text=True, timeout=600)
+        if child.returncode != 0:
+            print(child.stderr, file=sys.stderr)
+            raise RuntimeError("the oracle timing leg failed")
+        res["cpu_baseline"] = json.loads(child.stdout.strip().splitlines()[-1])
     print(json.dumps(res))
 
 
