@@ -65,7 +65,12 @@ enum {
   BR_ST_I_AFTER = 8,         /* ... after the round */
   BR_ST_SPREAD = 9,          /* max(L) - min(L) after the round (Sec. 6.1 "average imbalance") */
   BR_ST_QLEN = 10,           /* waiting requests considered (after the arrivals joined) */
-  BR_ST_WORKERS_DROPPED = 11 /* workers set aside because no waiting request was admissible */
+  BR_ST_WORKERS_DROPPED = 11, /* workers set aside because no waiting request was admissible */
+  BR_ST_LOAD_RANGE = 12       /* workers whose load after the call is 2^25 or more: outside the input range stated
+                                 above.  The kernels order workers by keys that pack a load into 25 bits, so from the
+                                 round that reports a non-zero count on the choice of worker may differ from
+                                 Alg. BR-0 / BR-H (loads, lists and counters stay consistent); keep B * (longest
+                                 KV length) below 2^25 */
 };
 
 /* Kernel ids for br_profile_read(). */

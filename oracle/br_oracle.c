@@ -592,6 +592,7 @@ int32_t orc_route_step(const orc_params *P, orc_io *io) {
       if (R.L[g] > mx) mx = R.L[g];
       if (R.L[g] < mn) mn = R.L[g];
       if (P->token_cap > 0 && R.L[g] > P->token_cap) st[ORC_ST_OVERCAP] += 1;
+      if (R.L[g] >= ((int64_t)1 << 25)) st[ORC_ST_LOAD_RANGE] += 1;
     }
     st[ORC_ST_SPREAD] = mx - mn;
   }
@@ -715,6 +716,7 @@ int32_t orc_route_bypass(const orc_params *P, orc_io *io) {
       if (L0[g] > mx) mx = L0[g];
       if (L0[g] < mn) mn = L0[g];
       if (P->token_cap > 0 && L0[g] > P->token_cap) st[ORC_ST_OVERCAP] += 1;
+      if (L0[g] >= ((int64_t)1 << 25)) st[ORC_ST_LOAD_RANGE] += 1;
     }
     st[ORC_ST_SPREAD] = mx - mn;
   }

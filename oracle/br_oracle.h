@@ -65,7 +65,8 @@ enum {
   ORC_ST_I_AFTER = 8,
   ORC_ST_SPREAD = 9,
   ORC_ST_QLEN = 10,
-  ORC_ST_WORKERS_DROPPED = 11
+  ORC_ST_WORKERS_DROPPED = 11,
+  ORC_ST_LOAD_RANGE = 12 /* workers whose load after the call is 2^25 or more (outside the stated input range) */
 };
 
 typedef struct {

@@ -20,7 +20,7 @@ _LIB = os.path.join(_HERE, "libbr_oracle.so")
 
 NSTATS = 16
 ST = dict(admitted=0, deferred=1, dropped=2, stage1=3, stage2_pops=4, guard=5, overcap=6,
-          I_before=7, I_after=8, spread=9, qlen=10, workers_dropped=11)
+          I_before=7, I_after=8, spread=9, qlen=10, workers_dropped=11, load_range=12)
 
 
 def build(force: bool = False) -> str:

@@ -20,7 +20,7 @@ NSTATS = 16
 NKERNELS = 6
 KERNEL_NAMES = ("project", "score", "assign", "advance", "init", "bypass")
 ST = dict(admitted=0, deferred=1, dropped=2, stage1=3, stage2_pops=4, guard=5, overcap=6,
-          I_before=7, I_after=8, spread=9, qlen=10, workers_dropped=11)
+          I_before=7, I_after=8, spread=9, qlen=10, workers_dropped=11, load_range=12)
 BR_OK, BR_EINVAL, BR_ENOMEM, BR_EHIP, BR_ELIMIT = 0, -1, -2, -3, -4
 
 EXPORTS = ("br_workspace_bytes", "br_init", "br_route_step", "br_route_step_static", "br_route_advance", "br_route_bypass", "br_advance_decode", "br_free",

@@ -181,6 +181,7 @@ __device__ __forceinline__ void br_write_state(const BrTailArgs &t, int inst, in
   const int Lmax = br_wave_max(Lact);
   const int Lmin = br_wave_min(act ? Lact : INT32_MAX);
   const int over = __builtin_popcountll(br_ballot(act && t.C > 0 && Lact > t.C));
+  const int wide = __builtin_popcountll(br_ballot(act && Lact >= (1 << 25)));  // beyond what the packed worker keys order
   long long sumL = 0;
   if (t.stats) {
     const int L0 = act ? Lcur : 0;
@@ -201,7 +202,8 @@ __device__ __forceinline__ void br_write_state(const BrTailArgs &t, int inst, in
       BR_STAT(t, inst, 9) = (long long)Lmax - Lmin;
       BR_STAT(t, inst, 10) = qn;
       BR_STAT(t, inst, 11) = rc.wdrop;
-      for (int k = 12; k < 16; ++k) BR_STAT(t, inst, k) = 0;
+      BR_STAT(t, inst, 12) = wide;
+      for (int k = 13; k < 16; ++k) BR_STAT(t, inst, k) = 0;
     }
   }
 }

@@ -99,6 +99,7 @@ __global__ __launch_bounds__(256) void br_k_bypass(BrParams p, BrArr a, BrOut o,
   const int Lmax = br_wave_max(L);
   const int Lmin = br_wave_min(act ? L : INT32_MAX);
   const int over = __builtin_popcountll(br_ballot(act && p.C > 0 && L > p.C));
+  const int wide = __builtin_popcountll(br_ballot(act && L >= (1 << 25)));
   const long long sumL = o.stats ? sum_loads() : 0;
   if (lane == 0) {
     p.qlen[inst] = q;
@@ -112,6 +113,7 @@ __global__ __launch_bounds__(256) void br_k_bypass(BrParams p, BrArr a, BrOut o,
       BR_STATB(o, inst, 8) = (long long)G * Lmax - sumL;
       BR_STATB(o, inst, 9) = (long long)Lmax - Lmin;
       BR_STATB(o, inst, 10) = cnt;
+      BR_STATB(o, inst, 12) = wide;
     }
   }
 }

@@ -366,6 +366,53 @@ def test_edge_cases_long_horizon_and_wide_window():
         r.close()
 
 
+def test_loads_at_the_edge_of_the_key_range():
+    """Per-worker loads just below 2^25 (the range the library states: its worker keys pack a load into 25 bits):
+    full parity and a zero range counter; and a one-worker cluster beyond it, where no ordering is involved:
+    the counter reports it on both sides."""
+    G, B, Q = 4, 1024, 256
+    rng = np.random.default_rng(77)
+    cfg = wl.RouteConfig(name="edge25", n_inst=3, G=G, B=B, max_wait=Q, H=0)
+    n = np.array([[1020, 1019, 1021, 1018], [1023, 1023, 1022, 1024], [1000, 1016, 1016, 1010]], np.int32)
+    kv = np.zeros((3, G, B), np.int32)
+    rem = np.zeros((3, G, B), np.int32)
+    used = np.arange(B)[None, None, :] < n[:, :, None]
+    kv[used] = 32768
+    rem[used] = rng.integers(2, 9, size=int(used.sum()))
+    init = wl.InitState(n=n, kv=kv, rem=rem, pred=None)
+    _say("loads just below 2^25")
+    oc, r = br_oracle.OracleCluster(cfg, init), binding.Router(cfg, init)
+    for rnd in range(3):
+        s = rng.integers(20000, 30001, size=(3, Q)).astype(np.int32)
+        arr = wl.Arrivals(count=np.array([40, 7, 256], np.int32), s=s, o=rng.integers(1, 5, size=(3, Q)).astype(np.int32),
+                          id=np.arange(3 * Q, dtype=np.int32).reshape(3, Q), pred=None)
+        ref, out = oc.route_step(arr), r.route_step(arr)
+        compare_outputs(ref, out, cfg, f"edge25 r{rnd}")
+        assert (ref["stats"][:, br_oracle.ST["load_range"]] == 0).all() and ref["stats"][:, br_oracle.ST["spread"]].max() < 1 << 25
+        assert oc.L.max() > (1 << 25) - (1 << 21)      # the case does sit at the edge
+        oc.advance(1), r.advance(1)
+        compare_state(oc, r.state(), cfg, f"edge25 r{rnd}")
+    r.close()
+    _say("one worker beyond 2^25")
+    cfg = wl.RouteConfig(name="edge25b", n_inst=2, G=1, B=B, max_wait=16, H=0)
+    n = np.array([[1000], [10]], np.int32)
+    kv = np.zeros((2, 1, B), np.int32)
+    rem = np.zeros((2, 1, B), np.int32)
+    kv[0, 0, :1000], rem[0, 0, :1000] = 40000, 3
+    kv[1, 0, :10], rem[1, 0, :10] = 500, 3
+    init = wl.InitState(n=n, kv=kv, rem=rem, pred=None)
+    oc, r = br_oracle.OracleCluster(cfg, init), binding.Router(cfg, init)
+    arr = wl.Arrivals(count=np.array([5, 5], np.int32), s=np.full((2, 16), 100, np.int32), o=np.full((2, 16), 2, np.int32),
+                      id=np.arange(32, dtype=np.int32).reshape(2, 16), pred=None)
+    ref, out = oc.route_step(arr), r.route_step(arr)
+    compare_outputs(ref, out, cfg, "edge25b")
+    assert ref["stats"][:, br_oracle.ST["load_range"]].tolist() == [1, 0]
+    ref, out = oc.route_bypass(arr), r.route_bypass(arr)
+    assert np.array_equal(out["stats"], ref["stats"]) and ref["stats"][:, br_oracle.ST["load_range"]].tolist() == [1, 0]
+    compare_state(oc, r.state(), cfg, "edge25b")
+    r.close()
+
+
 def test_advance_many_steps_closed_form():
     """n decode steps in one call equal n single steps of the oracle (requests leave mid-way)."""
     for H in (0, 4):

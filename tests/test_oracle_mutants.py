@@ -54,6 +54,10 @@ MUTANTS = [
     ("envelope not raised after an admission", "    if (R->Lh[g][h] > R->Mh[h]) R->Mh[h] = R->Lh[g][h];\n", ""),
     ("single-request ties to the last", "    if (best < 0 || f > bf) {\n      best = pos;", "    if (best < 0 || f >= bf) {\n      best = pos;"),
     ("imbalance", "return (int64_t)G * M - sum;", "return (int64_t)(G - 1) * M - sum;"),
+    # snapshot reductions
+    ("snapshot best worker ties to the highest index", "if (bg < 0 || f > bgf) {", "if (bg < 0 || f >= bgf) {"),
+    ("snapshot best request: shorter request on equal scores", "(f == bi_f[g] && io->qs[i] > bi_s[g])", "(f == bi_f[g] && io->qs[i] < bi_s[g])"),
+    ("snapshot best request: later arrival on equal scores and lengths", "if (cur < 0 || f > bi_f[g] ||", "if (cur < 0 || f >= bi_f[g] ||"),
     # decode step
     ("leaves one step late", "if (rem <= 0) { /* finished", "if (rem < 0) { /* finished"),
     ("kv does not grow", "io->kv[base + k] = kv + 1;", "io->kv[base + k] = kv;"),

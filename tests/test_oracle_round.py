@@ -94,6 +94,29 @@ def test_snapshot_scores_and_reductions(orc):
     assert out["best_i"][0].tolist() == [1, -1, 2]             # w0: max(-100,-80,-240); w2: max(50,40,60)
 
 
+def test_snapshot_reductions_tie_rules_hand_worked(orc):
+    # Equal snapshot scores.  Per request: the lowest worker index.  Per worker: the longer request, then the
+    # earlier arrival (the rule of argmax_i F_g({i}) in the round: lowest position in the order "longest first,
+    # arrival order among equals").
+    # G=3, loads (40, 40, 100): M = 100, margins (60, 60, 0), one free slot each.
+    cfg = wl.RouteConfig(name="h5", n_inst=1, G=3, B=2, max_wait=8)
+    oc = _mk(orc, cfg, _init([1, 1, 1], [[40], [40], [100]], 2))
+    # waiting 40, 70, 40, 50: on workers 0 and 1 (margin 60): F(40) = 40, F(70) = 70 - 3*10 = 40, F(50) = 50;
+    # on worker 2 (margin 0): F(s) = -2 s: -80, -140, -80, -100
+    out = oc.route_step(_arr([40, 70, 40, 50]))
+    assert out["F"][0, :4].tolist() == [[40, 40, -80], [40, 40, -140], [40, 40, -80], [50, 50, -100]]
+    assert out["best_g"][0, :4].tolist() == [0, 0, 0, 0]        # workers 0 and 1 tie on every request: lowest index
+    assert out["best_i"][0].tolist() == [3, 3, 0]               # worker 2: -80 twice: equal lengths, earlier arrival
+    # without the 50: three requests tie at 40 on workers 0 and 1: the longer one (70, position 1) wins
+    oc = _mk(orc, cfg, _init([1, 1, 1], [[40], [40], [100]], 2))
+    out = oc.route_step(_arr([40, 70, 40]))
+    assert out["best_i"][0].tolist() == [1, 1, 0]
+    # a full worker is no candidate: ties then resolve among the rest
+    oc = _mk(orc, cfg, _init([2, 1, 1], [[20, 20], [40], [100]], 2))
+    out = oc.route_step(_arr([40, 70, 40]))
+    assert out["best_g"][0, :3].tolist() == [1, 1, 1] and out["best_i"][0].tolist() == [-1, 1, 0]
+
+
 # ---- structural invariants over replays -----------------------------------------------
 
 def _replay_cfg(H, **kw):
