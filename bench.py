@@ -412,6 +412,57 @@ def window_run(device, R_max=16, n_inst=1024, steps=4, warmup=1):
                 decisions_per_s=int(st[:, binding.ST["admitted"]].sum()) * steps / elapsed)
 
 
+def quality_run(device, name="c2", steps=2000):
+    """Trace-mean imbalance (max - min load per step, Sec. 6.1) of the comparison policies, BR-0 and BR-H on one
+    replay workload, all through the C ABI on the same synthetic trace; BR-H runs with c_hat = min(remaining
+    steps, H) kept by the caller in the workspace (the paper's "BR-H oracle" configuration).  Per-step statistics
+    stay on the device until the end.  Qualitative comparison: synthetic traces, not the paper's numbers."""
+    import dataclasses
+    import torch
+    from paper_2605_06113_amd import binding, workloads as wl
+    base = wl.config(name, token_watermark=0, token_cap=0)
+    steps = min(steps, base.steps)
+    H = base.H if base.H > 0 else 8
+    flat = dataclasses.replace(base, H=0, pred_mode=0)
+    res = {}
+    for policy in ("random", "rr", "p2c", "jsq", "br0", "brh"):
+        cfg = dataclasses.replace(base, H=H, pred_mode=1) if policy == "brh" else flat
+        tr = wl.arrival_trace(cfg, steps)
+        r = binding.Router(cfg, None, device=device)
+        t = lambda a, dt=np.int32: torch.as_tensor(np.ascontiguousarray(a, dt), device=device)
+        count, s, o, ids = t(tr.count), t(tr.s), t(tr.o), t(tr.id)
+        pred = t(np.minimum(tr.o, H)[..., None], np.float32) if policy == "brh" else None
+        cap = int(tr.s.shape[-1])
+        out = r.alloc_outputs(scores=False)
+        stats_all = torch.zeros((steps, 1, binding.NSTATS), dtype=torch.int64, device=device)
+        lay = r.layout
+        import ctypes as C
+        t0 = time.perf_counter()
+        for k in range(steps):
+            a = binding.Arrivals(count=count[k].data_ptr(), s=s[k].data_ptr(), o=o[k].data_ptr(), id=ids[k].data_ptr(),
+                                 pred=pred[k].data_ptr() if pred is not None else None, arr_cap=cap, pad=0)
+            out["stats"] = stats_all[k]
+            ostruct = r.out_struct(out)
+            if policy in binding.POLICY:
+                rc = r.lib.br_route_baseline(r.ctx, C.byref(a), C.byref(ostruct), binding.POLICY[policy], 5)
+            else:
+                rc = r.lib.br_route_step(r.ctx, C.byref(a), C.byref(ostruct))
+            assert rc == 0
+            r.advance(1)
+            if policy == "brh":
+                r._view(lay.pred, (1, r.G, r.Bs, 1), "f32")[..., 0].copy_(r._view(lay.rem, (1, r.G, r.Bs)).clamp(max=H).float())
+                r._view(lay.qpred, (1, r.Q, 1), "f32")[..., 0].copy_(r._view(lay.qo, (1, r.Q)).clamp(max=H).float())
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        st = stats_all.cpu().numpy()[:, 0]
+        res[policy] = dict(mean_imbalance=float(st[steps // 5:, binding.ST["spread"]].mean()),
+                           admitted=int(st[:, binding.ST["admitted"]].sum()), us_per_step=dt / steps * 1e6)
+        r.close()
+    return dict(workload=f"{name} shape, {steps} decode steps, one instance (G={base.G}, B={base.B}, queue cap {base.max_wait}); "
+                         f"mean over the last four fifths of max - min load after each round; BR-H: H={H}, c_hat = min(remaining, H)",
+                policies=res)
+
+
 def c1_latency(device, reps=200):
     """The single BR-0 round of c1 (one instance, G=4, 32 waiting), repeated on fresh contexts."""
     import torch
@@ -663,6 +714,7 @@ def main():
         res["window16"] = window_run(device)
         res["bypass"] = bypass_run(device, cfg, init, arr)
         res["replay_batched"] = replay_run(device)
+        res["quality"] = quality_run(device)
     if args.latency_steps > 0:
         res["latency"] = latency_run(args.latency_steps, device)
         res["latency_c1"] = c1_latency(device)

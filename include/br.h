@@ -40,7 +40,7 @@ extern "C" {
 #define BR_MAX_RMAX 16
 #define BR_MAX_S 32768
 #define BR_NSTATS 16
-#define BR_NKERNELS 6
+#define BR_NKERNELS 7
 #define BR_STATIC_MAX_INST 16          /* most clusters br_route_step_static serves */
 #define BR_STATIC_SCRATCH_BYTES 1441792 /* device memory the library holds per GPU for it, until the process ends */
 
@@ -80,8 +80,12 @@ enum {
   BR_K_ASSIGN = 2,  /* sequential two-stage assignment */
   BR_K_ADVANCE = 3, /* decode step */
   BR_K_INIT = 4,
-  BR_K_BYPASS = 5   /* pool-bypass dispatch */
+  BR_K_BYPASS = 5,  /* pool-bypass dispatch */
+  BR_K_BASELINE = 6 /* comparison policies */
 };
+
+/* Comparison policies of br_route_baseline (Sec. 6.1, "Baselines"). */
+enum { BR_POLICY_RANDOM = 0, BR_POLICY_RR = 1, BR_POLICY_P2C = 2, BR_POLICY_JSQ = 3 };
 
 typedef struct br_ctx br_ctx; /* opaque; host object owned by the library */
 
@@ -263,6 +267,30 @@ int32_t br_route_step_static(br_ctx *ctx, const br_arrivals *in, const br_step_o
  * considered; stage counters zero).  Other outputs are ignored.
  */
 int32_t br_route_bypass(br_ctx *ctx, const br_arrivals *in, const br_step_out *out);
+
+/*
+ * One dispatch round of a comparison policy (Sec. 6.1 "Baselines": Random, Round-Robin, Power-of-Two-Choices,
+ * Join-Shortest-Queue, the load-balancing policies BalanceRoute is measured against) on the same cluster
+ * state, so that a replay can report the per-step imbalance (BR_ST_SPREAD, the paper's "average imbalance" is its
+ * trace mean) of every policy side by side.  The arrivals join the waiting queue as in br_route_step; then the
+ * waiting requests are taken in arrival order and each is bound to a worker chosen among those with a free slot,
+ * without looking at any length:
+ *   BR_POLICY_RANDOM  uniform over the eligible workers;
+ *   BR_POLICY_RR      the first eligible worker at or after a per-cluster cursor, cyclically; the cursor then
+ *                     stands one past it;
+ *   BR_POLICY_P2C     two distinct eligible workers drawn uniformly, the one holding fewer requests (the first
+ *                     drawn on equal counts); the only eligible worker if there is just one;
+ *   BR_POLICY_JSQ     the eligible worker holding the fewest requests, lowest index on equal counts.
+ * Dispatch stops when every worker is full; the rest keeps waiting in arrival order.  The token watermark is
+ * not applied (these policies are workload-unaware).  Draws are counter-based and reproducible: draw c of
+ * cluster i is SplitMix64 output c of the stream started at seed ^ (i << 32) (output function
+ * z ^= z >> 30, z *= 0xBF58476D1CE4E5B9, z ^= z >> 27, z *= 0x94D049BB133111EB, z ^= z >> 31 on
+ * state = start + (c + 1) * 0x9E3779B97F4A7C15); a 32-bit half u picks index (u * E) >> 32 among E candidates in
+ * ascending worker order, low half first.  Cursor and draw count live in the workspace and persist across calls.
+ * Requires H == 0 (BR_EINVAL otherwise, and for an unknown policy).  out->assign / assign_id / stats as in
+ * br_route_step (stage counters zero); other outputs are ignored.
+ */
+int32_t br_route_baseline(br_ctx *ctx, const br_arrivals *in, const br_step_out *out, int32_t policy, uint64_t seed);
 
 /* Destroy the context (host memory only; the workspace stays the caller's). NULL is allowed. */
 void br_free(br_ctx *ctx);

@@ -723,3 +723,120 @@ int32_t orc_route_bypass(const orc_params *P, orc_io *io) {
   if (io->stats) memcpy(io->stats, st, sizeof st);
   return 0;
 }
+
+/* ------------------------------------------------------ comparison policies */
+
+/* Output c of the SplitMix64 stream started at `key` (published output function and increment). */
+uint64_t orc_hash64(uint64_t key, uint64_t c) {
+  uint64_t z = key + (c + 1) * 0x9E3779B97F4A7C15ULL;
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ULL;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBULL;
+  return z ^ (z >> 31);
+}
+
+/* the k-th eligible worker (free slot) in ascending index order, k counted from 0; `skip`: a worker left out */
+static int kth_eligible(const orc_params *P, const orc_io *io, int k, int skip) {
+  int g;
+  for (g = 0; g < P->G; ++g) {
+    if (io->n[g] >= P->B || g == skip) continue;
+    if (k == 0) return g;
+    --k;
+  }
+  return -1;
+}
+
+/* Sec. 6.1 "Baselines": Random, Round-Robin, Power-of-Two-Choices, Join-Shortest-Queue; see br_oracle.h for
+ * the rules.  Requests leave the waiting queue in arrival order; lengths are never looked at. */
+int32_t orc_route_baseline(const orc_params *P, orc_io *io, int32_t policy, uint64_t seed, int32_t cluster,
+                           int32_t *pol_state) {
+  int G = P->G, g, i;
+  int32_t qlen, space, acc, taken = 0;
+  int64_t st[ORC_NSTATS], L0[ORC_MAX_G];
+  uint64_t key = seed ^ ((uint64_t)(uint32_t)cluster << 32);
+  if (G < 1 || G > ORC_MAX_G || P->H != 0 || policy < 0 || policy > 3 || !pol_state) return -1;
+  memset(st, 0, sizeof st);
+
+  /* arrivals join the waiting queue in arrival order; what does not fit is dropped */
+  qlen = *io->qlen;
+  space = P->max_wait - qlen;
+  acc = io->a_count < space ? io->a_count : space;
+  if (acc < 0) acc = 0;
+  for (i = 0; i < acc; ++i) {
+    io->qs[qlen + i] = clamp_s(io->a_s[i]);
+    io->qo[qlen + i] = io->a_o[i] < 1 ? 1 : io->a_o[i];
+    io->qid[qlen + i] = io->a_id ? io->a_id[i] : i;
+  }
+  st[ORC_ST_DROPPED] = (io->a_count > 0 ? io->a_count : 0) - acc;
+  qlen += acc;
+  st[ORC_ST_QLEN] = qlen;
+  for (i = 0; i < P->max_wait; ++i) {
+    if (io->assign) io->assign[i] = -1;
+    if (io->assign_id) io->assign_id[i] = i < qlen ? io->qid[i] : -1;
+  }
+  for (g = 0; g < G; ++g) L0[g] = io->L[g];
+  st[ORC_ST_I_BEFORE] = imbalance(L0, G);
+
+  for (i = 0; i < qlen; ++i) {
+    int E = 0, pick = -1;
+    for (g = 0; g < G; ++g)
+      if (io->n[g] < P->B) ++E;
+    if (E == 0) break; /* every worker is full: the rest keeps waiting */
+    if (policy == ORC_POLICY_RR) {
+      int k;
+      for (k = 0; k < G; ++k) {
+        g = (pol_state[0] + k) % G;
+        if (io->n[g] < P->B) {
+          pick = g;
+          break;
+        }
+      }
+      pol_state[0] = (pick + 1) % G;
+    } else if (policy == ORC_POLICY_JSQ) {
+      for (g = 0; g < G; ++g)
+        if (io->n[g] < P->B && (pick < 0 || io->n[g] < io->n[pick])) pick = g;
+    } else {
+      uint64_t z = orc_hash64(key, (uint64_t)(uint32_t)pol_state[1]);
+      uint32_t lo = (uint32_t)z, hi = (uint32_t)(z >> 32);
+      int a = kth_eligible(P, io, (int)(((uint64_t)lo * (uint64_t)E) >> 32), -1);
+      pol_state[1] += 1;
+      pick = a;
+      if (policy == ORC_POLICY_P2C && E > 1) {
+        int b = kth_eligible(P, io, (int)(((uint64_t)hi * (uint64_t)(E - 1)) >> 32), a);
+        if (io->n[b] < io->n[a]) pick = b;
+      }
+    }
+    {
+      int64_t slot = (int64_t)pick * P->B + io->n[pick];
+      io->kv[slot] = io->qs[i];
+      io->rem[slot] = io->qo[i];
+      io->n[pick] += 1;
+      io->L[pick] += io->qs[i];
+      if (io->assign) io->assign[i] = pick;
+      ++taken;
+    }
+  }
+  /* the dispatched requests are a prefix of the queue: the rest moves up */
+  for (i = taken; i < qlen; ++i) {
+    io->qs[i - taken] = io->qs[i];
+    io->qo[i - taken] = io->qo[i];
+    io->qid[i - taken] = io->qid[i];
+  }
+  qlen -= taken;
+  *io->qlen = qlen;
+  st[ORC_ST_ADMITTED] = taken;
+  st[ORC_ST_DEFERRED] = qlen;
+  for (g = 0; g < G; ++g) L0[g] = io->L[g];
+  st[ORC_ST_I_AFTER] = imbalance(L0, G);
+  {
+    int64_t mx = L0[0], mn = L0[0];
+    for (g = 0; g < G; ++g) {
+      if (L0[g] > mx) mx = L0[g];
+      if (L0[g] < mn) mn = L0[g];
+      if (P->token_cap > 0 && L0[g] > P->token_cap) st[ORC_ST_OVERCAP] += 1;
+      if (L0[g] >= ((int64_t)1 << 25)) st[ORC_ST_LOAD_RANGE] += 1;
+    }
+    st[ORC_ST_SPREAD] = mx - mn;
+  }
+  if (io->stats) memcpy(io->stats, st, sizeof st);
+  return 0;
+}

@@ -19,6 +19,7 @@
  *   - exhaustive subset search of Stage 2:     Appendix "Bit-set subset selection"
  *   - pool-bypass dispatch:                    Appendix "Pool-bypass deployment path for BR-0"
  *   - empirical-survival estimator, refresh:   Appendix "Estimator realizations", "Refresh logic"
+ *   - comparison policies (Random, RR, P2C, JSQ): Sec. 6.1 "Baselines" names them; their rules are stated below
  *
  * BR-0/BR-H are heuristics without an exactness claim, so the oracle is the
  * algorithm itself, step by step.  Integer quantities are int64; BR-H scores are
@@ -148,6 +149,27 @@ int32_t orc_advance(const orc_params *P, orc_io *io, int32_t n_steps);
  * at a time, in order, on argmax_g F_g(s) over the workers with a free slot; io->assign[a] gets the
  * worker of arrival a, -1 if it had to join the waiting queue, -2 if that was full too. */
 int32_t orc_route_bypass(const orc_params *P, orc_io *io);
+
+/* ---- comparison policies (Sec. 6.1 "Baselines": Random, Round-Robin, Power-of-Two-Choices, Join-Shortest-Queue) ----
+ * Workload-unaware dispatch: waiting requests are taken in arrival order and each goes to a worker chosen among
+ * those with a free slot (eligible workers), without looking at any length:
+ *   ORC_POLICY_RANDOM  uniform over the eligible workers;
+ *   ORC_POLICY_RR      the first eligible worker at or after a cursor, cyclically; the cursor moves one past it;
+ *   ORC_POLICY_P2C     two distinct eligible workers drawn uniformly, the one holding fewer requests (the first
+ *                      drawn on equal counts); the only eligible worker if there is one;
+ *   ORC_POLICY_JSQ     the eligible worker holding the fewest requests, lowest index on equal counts.
+ * Dispatch stops when no worker has a free slot; what is left keeps waiting, in arrival order.
+ * Random draws are counter-based: draw number c of cluster i under `seed` is the SplitMix64 output function
+ * (Steele, Lea, Flood 2014: z = x; z = (z ^ z >> 30) * 0xBF58476D1CE4E5B9; z = (z ^ z >> 27) * 0x94D049BB133111EB;
+ * z ^ z >> 31) applied to x = (seed ^ i << 32) + (c + 1) * 0x9E3779B97F4A7C15, i.e. output c of the SplitMix64
+ * stream started at seed ^ i << 32.  A 32-bit half u picks index (u * E) >> 32 among E candidates in ascending
+ * worker order; P2C uses the low half for the first pick and the high half for the second (among the other
+ * E - 1).  pol_state[0] is the round-robin cursor, pol_state[1] the number of draws made so far; both persist
+ * across calls (in/out). */
+enum { ORC_POLICY_RANDOM = 0, ORC_POLICY_RR = 1, ORC_POLICY_P2C = 2, ORC_POLICY_JSQ = 3 };
+uint64_t orc_hash64(uint64_t key, uint64_t c);
+int32_t orc_route_baseline(const orc_params *P, orc_io *io, int32_t policy, uint64_t seed, int32_t cluster,
+                           int32_t *pol_state);
 
 #ifdef __cplusplus
 }

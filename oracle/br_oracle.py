@@ -82,6 +82,10 @@ def lib():
         for f in (_lib.orc_project, _lib.orc_route_step, _lib.orc_route_bypass):
             f.restype = C.c_int32
             f.argtypes = [C.POINTER(Params), C.POINTER(IO)]
+        _lib.orc_hash64.restype = C.c_uint64
+        _lib.orc_hash64.argtypes = [C.c_uint64, C.c_uint64]
+        _lib.orc_route_baseline.restype = C.c_int32
+        _lib.orc_route_baseline.argtypes = [C.POINTER(Params), C.POINTER(IO), C.c_int32, C.c_uint64, C.c_int32, _P]
         _lib.orc_advance.restype = C.c_int32
         _lib.orc_advance.argtypes = [C.POINTER(Params), C.POINTER(IO), C.c_int32]
     return _lib
@@ -89,6 +93,13 @@ def lib():
 
 def _ptr(a: Optional[np.ndarray]):
     return None if a is None else a.ctypes.data_as(_P)
+
+
+POLICY = dict(random=0, rr=1, p2c=2, jsq=3)
+
+
+def hash64(key: int, c: int) -> int:
+    return int(lib().orc_hash64(key & (2 ** 64 - 1), c))
 
 
 def score_br0(G: int, m: int, delta: int) -> int:
@@ -259,6 +270,29 @@ class OracleCluster:
             io.a_s, io.a_o, io.a_id = _ptr(a_s[i]), _ptr(a_o[i]), _ptr(a_id[i])
             io.assign, io.stats = _ptr(out["assign"][i]), _ptr(out["stats"][i])
             rc = lib().orc_route_bypass(C.byref(self.params), C.byref(io))
+            assert rc == 0, rc
+        return out
+
+    def route_baseline(self, arr, policy: int, seed: int = 0):
+        """One dispatch round of a comparison policy (BR-0 contexts): FIFO over the waiting queue."""
+        N, Q = self.N, self.Q
+        if not hasattr(self, "pol_state"):
+            self.pol_state = np.zeros((N, 2), np.int32)     # round-robin cursor, draws made
+        out = dict(assign=np.full((N, Q), -1, np.int32), assign_id=np.full((N, Q), -1, np.int32),
+                   stats=np.zeros((N, NSTATS), np.int64))
+        if arr is not None:
+            a_s = np.ascontiguousarray(arr.s, np.int32)
+            a_o = np.ascontiguousarray(arr.o, np.int32)
+            a_id = np.ascontiguousarray(arr.id, np.int32)
+        for i in range(N):
+            io = self._io(i)
+            if arr is not None:
+                io.a_count = int(arr.count[i])
+                io.a_s, io.a_o, io.a_id = _ptr(a_s[i]), _ptr(a_o[i]), _ptr(a_id[i])
+            io.assign, io.assign_id, io.stats = (_ptr(out["assign"][i]), _ptr(out["assign_id"][i]),
+                                                 _ptr(out["stats"][i]))
+            rc = lib().orc_route_baseline(C.byref(self.params), C.byref(io), int(policy), int(seed) & (2 ** 64 - 1), i,
+                                          _ptr(self.pol_state[i]))
             assert rc == 0, rc
         return out
 

@@ -17,13 +17,14 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libbr_hip.so")
 
 NSTATS = 16
-NKERNELS = 6
-KERNEL_NAMES = ("project", "score", "assign", "advance", "init", "bypass")
+NKERNELS = 7
+KERNEL_NAMES = ("project", "score", "assign", "advance", "init", "bypass", "baseline")
+POLICY = dict(random=0, rr=1, p2c=2, jsq=3)
 ST = dict(admitted=0, deferred=1, dropped=2, stage1=3, stage2_pops=4, guard=5, overcap=6,
           I_before=7, I_after=8, spread=9, qlen=10, workers_dropped=11, load_range=12)
 BR_OK, BR_EINVAL, BR_ENOMEM, BR_EHIP, BR_ELIMIT = 0, -1, -2, -3, -4
 
-EXPORTS = ("br_workspace_bytes", "br_init", "br_route_step", "br_route_step_static", "br_route_advance", "br_route_bypass", "br_advance_decode", "br_free",
+EXPORTS = ("br_workspace_bytes", "br_init", "br_route_step", "br_route_step_static", "br_route_advance", "br_route_bypass", "br_route_baseline", "br_advance_decode", "br_free",
            "br_last_hip_error", "br_get_layout", "br_profile_enable", "br_profile_read")
 
 _P = C.c_void_p
@@ -82,6 +83,8 @@ def load():
     lib.br_route_advance.argtypes = [_P, C.POINTER(Arrivals), C.POINTER(StepOut), C.c_int32]
     lib.br_route_bypass.restype = C.c_int32
     lib.br_route_bypass.argtypes = [_P, C.POINTER(Arrivals), C.POINTER(StepOut)]
+    lib.br_route_baseline.restype = C.c_int32
+    lib.br_route_baseline.argtypes = [_P, C.POINTER(Arrivals), C.POINTER(StepOut), C.c_int32, C.c_uint64]
     lib.br_advance_decode.restype = C.c_int32
     lib.br_advance_decode.argtypes = [_P, C.c_int32]
     lib.br_free.restype = None
@@ -271,6 +274,21 @@ class Router:
         out = dict(assign=torch.full((self.N, darr.arr_cap), -3, dtype=torch.int32, device=self.device),
                    stats=torch.zeros((self.N, NSTATS), dtype=torch.int64, device=self.device))
         self.route_bypass_device(darr, out)
+        self.stream.synchronize()
+        return {k: v.cpu().numpy() for k, v in out.items()}
+
+    def route_baseline_device(self, darr: Optional[DeviceArrivals], out, policy: int, seed: int = 0) -> None:
+        """Enqueue one dispatch round of a comparison policy (BR-0 contexts); no synchronisation."""
+        a = darr.struct() if darr is not None else None
+        o = self.out_struct(out)
+        _check(self.lib.br_route_baseline(self.ctx, C.byref(a) if a is not None else None, C.byref(o), int(policy),
+                                          int(seed) & (2 ** 64 - 1)), "br_route_baseline", self.ctx)
+
+    def route_baseline(self, arr, policy: int, seed: int = 0):
+        """Convenience for tests: host arrays in, numpy out (synchronises)."""
+        darr = DeviceArrivals(arr, self.device, 0) if arr is not None else None
+        out = self.alloc_outputs(scores=False)
+        self.route_baseline_device(darr, out, policy, seed)
         self.stream.synchronize()
         return {k: v.cpu().numpy() for k, v in out.items()}
 

@@ -45,7 +45,8 @@ bool config_ok(const br_config *c) {
 
 // `dl`: byte offset of the discount table that horizons beyond BR_HP keep in the workspace (after the
 // arrays of the public layout), or 0
-void make_layout(const br_config &c, br_layout *l, uint64_t *dl = nullptr, uint64_t *score_scratch = nullptr) {
+void make_layout(const br_config &c, br_layout *l, uint64_t *dl = nullptr, uint64_t *score_scratch = nullptr,
+                 uint64_t *pol = nullptr) {
   const uint64_t N = (uint64_t)c.n_inst, G = (uint64_t)c.G, Q = (uint64_t)c.max_wait, H1 = (uint64_t)c.H + 1;
   const uint64_t P = (uint64_t)pred_width(c), Pq = (uint64_t)queue_pred_width(c);
   const uint64_t Bs = ((uint64_t)c.B + 3u) & ~(uint64_t)3u;
@@ -74,6 +75,8 @@ void make_layout(const br_config &c, br_layout *l, uint64_t *dl = nullptr, uint6
   const uint64_t ss_bytes = br_score_scratch_bytes(c.n_inst, c.max_wait, c.G);
   const uint64_t ss_at = ss_bytes ? take(ss_bytes / 4) : 0;  // partial results of the tiled score path (private)
   if (score_scratch) *score_scratch = ss_at;
+  const uint64_t pol_at = take(2 * N);  // comparison policies: round-robin cursor and draw count per cluster (private)
+  if (pol) *pol = pol_at;
   l->total_bytes = off;
   l->B_stride = (int32_t)Bs;
   l->P = (int32_t)P;
@@ -88,6 +91,7 @@ struct br_ctx {
   br_layout lay;
   BrParams p;
   int *score_scratch;
+  int *pol;                // [N][2] state of the comparison policies
   int *static_scratch;     // the library's fixed scratch array on this context's device (br_route_step_static), or null
   int32_t static_hip;      // why it is null: the hipError_t of the failed look-up
   hipStream_t st;
@@ -165,8 +169,8 @@ int32_t br_init(const br_config *cfg, const br_init_state *init, br_ctx **out) {
   if (!out || !config_ok(cfg) || !cfg->workspace) return BR_EINVAL;
   if (((uintptr_t)cfg->workspace & 255u) != 0) return BR_EINVAL;
   br_layout l;
-  uint64_t dl_at = 0, ss_at = 0;
-  make_layout(*cfg, &l, &dl_at, &ss_at);
+  uint64_t dl_at = 0, ss_at = 0, pol_at = 0;
+  make_layout(*cfg, &l, &dl_at, &ss_at, &pol_at);
   if (cfg->workspace_bytes < l.total_bytes) return BR_ENOMEM;
   const int P = pred_width(*cfg);
   if (init && (!init->n || !init->kv || !init->rem || (P > 0 && !init->pred))) return BR_EINVAL;
@@ -233,12 +237,13 @@ int32_t br_init(const br_config *cfg, const br_init_state *init, br_ctx **out) {
   p.minm = (int32_t *)(base + l.minm);
   p.dl = dl_at ? (const float *)(base + dl_at) : nullptr;
   ctx->score_scratch = ss_at ? (int *)(base + ss_at) : nullptr;
+  ctx->pol = (int *)(base + pol_at);
   // set-up of the allocation-free entry point: the device address of the fixed scratch array, looked up once per
   // device with the context's device current (the caller's, as for every launch on its stream)
   ctx->static_scratch = nullptr;
   ctx->static_hip = (int32_t)br_static_scratch_resolve(&ctx->static_scratch);
 
-  int32_t rc = enqueue(ctx, BR_K_INIT, [&] { br_launch_clear(p, ctx->st); });
+  int32_t rc = enqueue(ctx, BR_K_INIT, [&] { br_launch_clear(p, ctx->pol, ctx->st); });
   if (rc == BR_OK && p.dl) rc = enqueue(ctx, BR_K_INIT, [&] { br_launch_discounts(p, cfg->gamma, ctx->st); });
   if (rc == BR_OK && init)
     rc = enqueue(ctx, BR_K_INIT, [&] { br_launch_load_init(p, init->n, init->kv, init->rem, init->pred, ctx->st); });
@@ -338,6 +343,27 @@ int32_t br_route_bypass(br_ctx *ctx, const br_arrivals *in, const br_step_out *o
     o.stats = (long long *)out->stats;
   }
   return enqueue(ctx, BR_K_BYPASS, [&] { br_launch_bypass(ctx->p, a, o, ctx->st); });
+}
+
+int32_t br_route_baseline(br_ctx *ctx, const br_arrivals *in, const br_step_out *out, int32_t policy, uint64_t seed) {
+  if (!ctx || ctx->p.H != 0 || policy < BR_POLICY_RANDOM || policy > BR_POLICY_JSQ) return BR_EINVAL;
+  if (in && in->arr_cap < 0) return BR_EINVAL;
+  BrArr a{};
+  if (in && in->count && in->arr_cap > 0) {
+    if (!in->s || !in->o) return BR_EINVAL;
+    a.count = in->count;
+    a.s = in->s;
+    a.o = in->o;
+    a.id = in->id;
+    a.arr_cap = in->arr_cap;
+  }
+  BrOut o{};
+  if (out) {
+    o.assign = out->assign;
+    o.assign_id = out->assign_id;
+    o.stats = (long long *)out->stats;
+  }
+  return enqueue(ctx, BR_K_BASELINE, [&] { br_launch_baseline(ctx->p, a, o, ctx->pol, policy, (unsigned long long)seed, ctx->st); });
 }
 
 int32_t br_advance_decode(br_ctx *ctx, int32_t n_steps) {

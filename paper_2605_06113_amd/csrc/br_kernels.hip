@@ -8,14 +8,18 @@
 
 // ------------------------------------------------------------------ initialisation
 
-__global__ void br_k_clear(BrParams p) {
+__global__ void br_k_clear(BrParams p, int *pol) {
   const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int64_t rows = (int64_t)p.N * p.G;
   if (tid < rows) {
     p.L[tid] = 0;
     p.n[tid] = 0;
   }
-  if (tid < p.N) p.qlen[tid] = 0;
+  if (tid < p.N) {
+    p.qlen[tid] = 0;
+    pol[2 * tid] = 0;
+    pol[2 * tid + 1] = 0;
+  }
 }
 
 // One wave per (cluster, worker): copy the caller's dense active list into the workspace
@@ -616,9 +620,9 @@ __global__ __launch_bounds__(256) void br_k_score_wave(BrParams p, BrArr a, BrOu
 
 // ------------------------------------------------------------------ launchers
 
-void br_launch_clear(const BrParams &p, hipStream_t st) {
+void br_launch_clear(const BrParams &p, int *pol, hipStream_t st) {
   const int64_t n = (int64_t)p.N * p.G;
-  hipLaunchKernelGGL(br_k_clear, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p);
+  hipLaunchKernelGGL(br_k_clear, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p, pol);
 }
 
 void br_launch_load_init(const BrParams &p, const int32_t *n, const int32_t *kv, const int32_t *rem, const float *pred,

@@ -5,7 +5,8 @@
 
 #include "br_device.h"
 
-void br_launch_clear(const BrParams &p, hipStream_t st);
+// `pol`: per-cluster state of the comparison policies (round-robin cursor, draws made), [N][2]
+void br_launch_clear(const BrParams &p, int *pol, hipStream_t st);
 void br_launch_load_init(const BrParams &p, const int32_t *n, const int32_t *kv, const int32_t *rem, const float *pred,
                          hipStream_t st);
 void br_launch_advance(const BrParams &p, int t, hipStream_t st);
@@ -30,3 +31,6 @@ void br_launch_route4(const BrParams &p, const BrArr &a, const BrOut &o, hipStre
 // BR-H (H <= BR_HP), Q <= 512: the same in one launch per four clusters
 void br_launch_route_h(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st);
 void br_launch_bypass(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st);
+// comparison policies (Random, RR, P2C, JSQ): FIFO dispatch of the waiting queue, BR-0 contexts
+void br_launch_baseline(const BrParams &p, const BrArr &a, const BrOut &o, int *pol, int policy, unsigned long long seed,
+                        hipStream_t st);

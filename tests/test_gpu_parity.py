@@ -373,7 +373,7 @@ def test_loads_at_the_edge_of_the_key_range():
     G, B, Q = 4, 1024, 256
     rng = np.random.default_rng(77)
     cfg = wl.RouteConfig(name="edge25", n_inst=3, G=G, B=B, max_wait=Q, H=0)
-    n = np.array([[1020, 1019, 1021, 1018], [1023, 1023, 1022, 1024], [1000, 1016, 1016, 1010]], np.int32)
+    n = np.array([[1020, 1019, 1021, 1018], [1023, 1023, 1022, 1023], [1000, 1016, 1016, 1010]], np.int32)
     kv = np.zeros((3, G, B), np.int32)
     rem = np.zeros((3, G, B), np.int32)
     used = np.arange(B)[None, None, :] < n[:, :, None]

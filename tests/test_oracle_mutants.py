@@ -15,7 +15,7 @@ import pytest
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 SRC = os.path.join(ROOT, "oracle", "br_oracle.c")
 PIN_FILES = ["tests/test_oracle_scores.py", "tests/test_oracle_round.py", "tests/test_oracle_bypass.py",
-             "tests/test_oracle_survival.py"]
+             "tests/test_oracle_survival.py", "tests/test_oracle_baselines.py"]
 
 MUTANTS = [
     # eq. (br0-Fscore)
@@ -67,6 +67,17 @@ MUTANTS = [
     ("window one short", "hi = hist_rank(P, age + P->H);", "hi = hist_rank(P, age + P->H - 1);"),
     ("no decrement between refreshes", "c = c - 1.0f;\n            if (c < 1.0f) {", "if (c < 1.0f) {"),
     ("refresh one token late", "if ((int64_t)since >= P->refresh) {", "if ((int64_t)since > P->refresh) {"),
+    # comparison policies
+    ("generator: wrong shift", "z = (z ^ (z >> 27)) * 0x94D049BB133111EBULL;", "z = (z ^ (z >> 28)) * 0x94D049BB133111EBULL;"),
+    ("generator: counter starts at zero", "uint64_t z = key + (c + 1) * 0x9E3779B97F4A7C15ULL;", "uint64_t z = key + c * 0x9E3779B97F4A7C15ULL;"),
+    ("round robin: cursor stays on the chosen worker", "pol_state[0] = (pick + 1) % G;", "pol_state[0] = pick % G;"),
+    ("jsq takes the fullest", "(pick < 0 || io->n[g] < io->n[pick])) pick = g;", "(pick < 0 || io->n[g] > io->n[pick])) pick = g;"),
+    ("jsq ties to the highest index", "(pick < 0 || io->n[g] < io->n[pick])) pick = g;", "(pick < 0 || io->n[g] <= io->n[pick])) pick = g;"),
+    ("p2c keeps the fuller", "if (io->n[b] < io->n[a]) pick = b;", "if (io->n[b] > io->n[a]) pick = b;"),
+    ("p2c second pick may repeat the first", "(E - 1)) >> 32), a);", "(E - 1)) >> 32), -1);"),
+    ("p2c uses the same half twice", "uint32_t lo = (uint32_t)z, hi = (uint32_t)(z >> 32);", "uint32_t lo = (uint32_t)z, hi = (uint32_t)z;"),
+    ("policies ignore the slot limit", "    if (E == 0) break; /* every worker is full: the rest keeps waiting */\n", ""),
+    ("random pick ignores full workers' absence", "int a = kth_eligible(P, io, (int)(((uint64_t)lo * (uint64_t)E) >> 32), -1);", "int a = (int)(((uint64_t)lo * (uint64_t)G) >> 32);"),
     # pool bypass
     ("bypass ignores the slot limit", "      if (io->n[g] >= P->B) continue;\n", ""),
     ("bypass scores against the stale load", "      io->L[best] += s;\n", ""),
