@@ -377,13 +377,14 @@ def bypass_run(device, cfg, init, arr, steps=6, warmup=2):
                 pairs_per_s=int(st[:, binding.ST["qlen"]].sum()) * cfg.G * steps / elapsed)
 
 
-def window_run(device, R_max=16, n_inst=1024, steps=4, warmup=1):
-    """Stage 2 with a wide candidate window: the c4 cluster shape with R_max = 16 and S_greedy = 64 as in the
-    main workload, so the last 64 free slots of a cluster (4 per worker) are filled by pops that search the
-    subsets of at most 4 out of 16 requests."""
+def window_run(device, R_max=16, n_inst=1024, steps=4, warmup=1, S_greedy=64):
+    """Stage 2 with a wide candidate window: the c4 cluster shape with R_max = 16 (every subset mask) or 32 (the
+    reachable sums of Appendix "Bit-set subset selection"); with S_greedy = 64 as in the main workload the last 64
+    free slots of a cluster (4 per worker) are filled by pops that search subsets of at most 4 requests of the
+    window, with S_greedy = 512 every admission goes through Stage 2 (up to 16 requests per pop)."""
     import torch
     from paper_2605_06113_amd import binding, workloads as wl
-    cfg = wl.config("c4", n_inst=n_inst, R_max=R_max, S_greedy=64)
+    cfg = wl.config("c4", n_inst=n_inst, R_max=R_max, S_greedy=S_greedy)
     init, arr = wl.initial_state(cfg), wl.initial_waiting(cfg)
     routers = [binding.Router(cfg, init, device=device) for _ in range(steps + warmup)]
     darr = binding.DeviceArrivals(arr, device, 0)
@@ -407,7 +408,7 @@ def window_run(device, R_max=16, n_inst=1024, steps=4, warmup=1):
     for r in routers:
         r.close()
     pops, guard = int(st[:, binding.ST["stage2_pops"]].sum()), int(st[:, binding.ST["guard"]].sum())
-    return dict(workload=f"{n_inst} clusters of the c4 shape with R_max={R_max}, S_greedy=64: round + decode step",
+    return dict(workload=f"{n_inst} clusters of the c4 shape with R_max={R_max}, S_greedy={S_greedy}: round + decode step",
                 ms_per_step=elapsed / steps * 1e3, assign_kernel_ms=ms / max(cnt, 1), stage2_pops=pops, guard_pops=guard,
                 decisions_per_s=int(st[:, binding.ST["admitted"]].sum()) * steps / elapsed)
 
@@ -712,6 +713,8 @@ def main():
         res["brh_batched_gate_off"] = brh_run(device, gate=0.0)   # hazards live: no request counts at the last offset
         res["brh_batched_h80"] = brh_run(device, deployed=True)
         res["window16"] = window_run(device)
+        res["window32"] = window_run(device, R_max=32)                       # reachable sums instead of masks
+        res["window32_all_stage2"] = window_run(device, R_max=32, S_greedy=512)
         res["bypass"] = bypass_run(device, cfg, init, arr)
         res["replay_batched"] = replay_run(device)
         res["quality"] = quality_run(device)

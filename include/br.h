@@ -21,7 +21,7 @@
  *    nothing aborts.  Data-dependent conditions (a full waiting queue, a worker that
  *    can take nothing) are not errors: they are counted in the stats block.
  *  - Limits: G <= 64, B <= 1024, max_wait <= 2048, H <= 128 (H <= 8 with pred_mode 0),
- *    R_max <= 16, prefill length in [1, 32768] (values outside are clamped on arrival),
+ *    R_max <= 32 (R_max <= 16 when H > 8), prefill length in [1, 32768] (values outside are clamped on arrival),
  *    per-worker load < 2^25.
  */
 #ifndef BR_H
@@ -37,7 +37,8 @@ extern "C" {
 #define BR_MAX_B 1024
 #define BR_MAX_WAIT 2048
 #define BR_MAX_H 128
-#define BR_MAX_RMAX 16
+#define BR_MAX_RMAX 32
+#define BR_DP_MAX_SUM 131071 /* windows beyond 16 requests: largest total prefill length a Stage-2 subset may have */
 #define BR_MAX_S 32768
 #define BR_NSTATS 16
 #define BR_NKERNELS 7
@@ -101,8 +102,12 @@ typedef struct {
                               per-offset state moves from registers to on-chip memory (same results,
                               other kernels) and pred_mode must not be 0 */
   int32_t S_greedy;        /* Stage 1 runs while total free slots > S_greedy; >= 0 */
-  int32_t R_max;           /* Stage-2 candidate window and subset size, 1..16; every
-                              subset of the window is searched, exactly */
+  int32_t R_max;           /* Stage-2 candidate window and subset size, 1..32 (1..16 when H > 8).  The search is exact:
+                              windows of up to 16 requests scan every subset; wider ones (Appendix "Bit-set subset
+                              selection") score every sum reachable with the allowed number of requests, up to
+                              BR_DP_MAX_SUM tokens (subsets with a larger total are not candidates), and return the
+                              same subset the scan would: best score, lowest mask in window order.  R_max > 16 adds
+                              16 KB + 144 KB x min(B, R_max) of workspace per cluster (br_workspace_bytes says) */
   int32_t token_watermark; /* 0 = off; else a request is admissible on g only if L_g + s <= watermark */
   int32_t token_cap;       /* 0 = off; reporting only (BR_ST_OVERCAP) */
   int32_t pred_mode;       /* H > 0: 0 = per-step termination hazards p[1..H] per request,

@@ -269,6 +269,75 @@ int32_t orc_best_subset(const orc_params *P, const int64_t *m_g, int64_t L_g, in
   return best_subset(P, &S, m_g, L_g, cap_g, win_s, w, best_score);
 }
 
+/* Appendix "Bit-set subset selection", "Reduction to reachable sums": F_g(Q) depends on Q only through
+ * Delta_s(Q), so it suffices to know, for the cardinality limit k, which sums are reachable with at most k
+ * requests of the window, to score each of them once and to recover a subset for the best one.  The table is the
+ * 0/1-knapsack recurrence over the window in mask-bit order (entry [j][sum] is filled from [j-1][sum - s_b], j
+ * descending so that request b is used at most once); instead of a reachable bit an entry holds the lowest mask
+ * that attains it: a subset that uses request b has a higher mask than any subset of the requests before b, so an
+ * entry, once filled, already holds its lowest mask, and a new entry takes the lowest mask of its predecessor
+ * plus bit b.  Equal best scores resolve to the lowest mask, as in the scan over all masks. */
+static int32_t best_subset_reach(const orc_params *P, const scorer *S, const int64_t *m_g, int64_t L_g,
+                                 int64_t cap_g, const int32_t *win_s, int32_t w, double *best_score) {
+  int64_t kmax = cap_g < P->R_max ? cap_g : P->R_max;
+  int64_t top = 0, sum, j;
+  int64_t *tab; /* [kmax + 1][top + 1]: lowest mask of a subset with at most j requests and that sum, -1 = none */
+  int32_t best = 0;
+  double bs = 0.0;
+  int b;
+  if (kmax > w) kmax = w;
+  if (kmax < 1) {
+    if (best_score) *best_score = 0.0;
+    return 0;
+  }
+  { /* no subset of at most kmax requests sums to more than the kmax longest ones: the table ends there */
+    uint8_t used[ORC_MAX_RMAX];
+    memset(used, 0, sizeof used);
+    for (j = 0; j < kmax; ++j) {
+      int pick = -1;
+      for (b = 0; b < w; ++b)
+        if (!used[b] && (pick < 0 || win_s[b] > win_s[pick])) pick = b;
+      used[pick] = 1;
+      top += win_s[pick];
+    }
+  }
+  if (top > ORC_DP_MAX_SUM) top = ORC_DP_MAX_SUM;
+  tab = (int64_t *)malloc(sizeof(int64_t) * (size_t)(kmax + 1) * (size_t)(top + 1));
+  for (j = 0; j <= kmax; ++j) {
+    for (sum = 0; sum <= top; ++sum) tab[j * (top + 1) + sum] = -1;
+    tab[j * (top + 1)] = 0; /* the empty subset */
+  }
+  for (b = 0; b < w; ++b) {
+    int64_t s = win_s[b];
+    for (j = kmax; j >= 1; --j)
+      for (sum = top; sum >= s; --sum) {
+        int64_t from = tab[(j - 1) * (top + 1) + (sum - s)];
+        if (from >= 0 && tab[j * (top + 1) + sum] < 0) tab[j * (top + 1) + sum] = from | ((int64_t)1 << b);
+      }
+  }
+  for (sum = 1; sum <= top; ++sum) {
+    int64_t mask = tab[kmax * (top + 1) + sum];
+    double f;
+    if (mask < 0) continue;
+    if (P->token_watermark > 0 && L_g + sum > P->token_watermark) continue;
+    f = score(S, m_g, sum);
+    if (best == 0 || f > bs || (f == bs && mask < (int64_t)(uint32_t)best)) {
+      best = (int32_t)(uint32_t)mask;
+      bs = f;
+    }
+  }
+  free(tab);
+  if (best_score) *best_score = bs;
+  return best;
+}
+
+int32_t orc_best_subset_reach(const orc_params *P, const int64_t *m_g, int64_t L_g, int32_t cap_g,
+                              const int32_t *win_s, int32_t w, double *best_score) {
+  scorer S;
+  scorer_init(&S, P, P->force_float);
+  return best_subset_reach(P, &S, m_g, L_g, cap_g, win_s, w, best_score);
+}
+
 /* ---------------------------------------------------------------- a round */
 
 typedef struct {
@@ -528,7 +597,10 @@ int32_t orc_route_step(const orc_params *P, orc_io *io) {
           win_pos[w] = pos;
           ++w;
         }
-      mask = best_subset(P, &R.S, R.m[bw], R.L[bw], R.cap[bw], win_s, w, &f);
+      if (w <= ORC_ENUM_RMAX)
+        mask = best_subset(P, &R.S, R.m[bw], R.L[bw], R.cap[bw], win_s, w, &f);
+      else
+        mask = best_subset_reach(P, &R.S, R.m[bw], R.L[bw], R.cap[bw], win_s, w, &f);
       if (mask == 0 || f <= 0.0) { /* starvation guard: single best request anyway */
         T.guard += 1;
         pos = best_single(&T, bw, &f);
@@ -543,7 +615,7 @@ int32_t orc_route_step(const orc_params *P, orc_io *io) {
         int64_t delta = 0;
         int cnt = 0;
         for (b = 0; b < w; ++b)
-          if (mask & (1 << b)) {
+          if ((uint32_t)mask & ((uint32_t)1 << b)) {
             bind(&T, win_pos[b], bw);
             delta += win_s[b];
             ++cnt;

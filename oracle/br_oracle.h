@@ -16,7 +16,8 @@
  *   - in-window contribution, projected loads: Appendix "Short-horizon prediction
  *     interface", eqs. (two-stage), (composite), (wprofile-new); gate and floor from
  *     Appendix "Refresh logic"
- *   - exhaustive subset search of Stage 2:     Appendix "Bit-set subset selection"
+ *   - subset search of Stage 2:                Appendix "Bit-set subset selection" (every mask for windows of up
+ *     to 16 requests; the optimum over reachable sums for wider ones)
  *   - pool-bypass dispatch:                    Appendix "Pool-bypass deployment path for BR-0"
  *   - empirical-survival estimator, refresh:   Appendix "Estimator realizations", "Refresh logic"
  *   - comparison policies (Random, RR, P2C, JSQ): Sec. 6.1 "Baselines" names them; their rules are stated below
@@ -30,7 +31,8 @@
  * discounted-imbalance identity of the horizon score; survival-sum == two-stage
  * composite; eq. (composite) on a supplied (p_fin, mu_rem) against fp64 and at its corners;
  * subset enumeration == best over reachable sums (for windows of up to 16 requests the sums are
- * built by the shift-OR recurrence of Appendix "Bit-set subset selection"); structural invariants
+ * built by the shift-OR recurrence of Appendix "Bit-set subset selection"); the reachable-sum search of wide
+ * windows == the scan of all masks wherever both apply, == brute force over all masks of 20-request windows; structural invariants
  * of a round (sticky, disjoint, slot limit, load conservation, work conservation,
  * telescoping of the imbalance); brute force over all assignments on tiny instances.
  *
@@ -49,7 +51,9 @@ extern "C" {
 
 #define ORC_MAX_G 64
 #define ORC_MAX_H 128
-#define ORC_MAX_RMAX 16
+#define ORC_MAX_RMAX 32
+#define ORC_ENUM_RMAX 16     /* windows up to here: every subset mask is scanned; beyond: reachable sums */
+#define ORC_DP_MAX_SUM 131071 /* windows beyond ORC_ENUM_RMAX: the table of reachable sums ends here */
 #define ORC_NSTATS 16
 #define ORC_MAX_S 32768
 
@@ -141,6 +145,13 @@ float orc_survival(const orc_params *P, int64_t age);
 /* Stage-2 subset search on an explicit window; returns the chosen mask (0 = none feasible) */
 int32_t orc_best_subset(const orc_params *P, const int64_t *m_g, int64_t L_g, int32_t cap_g,
                         const int32_t *win_s, int32_t w, double *best_score);
+/* The same search by the reduction of Appendix "Bit-set subset selection": the score of a subset depends on its
+ * sum only, so the optimum is the best score over the sums reachable with 1..k requests of the window; among the
+ * subsets that attain it the lowest mask is returned, as by the scan of all masks.  Subsets whose sum exceeds
+ * ORC_DP_MAX_SUM are not candidates (the table of reachable sums is sized by that bound).  Any window size up to
+ * ORC_MAX_RMAX; the round uses it for windows beyond ORC_ENUM_RMAX. */
+int32_t orc_best_subset_reach(const orc_params *P, const int64_t *m_g, int64_t L_g, int32_t cap_g,
+                              const int32_t *win_s, int32_t w, double *best_score);
 
 int32_t orc_project(const orc_params *P, orc_io *io);
 int32_t orc_route_step(const orc_params *P, orc_io *io);

@@ -79,6 +79,8 @@ def lib():
         _lib.orc_best_subset.restype = C.c_int32
         _lib.orc_best_subset.argtypes = [C.POINTER(Params), _P, C.c_int64, C.c_int32, _P, C.c_int32,
                                          C.POINTER(C.c_double)]
+        _lib.orc_best_subset_reach.restype = C.c_int32
+        _lib.orc_best_subset_reach.argtypes = _lib.orc_best_subset.argtypes
         for f in (_lib.orc_project, _lib.orc_route_step, _lib.orc_route_bypass):
             f.restype = C.c_int32
             f.argtypes = [C.POINTER(Params), C.POINTER(IO)]
@@ -147,6 +149,16 @@ def best_subset(params: Params, m_g, L_g: int, cap_g: int, win_s):
     mask = lib().orc_best_subset(C.byref(params), _ptr(mm), int(L_g), int(cap_g), _ptr(ws), len(ws),
                                  C.byref(f))
     return int(mask), float(f.value)
+
+
+def best_subset_reach(params: Params, m_g, L_g: int, cap_g: int, win_s):
+    """The subset search by reachable sums (any window up to 32 requests); mask as an unsigned 32-bit value."""
+    mm = np.ascontiguousarray(m_g, np.int64)
+    ws = np.ascontiguousarray(win_s, np.int32)
+    f = C.c_double(0.0)
+    mask = lib().orc_best_subset_reach(C.byref(params), _ptr(mm), int(L_g), int(cap_g), _ptr(ws), len(ws),
+                                       C.byref(f))
+    return int(mask) & 0xFFFFFFFF, float(f.value)
 
 
 class OracleCluster:

@@ -8,6 +8,7 @@
 #include "br.h"
 #include "br_device.h"
 #include "br_launch.h"
+#include "br_subset_dp.h"
 
 namespace {
 
@@ -33,6 +34,7 @@ bool config_ok(const br_config *c) {
   if (c->token_watermark < 0 || c->token_cap < 0) return false;
   if (c->pred_mode < 0 || c->pred_mode > 3) return false;
   if (c->H > BR_HP && c->pred_mode == 0) return false;  // a hazard per offset is carried for short horizons only
+  if (c->H > BR_HP && c->R_max > 16) return false;      // the search by reachable sums serves the register-horizon kernels
   if (c->pred_mode == 2) {
     if (c->H == 0 || !c->hist || !c->hist_sum || c->hist_n < 1 || c->hist_n > (1 << 20) || c->refresh_period < 1)
       return false;
@@ -46,7 +48,7 @@ bool config_ok(const br_config *c) {
 // `dl`: byte offset of the discount table that horizons beyond BR_HP keep in the workspace (after the
 // arrays of the public layout), or 0
 void make_layout(const br_config &c, br_layout *l, uint64_t *dl = nullptr, uint64_t *score_scratch = nullptr,
-                 uint64_t *pol = nullptr) {
+                 uint64_t *pol = nullptr, uint64_t *dp = nullptr) {
   const uint64_t N = (uint64_t)c.n_inst, G = (uint64_t)c.G, Q = (uint64_t)c.max_wait, H1 = (uint64_t)c.H + 1;
   const uint64_t P = (uint64_t)pred_width(c), Pq = (uint64_t)queue_pred_width(c);
   const uint64_t Bs = ((uint64_t)c.B + 3u) & ~(uint64_t)3u;
@@ -77,6 +79,9 @@ void make_layout(const br_config &c, br_layout *l, uint64_t *dl = nullptr, uint6
   if (score_scratch) *score_scratch = ss_at;
   const uint64_t pol_at = take(2 * N);  // comparison policies: round-robin cursor and draw count per cluster (private)
   if (pol) *pol = pol_at;
+  // windows beyond 16 requests: bit rows and first-request table of the subset search, per cluster (private)
+  const uint64_t dp_at = c.R_max > 16 ? take(N * (uint64_t)br_dp_cluster_words(c.B < c.R_max ? c.B : c.R_max)) : 0;
+  if (dp) *dp = dp_at;
   l->total_bytes = off;
   l->B_stride = (int32_t)Bs;
   l->P = (int32_t)P;
@@ -169,8 +174,8 @@ int32_t br_init(const br_config *cfg, const br_init_state *init, br_ctx **out) {
   if (!out || !config_ok(cfg) || !cfg->workspace) return BR_EINVAL;
   if (((uintptr_t)cfg->workspace & 255u) != 0) return BR_EINVAL;
   br_layout l;
-  uint64_t dl_at = 0, ss_at = 0, pol_at = 0;
-  make_layout(*cfg, &l, &dl_at, &ss_at, &pol_at);
+  uint64_t dl_at = 0, ss_at = 0, pol_at = 0, dp_at = 0;
+  make_layout(*cfg, &l, &dl_at, &ss_at, &pol_at, &dp_at);
   if (cfg->workspace_bytes < l.total_bytes) return BR_ENOMEM;
   const int P = pred_width(*cfg);
   if (init && (!init->n || !init->kv || !init->rem || (P > 0 && !init->pred))) return BR_EINVAL;
@@ -236,6 +241,7 @@ int32_t br_init(const br_config *cfg, const br_init_state *init, br_ctx **out) {
   p.mh = (int32_t *)(base + l.mh);
   p.minm = (int32_t *)(base + l.minm);
   p.dl = dl_at ? (const float *)(base + dl_at) : nullptr;
+  p.dp = dp_at ? (int32_t *)(base + dp_at) : nullptr;
   ctx->score_scratch = ss_at ? (int *)(base + ss_at) : nullptr;
   ctx->pol = (int *)(base + pol_at);
   // set-up of the allocation-free entry point: the device address of the fixed scratch array, looked up once per

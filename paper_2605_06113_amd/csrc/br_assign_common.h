@@ -28,7 +28,7 @@ struct BrTailArgs {
   int32_t G, B, Bs, Q, P, Pq, C, arr_cap;
 };
 
-static_assert(sizeof(BrParams) == 248 && sizeof(BrArr) == 48 && sizeof(BrOut) == 48, "kernel argument layout");
+static_assert(sizeof(BrParams) == 256 && sizeof(BrArr) == 48 && sizeof(BrOut) == 48, "kernel argument layout");
 
 __device__ __forceinline__ BrTailArgs br_tail_args() {
   typedef __attribute__((address_space(4))) const char kchar_t;

@@ -42,6 +42,7 @@
 
 #include "br_sort.h"
 #include "br_assign_common.h"
+#include "br_subset_dp.h"
 
 template <int E>
 struct Log2E {
@@ -68,10 +69,12 @@ __device__ __forceinline__ void br_assign_body(const BrParams &p, const BrArr &a
   int *adm = lds + NP;        // [NP] by sorted position: worker << 16 | slot, or -1
   int *who = lds + 2 * NP;    // [NP] by arrival position: worker, or -1
   int *slots = lds + 3 * NP;  // [64] k-th alive request of a Stage-1 level: s << 11 | sorted position
-  int *win = slots + BR_WAVE; // [8]  Stage-2 candidate window, same packing (16-byte aligned); BIGR: [16]
-  int *hitab = win + 16;      // BIGR: [1024] sums of the window entries 6.. selected by the upper mask bits (16-byte aligned)
+  int *win = slots + BR_WAVE; // [8]  Stage-2 candidate window, same packing (16-byte aligned); BIGR: [32]
+  int *hitab = win + 32;      // BIGR: [1024] sums of the window entries 6.. selected by the upper mask bits (16-byte aligned)
   // COOP: mailbox of the searches that wave 0 hands to all four waves (one per 512 sorted positions)
-  int *svc = win + (BIGR ? 16 + 1024 : 8);  // [16] 0: 1 = search, 0 = round over; 1..9: margins; 10: room
+  int *svc = win + (BIGR ? 32 + 1024 : 8);  // [16] 0: 1 = search, 0 = round over; 1..9: margins; 10: room
+  // BIGR with windows beyond 16 requests: bit rows of the subset search (present when R_max > 16), after the rest
+  int *dprows = lds + 3 * NP + BR_WAVE + 32 + 1024 + (COOP ? 96 : 0);
   int *salive = svc + 16;                   // [64] wave 0's alive bits, one word per lane
   int *sres = salive + BR_WAVE;             // [8]  per wave: best key, its lowest sorted position
 
@@ -674,7 +677,14 @@ __device__ __forceinline__ void br_assign_body(const BrParams &p, const BrArr &a
         // score wins.
 #pragma unroll
         for (int b = 0; b < 8; ++b) wv[b] = 0, ws[b] = 0;
-        if (!guard_sure) {
+        if (!guard_sure && w > 16) {
+          // windows of 17..32 requests: reachable sums instead of masks (br_subset_dp.h)
+          br_wave_sync();
+          unsigned dm = 0u;
+          br_subset_dp<BRH>(p, mg, win, w, min(capmax, p.R_max), room, lane, dprows,
+                            p.dp + (size_t)inst * br_dp_cluster_words(min(p.B, p.R_max)), dm, bestkey);
+          bestmask = (int)dm;
+        } else if (!guard_sure) {
           br_wave_sync();
           const int nhi = w > 6 ? 1 << (w - 6) : 1;
           for (int c0 = 0; c0 < nhi; c0 += BR_WAVE) {
@@ -790,10 +800,11 @@ __device__ __forceinline__ void br_assign_body(const BrParams &p, const BrArr &a
         const int slot = __builtin_amdgcn_readlane(nn, g);
         int delta = 0;
         if constexpr (BIGR) {
-          if (lane < 16 && ((bestmask >> lane) & 1))
-            adm[win[lane] & IDX_MASK] = (g << 16) | (slot + __builtin_popcount(bestmask & ((1 << lane) - 1)));
+          const unsigned um = (unsigned)bestmask;
+          if (lane < 32 && ((um >> lane) & 1u))
+            adm[win[lane] & IDX_MASK] = (g << 16) | (slot + __builtin_popcount(um & ((1u << (lane & 31)) - 1u)));
           for (int b = 0; b < w; ++b)
-            if ((bestmask >> b) & 1) {
+            if ((um >> b) & 1u) {
               const int e = win[b];
               const int pb = e & IDX_MASK;
               alive = (lane == (pb & 63)) ? (alive & ~(1u << (pb >> 6))) : alive;
@@ -849,7 +860,7 @@ __device__ __forceinline__ void br_assign_body(const BrParams &p, const BrArr &a
 template <int E, bool BRH, bool ADV, bool BIGR = false>
 __global__ __launch_bounds__(256, (BRH && E == 8 && !BIGR) ? 4 : 1) void br_k_assign(BrParams p, BrArr a, BrOut o) {
   extern __shared__ int lds_all[];
-  constexpr int WORDS = 3 * E * BR_WAVE + BR_WAVE + (BIGR ? 16 + 1024 : 8) + (E == 32 ? 96 : 0);  // skey, adm, who, slots, win (+ table, + mailbox) per wave
+  constexpr int WORDS = 3 * E * BR_WAVE + BR_WAVE + (BIGR ? 32 + 1024 : 8) + (E == 32 ? 96 : 0);  // skey, adm, who, slots, win (+ table, + mailbox) per wave
   const int w = threadIdx.x >> 6;
   if constexpr (E == 32)  // one cluster per block, four waves for the sort
     br_assign_body<E, BRH, ADV, true, BIGR>(p, a, o, lds_all, (int)blockIdx.x, w);
@@ -860,8 +871,10 @@ __global__ __launch_bounds__(256, (BRH && E == 8 && !BIGR) ? 4 : 1) void br_k_as
 template <int E, bool BRH, bool BIGR = false>
 static void br_launch_assign_one(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st) {
   // several single-wave clusters share a block so that the chip's per-CU block slots do not cap residency
-  const int wpb = E <= 8 ? 4 : 1;  // clusters per block
-  const size_t lds = (size_t)wpb * (3 * E * BR_WAVE + BR_WAVE + (BIGR ? 16 + 1024 : 8) + (E == 32 ? 96 : 0)) * sizeof(int);
+  const bool dp = BIGR && p.R_max > 16;   // windows beyond 16 requests: one cluster per block, with LDS for the bit rows
+  const int wpb = (E <= 8 && !dp) ? 4 : 1;  // clusters per block
+  const size_t lds = ((size_t)wpb * (3 * E * BR_WAVE + BR_WAVE + (BIGR ? 32 + 1024 : 8) + (E == 32 ? 96 : 0)) +
+                      (dp ? BR_DP_LDS_WORDS : 0)) * sizeof(int);
   const dim3 grid((unsigned)((p.N + wpb - 1) / wpb)), block(E == 32 ? 4 * BR_WAVE : BR_WAVE * wpb);
   if constexpr (BIGR) {  // no fused decode steps for these: the caller launches the decode kernel
     hipLaunchKernelGGL((br_k_assign<E, BRH, false, true>), grid, block, lds, st, p, a, o);

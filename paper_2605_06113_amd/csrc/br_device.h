@@ -31,6 +31,7 @@ struct BrParams {
   const int32_t *hist;      // sorted output lengths (pred_mode 2)
   const long long *hsum;    // their prefix sums
   const float *dl;          // H > BR_HP: discount vector d[0..H], then zeros up to BR_HS(H) entries
+  int32_t *dp;              // R_max > 16: per-cluster areas for the subset search by reachable sums (br_subset_dp.h)
 };
 
 struct BrArr {  // arrivals of one round (device pointers, may be null when none)

@@ -36,7 +36,7 @@ def test_workspace_bytes_scale():
 
 
 @pytest.mark.parametrize("bad", [dict(G=0), dict(G=65), dict(B=0), dict(B=1025), dict(max_wait=0),
-                                 dict(max_wait=2049), dict(H=9), dict(H=129, pred_mode=1), dict(H=-1), dict(R_max=0), dict(R_max=17),
+                                 dict(max_wait=2049), dict(H=9), dict(H=129, pred_mode=1), dict(H=-1), dict(R_max=0), dict(R_max=33), dict(H=80, pred_mode=1, R_max=17),
                                  dict(n_inst=0), dict(token_watermark=-1), dict(pred_mode=2), dict(H=4, pred_mode=4),
                                  dict(H=2, alpha=0.0), dict(H=2, gamma=0.0), dict(H=2, gamma=1.5)])
 def test_invalid_config_rejected(bad):

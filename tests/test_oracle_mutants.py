@@ -44,6 +44,11 @@ MUTANTS = [
     # Stage 2 subsets
     ("subset size unbounded", "if (popcount32(mask) > kmax) continue;", ""),
     ("subset ties to the highest mask", "if (best == 0 || f > bs) {\n      best = (int32_t)mask;", "if (best == 0 || f >= bs) {\n      best = (int32_t)mask;"),
+    ("reachable sums: a request used twice", "    for (j = kmax; j >= 1; --j)\n      for (sum = top; sum >= s; --sum) {", "    for (j = 1; j <= kmax; ++j)\n      for (sum = s; sum <= top; ++sum) {"),
+    ("reachable sums: ties to the highest mask", "(f == bs && mask < (int64_t)(uint32_t)best)", "(f == bs && mask > (int64_t)(uint32_t)best)"),
+    ("reachable sums: a later subset replaces the entry", "if (from >= 0 && tab[j * (top + 1) + sum] < 0) tab", "if (from >= 0) tab"),
+    ("reachable sums: table one row short", "    int64_t mask = tab[kmax * (top + 1) + sum];", "    int64_t mask = tab[(kmax - 1) * (top + 1) + sum];"),
+    ("reachable sums: watermark ignored", "    if (mask < 0) continue;\n    if (P->token_watermark > 0 && L_g + sum > P->token_watermark) continue;", "    if (mask < 0) continue;"),
     # the round
     ("waiting set ascending", "if (x->s != y->s) return x->s > y->s ? -1 : 1;", "if (x->s != y->s) return x->s < y->s ? -1 : 1;"),
     ("stage 1 prefers the heaviest", "(R.cap[g] == R.cap[bw] && R.L[g] < R.L[bw])) bw = g;", "(R.cap[g] == R.cap[bw] && R.L[g] > R.L[bw])) bw = g;"),

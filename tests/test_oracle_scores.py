@@ -298,3 +298,97 @@ def test_subset_search_matches_bitset_reduction(orc, H):
         assert reach >> chosen & 1 and 1 <= bin(mask).count("1") <= kmax
         fc = orc.score_br0(G, int(m[0]), chosen) if H == 0 else orc.score_brh(H, cfg.alpha, cfg.beta_eff, cfg.gamma, m, chosen)
         assert fc == best
+
+
+# ---- wide windows: the subset search by reachable sums (Appendix "Bit-set subset selection") -------------------
+
+def _wide_case(rng, w, tie_heavy, H):
+    from paper_2605_06113_amd.workloads import RouteConfig
+    G = int(rng.integers(1, 33))
+    R_max = int(rng.integers(max(w, 1), 33))
+    cfg = RouteConfig(name="t", n_inst=1, G=G, B=64, max_wait=64, H=H, R_max=R_max, gamma=float(rng.choice([0.64, 0.9, 1.0])),
+                      token_watermark=int(rng.choice([0, 0, 9000])))
+    if tie_heavy:
+        win = sorted(rng.choice([64, 128, 192, 256], w).tolist(), reverse=True)
+        m = rng.integers(0, 1500, H + 1)
+    else:
+        win = sorted(rng.integers(1, int(rng.choice([40, 2500, 9000])), w).tolist(), reverse=True)
+        m = rng.integers(0, int(rng.choice([300, 12000, 60000])), H + 1)
+    cap = int(rng.integers(1, 40))
+    L_g = int(rng.integers(0, 5000))
+    return cfg, win, m, cap, L_g
+
+
+@pytest.mark.parametrize("H", [0, 3])
+def test_reachable_sum_search_equals_scan_of_all_masks(orc, H):
+    """Wherever both apply the two searches return the same subset and score: windows of 1..16 requests against
+    the scan the round uses there, windows of 17..20 against the same scan run over all 2^w masks.  Equal lengths
+    (many subsets per sum, many sums per score) exercise the lowest-mask rule."""
+    rng = np.random.default_rng(400 + H)
+    for case in range(150):
+        w = int(rng.integers(1, 17)) if case < 120 else int(rng.integers(17, 21))
+        cfg, win, m, cap, L_g = _wide_case(rng, w, tie_heavy=case % 3 == 0, H=H)
+        P = orc.params_from(cfg)
+        a = orc.best_subset(P, m, L_g, cap, win)
+        b = orc.best_subset_reach(P, m, L_g, cap, win)
+        assert (a[0] & 0xFFFFFFFF, a[1]) == b, (case, w, win, m.tolist(), cap, a, b)
+
+
+def test_reachable_sum_search_32_requests_lowest_mask_by_halves(orc):
+    """Windows of 32 requests, BR-0: the optimum over reachable sums by the shift-OR recurrence on Python integers,
+    and the lowest mask that attains it found independently by splitting the window into two halves of 16 (upper
+    half masks in ascending order, the lowest matching lower-half mask from a table)."""
+    from paper_2605_06113_amd.workloads import RouteConfig
+    rng = np.random.default_rng(77)
+    for case in range(12):
+        G = int(rng.integers(2, 33))
+        w = 32
+        cfg = RouteConfig(name="t", n_inst=1, G=G, B=64, max_wait=64, H=0, R_max=32)
+        P = orc.params_from(cfg)
+        win = sorted((rng.choice([64, 128, 192, 256], w) if case % 2 else rng.integers(1, 3000, w)).tolist(), reverse=True)
+        cap = int(rng.integers(1, 12))
+        kmax = min(cap, 32)
+        m = int(rng.integers(0, 20000))
+        mask, f = orc.best_subset_reach(P, [m], 0, cap, win)
+        dp = [0] * (kmax + 1)
+        dp[0] = 1
+        for s in win:
+            for j in range(kmax, 0, -1):
+                dp[j] |= dp[j - 1] << s
+        reach = dp[kmax] >> 1 << 1            # at most kmax requests (dp[j] contains dp[j-1]: dp[0] = {0} stays in all)
+        for j in range(1, kmax):
+            reach |= dp[j]
+        sums = [b for b in range(1, reach.bit_length()) if reach >> b & 1]
+        best = max(orc.score_br0(G, m, d) for d in sums)
+        assert f == best
+        targets = {d for d in sums if orc.score_br0(G, m, d) == best}
+        # lower half: for every (number of requests, sum) the lowest 16-bit mask
+        lo_w, hi_w = np.array(win[:16]), np.array(win[16:])
+        masks = np.arange(1 << 16)
+        bits = (masks[:, None] >> np.arange(16)) & 1
+        lo_sum, hi_sum, pop = bits @ lo_w, bits @ hi_w, bits.sum(1)
+        table = {}
+        for mk in range((1 << 16) - 1, -1, -1):
+            table[(int(pop[mk]), int(lo_sum[mk]))] = mk          # descending: the lowest mask is written last
+        found = None
+        for u in range(1 << 16):
+            if pop[u] > kmax:
+                continue
+            cands = [table.get((p, d - int(hi_sum[u]))) for d in targets for p in range(0, kmax - int(pop[u]) + 1)]
+            cands = [c for c in cands if c is not None and (c or u)]
+            if cands:
+                found = (u << 16) | min(cands)
+                break
+        assert found == mask, (case, hex(found), hex(mask))
+
+
+def test_reachable_sum_table_ends_at_its_bound(orc):
+    """Subsets whose sum exceeds the table's bound (131071) are not candidates: 17 requests of 32768 tokens, room
+    for 5, a margin that would take them all: three requests (98304) are the most the table holds."""
+    from paper_2605_06113_amd.workloads import RouteConfig
+    cfg = RouteConfig(name="t", n_inst=1, G=4, B=64, max_wait=64, H=0, R_max=17)
+    P = orc.params_from(cfg)
+    mask, f = orc.best_subset_reach(P, [10 ** 6], 0, 5, [32768] * 17)
+    assert (mask, f) == (0b111, 98304.0)
+    mask, f = orc.best_subset_reach(P, [10 ** 6], 0, 5, [32768] + [100] * 16)     # 32768 + 4 x 100 fits
+    assert (mask, f) == (0b11111, 33168.0)
