@@ -307,6 +307,18 @@ static int32_t route(br_ctx *ctx, const br_arrivals *in, const br_step_out *out,
   // large batches of clusters with short queues: the reductions ride along in the assignment launch
   const bool together = (o.best_g || o.best_i) && !o.F && p.N >= BR_SCORE_WAVE_MIN_N && p.R_max <= 8 &&
                         (p.H == 0 ? p.Q <= 256 : (p.H <= BR_HP && p.Q <= 512));
+  // BR-0 with decode steps: round and decode steps on two waves per cluster; the reductions ride on the helper wave
+  // unless the matrix is asked for (then the score kernel writes all three outputs)
+  const bool split = br_split_serves(p);
+  if (split) {
+    BrOut o2 = o;
+    if (o.F) {
+      rc = enqueue(ctx, BR_K_SCORE, [&] { br_launch_score(p, a, o, partials, ctx->st); }, br);
+      o2.F = nullptr, o2.best_g = nullptr, o2.best_i = nullptr;
+    }
+    if (rc == BR_OK) rc = enqueue(ctx, BR_K_ASSIGN, [&] { br_launch_route_split(p, a, o2, ctx->st); }, br);
+    return rc;
+  }
   if (rc == BR_OK && !together && (o.F || o.best_g || o.best_i))
     rc = enqueue(ctx, BR_K_SCORE, [&] { br_launch_score(p, a, o, partials, ctx->st); }, br);
   if (rc == BR_OK) {

@@ -13,12 +13,10 @@ __global__ __launch_bounds__(256) void br_k_route4(BrParams p, BrArr a, BrOut o)
   constexpr int E = 4;
   const int w = threadIdx.x >> 6, inst = (int)blockIdx.x * 4 + w;
   if (inst >= p.N) return;
-  {
-    BrScoreIn<E, false> in;
-    br_score_wave_load<E, false>(p, a, inst, br_lane(), in);
-    br_score_wave_run<E, false>(p, o, inst, br_lane(), in);
-  }
-  br_assign_body<E, false, ADV>(p, a, o, lds_all + w * (3 * E * BR_WAVE + BR_WAVE + 8), inst);
+  BrScoreIn<E, false> in;  // loaded once, used by both parts
+  br_score_wave_load<E, false>(p, a, inst, br_lane(), in);
+  br_score_wave_run<E, false>(p, o, inst, br_lane(), in);
+  br_assign_body<E, false, ADV>(p, a, o, lds_all + w * (3 * E * BR_WAVE + BR_WAVE + 8), inst, 0, &in);
 }
 
 void br_launch_route4(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st) {

@@ -5,6 +5,7 @@
 #pragma once
 
 #include "br_device.h"
+#include "br_score_wave.h"
 
 #define BR_STAT(o, inst, k) (o).stats[(int64_t)(inst) * 16 + (k)]
 
@@ -25,7 +26,7 @@ struct BrTailArgs {
   const float *apred;
   int32_t *assign, *assign_id;
   long long *stats;
-  int32_t G, B, Bs, Q, P, Pq, C, arr_cap;
+  int32_t G, B, Bs, Q, P, Pq, C, arr_cap, adv_t;
 };
 
 static_assert(sizeof(BrParams) == 256 && sizeof(BrArr) == 48 && sizeof(BrOut) == 48, "kernel argument layout");
@@ -45,7 +46,7 @@ __device__ __forceinline__ BrTailArgs br_tail_args() {
   t.qlen = kp->qlen, t.qs = kp->qs, t.qo = kp->qo, t.qid = kp->qid, t.qpred = kp->qpred;
   t.as = kaa->s, t.ao = kaa->o, t.aid = kaa->id, t.apred = kaa->pred;
   t.assign = ko->assign, t.assign_id = ko->assign_id, t.stats = ko->stats;
-  t.G = kp->G, t.B = kp->B, t.Bs = kp->Bs, t.Q = kp->Q, t.P = kp->P, t.Pq = kp->Pq, t.C = kp->C;
+  t.G = kp->G, t.B = kp->B, t.Bs = kp->Bs, t.Q = kp->Q, t.P = kp->P, t.Pq = kp->Pq, t.C = kp->C, t.adv_t = kp->adv_t;
   t.arr_cap = kaa->arr_cap;
   return t;
 }
@@ -291,8 +292,11 @@ __device__ __forceinline__ BrParams br_late_params() {
 // Decode advance of one cluster by the wave that has just routed it: br_adv_apply (the arithmetic of
 // the stand-alone advance kernel) over the cluster's G lists in (list, 256-slot chunk) units, UB units
 // requested before the first is used.  `Lcur`, `nn`: load and list length of worker `lane` after the round.
-template <int UB, bool BRH>
-__device__ __forceinline__ void br_advance_cluster(int inst, int lane, int Lcur, int nn, int g0 = 0, int g1 = 64) {
+// STORE = false: loads and counts are not stored; lane g returns its list's load change in `dL_out` and its new
+// length in `n_out` instead (the split kernels, where another wave owns the workers' final state).
+template <int UB, bool BRH, bool STORE = true>
+__device__ __forceinline__ void br_advance_cluster(int inst, int lane, int Lcur, int nn, int g0 = 0, int g1 = 64,
+                                                   int *dL_out = nullptr, int *n_out = nullptr) {
   const BrParams p = br_late_params();
   const int t = p.adv_t;
   br_wave_sync();  // the round's own writes into the lists are read back below
@@ -326,8 +330,153 @@ __device__ __forceinline__ void br_advance_cluster(int inst, int lane, int Lcur,
       }
     }
   }
-  if (lane >= g0 && lane < G) {
-    p.L[row0 + lane] = Lcur + dLw;
-    p.n[row0 + lane] = nw;
+  if constexpr (STORE) {
+    if (lane >= g0 && lane < G) {
+      p.L[row0 + lane] = Lcur + dLw;
+      p.n[row0 + lane] = nw;
+    }
+  } else {
+    *dL_out = dLw;
+    *n_out = nw;
   }
 }
+
+// ---------------------------------------------------------------- split step: round and decode step on two waves
+// In the split kernels (BR-0, queues of up to 512) the decode steps of a cluster's lists as they stand at the
+// start of the step are applied by a second wave (the helper) while the first runs the round; the wave that ran
+// the round then appends its admissions behind the survivors, already advanced.  Same final state as the round
+// followed by the decode steps: a list holds its old survivors in order, then the new survivors in admission
+// order; L_g = sum of the kv held; a request whose output is used up within the t steps leaves at once.
+// LDS area of one cluster: [0] flag (helper done), [4..68) per worker: entries its list lost (old length - kept),
+// [68..132) per worker: load change of the old entries.
+#define BR_SPLIT_WORDS 132
+
+// The helper's part for one cluster: snapshot reductions if asked for (they read what the round's epilogue will
+// overwrite, and the epilogue waits for the flag), the decode steps of the old entries, then the flag.
+// UB: (list, chunk) units requested before the first is used
+template <int E, int UB>
+__device__ __forceinline__ void br_split_helper(const BrParams &p, const BrArr &a, const BrOut &o, int inst, int lane,
+                                                int *split) {
+  const bool act = lane < p.G;
+  int n0;
+  if (o.best_g || o.best_i) {
+    BrScoreIn<E, false> in;
+    br_score_wave_load<E, false>(p, a, inst, lane, in);
+    br_score_wave_run<E, false>(p, o, inst, lane, in);
+    n0 = in.n;
+  } else {
+    n0 = act ? p.n[(int64_t)inst * p.G + lane] : p.B;
+  }
+  n0 = act ? min(max(n0, 0), p.B) : 0;
+  int dL = 0, kept = n0;
+  br_advance_cluster<UB, false, false>(inst, lane, 0, n0, 0, 64, &dL, &kept);
+  split[4 + lane] = n0 - kept;
+  split[4 + BR_WAVE + lane] = dL;
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // the lists are in place before the flag is seen
+  __builtin_amdgcn_wave_barrier();
+  if (lane == 0) split[0] = 1;
+}
+
+// The epilogue of the wave that ran the round, in a split kernel.  nn0: list lengths at the start of the step.
+template <int E>
+__device__ __forceinline__ void br_assign_epilogue_split(int inst, int lane, int q0, int qn, int cnt, const int *skey,
+                                                         const int *adm, int *who, int Lcur, int nn, int nn0,
+                                                         const BrRoundCounts &rc, int *split) {
+  const BrTailArgs t = br_tail_args();
+  constexpr int IDX_MASK = (1 << BR_IDX_BITS) - 1;
+  const int G = t.G, tt = t.adv_t;
+  const int64_t qrow = (int64_t)inst * t.Q, arow = (int64_t)inst * t.arr_cap;
+  // the helper is done with this cluster's lists (it never waits for anything: the flag always comes)
+  while (__atomic_load_n(split, __ATOMIC_RELAXED) == 0) __builtin_amdgcn_s_sleep(4);
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+  const int lost = split[4 + lane], dold = split[4 + BR_WAVE + lane];  // lane g: worker g
+  const int kept0 = nn0 - lost, a_g = nn - nn0;                        // old survivors, admissions of this round
+  int nfin = kept0 + a_g, Lfin = Lcur + dold + a_g * tt;               // if every admitted request outlives the t steps
+  bool slow = false;
+  if (rc.admitted > 0) {
+    // every admitted request of the cluster, E sorted positions per lane: all reads before the first store
+    int64_t row[E];
+    int kvv[E], remv[E];
+    bool ok[E];
+    bool short_one = false;
+#pragma unroll
+    for (int u = 0; u < E; ++u) {
+      const int pos = u * BR_WAVE + lane;
+      ok[u] = false;
+      kvv[u] = 0, remv[u] = 1, row[u] = 0;
+      if (pos < qn) {
+        const int ad = adm[pos];
+        if (ad >= 0) {
+          const int key = skey[pos];
+          const int idx = IDX_MASK - (key & IDX_MASK);
+          const int g = ad >> 16, slot = ad & 0xffff;
+          if (g < G && slot < t.B && idx < qn) {
+            ok[u] = true;
+            row[u] = ((int64_t)inst * G + g) * t.Bs + (slot - split[4 + g]);  // behind the old survivors
+            kvv[u] = key >> BR_IDX_BITS;
+            remv[u] = idx < q0 ? t.qo[qrow + idx] : max(t.ao[arow + (idx - q0)], 1);
+            short_one |= remv[u] <= tt;
+            who[idx] = g;
+          }
+        }
+      }
+    }
+    slow = br_ballot(short_one) != 0ull;  // some admitted request ends within the t steps: lists are compacted below
+    const int add = slow ? 0 : tt;
+#pragma unroll
+    for (int u = 0; u < E; ++u) {
+      if (ok[u]) {
+        t.kv[row[u]] = kvv[u] + add;
+        t.rem[row[u]] = remv[u] - add;
+      }
+    }
+  }
+  br_wave_sync();
+  int keptq = 0;
+  constexpr int GR = E < 4 ? E : 4;
+#pragma unroll
+  for (int j0 = 0; j0 < E; j0 += GR) {
+    if (j0 * BR_WAVE < t.Q) {
+      BrQueueGroup<GR> v;
+      br_queue_load<GR>(t, inst, lane, j0, q0, qn, who, v);
+      br_queue_store<GR>(t, inst, lane, j0, q0, v, keptq);
+    }
+  }
+  br_write_state(t, inst, lane, q0, qn, cnt, keptq, Lcur, nn, rc, false);  // statistics: the state right after the round
+  if (slow) {
+    // The admissions sit behind the old survivors as admitted (kv = s, rem = o); per worker the decode steps
+    // now run over that stretch alone: who outlives them moves up and gains t tokens, the others leave.
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");  // the stores above are read back below
+    __builtin_amdgcn_wave_barrier();
+    for (int g = 0; g < G; ++g) {
+      const int ag = __builtin_amdgcn_readlane(a_g, g);
+      if (ag <= 0) continue;
+      const int64_t base = ((int64_t)inst * G + g) * t.Bs + __builtin_amdgcn_readlane(kept0, g);
+      int keptn = 0, gone = 0;
+      for (int c0 = 0; c0 < ag; c0 += BR_WAVE) {
+        const int j = c0 + lane;
+        const bool in = j < ag;
+        const int kv = in ? t.kv[base + j] : 0, rem = in ? t.rem[base + j] : 0;
+        const bool stay = in && rem > tt;
+        const unsigned long long bal = br_ballot(stay);
+        const int dst = keptn + br_rank_below(bal);
+        if (stay) {  // at or below its own position; the chunk was read whole before
+          t.kv[base + dst] = kv + tt;
+          t.rem[base + dst] = rem - tt;
+        }
+        gone += br_wave_sum((in && !stay) ? kv : 0);
+        keptn += (int)__builtin_popcountll(bal);
+      }
+      if (lane == g) {
+        nfin = kept0 + keptn;
+        Lfin = Lcur + dold - gone + keptn * tt;
+      }
+    }
+  }
+  if (lane < G) {
+    const int64_t wrow = (int64_t)inst * G + lane;
+    t.L[wrow] = Lfin;
+    t.n[wrow] = nfin;
+  }
+}
+

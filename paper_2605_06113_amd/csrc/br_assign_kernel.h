@@ -43,6 +43,7 @@
 #include "br_sort.h"
 #include "br_assign_common.h"
 #include "br_subset_dp.h"
+#include "br_score_wave.h"
 
 template <int E>
 struct Log2E {
@@ -54,8 +55,12 @@ struct Log2E {
 // the round with the sorted keys read back from LDS and hands every full search over the waiting set
 // (argmax_i F_g({i})) to all four, 512 sorted positions each; all four share the epilogue and the decode step.
 template <int E, bool BRH, bool ADV, bool COOP = false, bool BIGR = false>
+// `pre`: what the snapshot reductions of the same wave have already loaded for this cluster (queue lengths,
+// prefill lengths in arrival order, worker loads and counts), or null: the round then loads them itself.
+// `split`: the cluster's BR_SPLIT_WORDS of LDS in a split kernel (another wave applies the decode steps to the old
+// list entries meanwhile), or null.
 __device__ __forceinline__ void br_assign_body(const BrParams &p, const BrArr &a, const BrOut &o, int *lds, int inst,
-                                               int w = 0) {
+                                               int w = 0, const BrScoreIn<E, BRH> *pre = nullptr, int *split = nullptr) {
   static_assert(!COOP || E == 32, "the four-wave sort covers 4 x 512 keys");
   constexpr int NP = E * BR_WAVE;
   constexpr int NH = BRH ? BR_HP + 1 : 1;
@@ -80,9 +85,14 @@ __device__ __forceinline__ void br_assign_body(const BrParams &p, const BrArr &a
 
   const int lane = br_lane();
   const int G = p.G;
-  const int q0 = br_uniform(min(max(p.qlen[inst], 0), p.Q));
-  int cnt = a.count ? a.count[inst] : 0;
-  cnt = br_uniform(min(max(cnt, 0), a.arr_cap));
+  int q0, cnt;
+  if (pre) {
+    q0 = pre->q0, cnt = pre->cnt;
+  } else {
+    q0 = br_uniform(min(max(p.qlen[inst], 0), p.Q));
+    cnt = a.count ? a.count[inst] : 0;
+    cnt = br_uniform(min(max(cnt, 0), a.arr_cap));
+  }
   const int qn = q0 + min(cnt, p.Q - q0);
   const int64_t qrow = (int64_t)inst * p.Q, arow = (int64_t)inst * a.arr_cap;
 
@@ -162,18 +172,39 @@ __device__ __forceinline__ void br_assign_body(const BrParams &p, const BrArr &a
   // ---- worker state, one worker per lane
   const bool act = lane < G;
   const int64_t wrow = (int64_t)inst * G + lane;
-  int nn = act ? min(max(p.n[wrow], 0), p.B) : p.B;
+  int nn = act ? min(max(pre ? pre->n : p.n[wrow], 0), p.B) : p.B;
   int cap = p.B - nn;
+  const int nn_start = nn;
   int Lh[NH], Mh[NH];
   if constexpr (BRH) {
 #pragma unroll
     for (int h = 0; h < NH; ++h) Lh[h] = act ? p.Lh[wrow * (p.H + 1) + min(h, p.H)] : BR_LOW;
   } else {
-    Lh[0] = act ? p.L[wrow] : BR_LOW;
+    Lh[0] = act ? (pre ? pre->L : p.L[wrow]) : BR_LOW;
   }
 #pragma unroll
   for (int h = 0; h < NH; ++h) Mh[h] = br_wave_max(Lh[h]);
   int S_tot = br_wave_sum(cap);
+  const bool small = G <= 16;  // every worker sits in the first row of 16 lanes: row reductions serve
+  // largest free-slot count among the workers: free slots only shrink during a round, so the value is tracked
+  // downwards with ballots instead of a reduction per pick
+  int capmax_cur = br_wave_max(cap);
+  auto cap_max = [&]() -> int {
+    while (capmax_cur > 0 && br_ballot(cap == capmax_cur) == 0ull) --capmax_cur;
+    return capmax_cur;
+  };
+  auto workers_max = [&](int x) -> int { return small ? br_row0_max(x) : br_wave_max(x); };
+  auto workers_min = [&](int x) -> int { return small ? br_row0_min(x) : br_wave_min(x); };
+  // rank of each member among the members by (load, index): lanes that are no members hold INT32_MAX
+  auto rank_of = [&](int wkey) -> int {
+    if (small) return br_row_rank(wkey);
+    int rank = 0;
+    for (int g0 = 0; g0 < G; g0 += 4) {  // lanes beyond G hold INT32_MAX and never count
+#pragma unroll
+      for (int u = 0; u < 4; ++u) rank += (__builtin_amdgcn_readlane(wkey, g0 + u) < wkey) ? 1 : 0;
+    }
+    return rank;
+  };
 
   // sum of loads in two 16-bit halves (each partial sum fits int32 for loads below 2^25)
   auto sum_loads = [&]() -> long long {
@@ -191,8 +222,13 @@ __device__ __forceinline__ void br_assign_body(const BrParams &p, const BrArr &a
       const int i = j * BR_WAVE + lane;
       unsigned key = 0;
       if (i < qn) {
-        int s = i < q0 ? p.qs[qrow + i] : a.s[arow + (i - q0)];
-        s = min(max(s, 1), BR_MAX_S_DEV);
+        int s;
+        if (pre) {
+          s = pre->s[j];  // already clamped
+        } else {
+          s = i < q0 ? p.qs[qrow + i] : a.s[arow + (i - q0)];
+          s = min(max(s, 1), BR_MAX_S_DEV);
+        }
         key = ((unsigned)s << BR_IDX_BITS) | (unsigned)(IDX_MASK - i);
       }
       xk[j] = key;
@@ -469,7 +505,7 @@ __device__ __forceinline__ void br_assign_body(const BrParams &p, const BrArr &a
       const bool taken = pp > pend || (sv[j] == vK && pp <= pK);
       alive &= ~((taken ? 1u : 0u) << j);
     }
-    Mh[0] = br_wave_max(Lh[0]);
+    Mh[0] = workers_max(Lh[0]);
     S_tot -= K;
     n_alive -= K;
     admitted += K;
@@ -484,17 +520,13 @@ __device__ __forceinline__ void br_assign_body(const BrParams &p, const BrArr &a
     // ---- Stage 1: greedy fill while free capacity is abundant
     for (int it = 0; it < bound; ++it) {
       if (!(S_tot > p.S_greedy && n_alive > 0)) break;
-      const int capmax = br_wave_max(cap);
+      const int capmax = cap_max();
       if (capmax <= 0) break;
       // the level: workers sharing the largest free-slot count, ranked by (load, index); each is
       // picked exactly once, in rank order, before any other worker can reach this free-slot count
       const bool member = cap == capmax;
       const int wkey = member ? (int)(((unsigned)Lh[0] << 6) | (unsigned)lane) : INT32_MAX;
-      int rank = 0;
-      for (int g0 = 0; g0 < G; g0 += 4) {  // lanes beyond G hold INT32_MAX and never count
-#pragma unroll
-        for (int u = 0; u < 4; ++u) rank += (__builtin_amdgcn_readlane(wkey, g0 + u) < wkey) ? 1 : 0;
-      }
+      const int rank = rank_of(wkey);
       const int level = __builtin_popcountll(br_ballot(member));
       const int kmaxp = min(level, min(S_tot - p.S_greedy, n_alive));
       // the first kmaxp alive requests, by rank, through LDS
@@ -518,7 +550,7 @@ __device__ __forceinline__ void br_assign_body(const BrParams &p, const BrArr &a
       const int s_k = mine >> BR_IDX_BITS, pos_k = mine & IDX_MASK;
       int lim = lane_minm();
       if (p.W > 0) lim = min(lim, p.W - Lh[0]);
-      const int k0 = br_wave_min((cand && s_k > lim) ? rank : kmaxp);
+      const int k0 = workers_min((cand && s_k > lim) ? rank : kmaxp);
       if (k0 > 0) {  // ranks 0..k0-1 are in the safe regime: k-th lightest worker takes k-th largest request
         const bool take = cand && rank < k0;
         if (take) adm[pos_k] = (lane << 16) | nn;
@@ -526,7 +558,8 @@ __device__ __forceinline__ void br_assign_body(const BrParams &p, const BrArr &a
         for (int h = 0; h < NH; ++h) Lh[h] += take ? s_k : 0;
         nn += take ? 1 : 0;
         cap -= take ? 1 : 0;
-        const int pstar = br_uniform(slots[k0 - 1] & IDX_MASK);  // last position taken; everything alive before it went too
+        // last position taken (everything alive before it went too): the request of the worker ranked k0 - 1
+        const int pstar = __builtin_amdgcn_readlane(pos_k, (int)__builtin_ctzll(br_ballot(cand && rank == k0 - 1)));
         const int jf = pstar >> 6, lf = pstar & 63;
         const unsigned clear = ((1u << jf) - 1u) | ((lane <= lf) ? (1u << jf) : 0u);
         alive &= ~clear;
@@ -590,11 +623,11 @@ __device__ __forceinline__ void br_assign_body(const BrParams &p, const BrArr &a
     const int lpop = __builtin_popcount(lane);
     for (int it = 0; it < bound; ++it) {
       if (n_alive <= 0) break;
-      const int capmax = br_wave_max(cap);
+      const int capmax = cap_max();
       if (capmax <= 0) break;
       // priority (free slots, horizon-min margin), lowest index on ties
       const int kc = (cap == capmax) ? (int)(((unsigned)lane_minm() << 6) | (unsigned)(63 - lane)) : -1;
-      const int g = 63 - (br_wave_max(kc) & 63);
+      const int g = 63 - (workers_max(kc) & 63);
       ++pops;
       int Lg[NH], mg[BR_HP + 1];
       margins_of(g, Lg, mg);
@@ -653,11 +686,7 @@ __device__ __forceinline__ void br_assign_body(const BrParams &p, const BrArr &a
             const int K = min(level, n_alive - w);
             if (K >= 3) {
               const int wkey = member ? (int)(((unsigned)Lh[0] << 6) | (unsigned)lane) : INT32_MAX;
-              int rank = 0;
-              for (int g0 = 0; g0 < G; g0 += 4) {
-#pragma unroll
-                for (int u = 0; u < 4; ++u) rank += (__builtin_amdgcn_readlane(wkey, g0 + u) < wkey) ? 1 : 0;
-              }
+              const int rank = rank_of(wkey);
               const int done = tail_bulk(member, rank, 0, K, (G - 1) * s_last / G);
               if (done > 0) {
                 pops += done - 1;
@@ -847,8 +876,17 @@ __device__ __forceinline__ void br_assign_body(const BrParams &p, const BrArr &a
     br_assign_epilogue_block4(inst, lane, 0, q0, qn, cnt, skey, adm, who, slots, Lw, nn, rc, c0, ADV);
     if constexpr (ADV) br_advance_cluster<4, BRH>(inst, lane, Lw, nn, 0, min((G + 3) >> 2, G));
   } else {
-    br_assign_epilogue<E>(inst, lane, q0, qn, cnt, skey, adm, who, Lh[0], nn, rc, c0);
-    if constexpr (ADV) br_advance_cluster<(BRH ? 4 : 8), BRH>(inst, lane, Lh[0], nn);  // BR-H units carry the estimator code: fewer unrolled
+    bool done = false;
+    if constexpr (!BRH && !BIGR && !ADV && E <= 8) {
+      if (split != nullptr) {
+        br_assign_epilogue_split<E>(inst, lane, q0, qn, cnt, skey, adm, who, Lh[0], nn, nn_start, rc, split);
+        done = true;
+      }
+    }
+    if (!done) {
+      br_assign_epilogue<E>(inst, lane, q0, qn, cnt, skey, adm, who, Lh[0], nn, rc, c0);
+      if constexpr (ADV) br_advance_cluster<(BRH ? 4 : 8), BRH>(inst, lane, Lh[0], nn);  // BR-H units carry the estimator code: fewer unrolled
+    }
   }
 }
 

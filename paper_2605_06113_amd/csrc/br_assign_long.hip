@@ -9,8 +9,9 @@
 // back to the single best request when no subset scores above zero.
 //
 // What differs from the short-horizon kernel is where the per-offset state lives:
-//   - the step-start projections L_g(k+h) stay in LDS, sL[h][g] (row stride 65 words, so that both
-//     "lane = worker" and "lane = offset" reads spread over the banks) and are never rewritten: an
+//   - the step-start projections L_g(k+h) stay in LDS, sL[h][g] (row stride G | 1 words: odd, so that both
+//     "lane = worker" and "lane = offset" reads spread over the banks, and no wider than the cluster needs:
+//     with few workers several clusters then share a CU's LDS) and are never rewritten: an
 //     admission adds its length at every offset (constant-s approximation of Sec. 4.1), so worker g's
 //     current projection is sL[h][g] + add_g with one register add_g per lane;
 //   - the envelope M_h and the margins of the worker in hand are LDS arrays maintained with lanes
@@ -25,7 +26,7 @@
 #include "br_sort.h"
 #include "br_assign_common.h"
 
-#define BR_LSTRIDE 65  // words between offsets in sL
+#define BR_LSTRIDE(G) ((G) | 1)  // words between offsets in sL (odd; one spare "no worker" column when G is even)
 
 template <int E, bool ADV>
 __global__ __launch_bounds__(64) void br_k_assign_long(BrParams p, BrArr a, BrOut o) {
@@ -43,8 +44,9 @@ __global__ __launch_bounds__(64) void br_k_assign_long(BrParams p, BrArr a, BrOu
   int *sM = win + BR_WAVE;          // [HS] envelope M_h
   float *smg = (float *)(sM + HS);  // [HS] margins of the worker in hand, as floats
   float *sd = smg + HS;             // [HS] discounts, zero beyond H
-  int *sL = sM + 3 * HS;            // [HS][65] step-start projections (rows beyond H: "no worker")
-  int *hitab = sL + ((HS * BR_LSTRIDE + 3) & ~3);  // R_max > 8: [1024] sums of window entries 6.. by upper mask bits
+  const int LS = BR_LSTRIDE(p.G);
+  int *sL = sM + 3 * HS;            // [HS][LS] step-start projections (rows beyond H: "no worker")
+  int *hitab = sL + ((HS * LS + 3) & ~3);  // R_max > 8: [1024] sums of window entries 6.. by upper mask bits
 
   const int lane = br_lane();
   const int G = p.G;
@@ -72,10 +74,10 @@ __global__ __launch_bounds__(64) void br_k_assign_long(BrParams p, BrArr a, BrOu
       smg[h] = 0.0f;
     }
   }
-  for (int g = 0; g < BR_WAVE; ++g) {  // workers beyond G and offsets beyond H read as "no worker"
+  for (int g = 0; g < LS; ++g) {  // a column beyond G and offsets beyond H read as "no worker"
     for (int h0 = 0; h0 < HS; h0 += BR_WAVE) {
       const int h = h0 + lane;
-      if (h < HS) sL[h * BR_LSTRIDE + g] = (g < G && h < H1) ? p.Lh[((int64_t)inst * G + g) * H1 + h] : BR_LOW;
+      if (h < HS) sL[h * LS + g] = (g < G && h < H1) ? p.Lh[((int64_t)inst * G + g) * H1 + h] : BR_LOW;
     }
   }
   int S_tot = br_wave_sum(cap);
@@ -126,7 +128,7 @@ __global__ __launch_bounds__(64) void br_k_assign_long(BrParams p, BrArr a, BrOu
     const int ag = __builtin_amdgcn_readlane(add, g);
     for (int h0 = 0; h0 < H1; h0 += BR_WAVE) {
       const int h = h0 + lane;
-      if (h < H1) smg[h] = (float)max(sM[h] - (sL[h * BR_LSTRIDE + g] + ag), 0);
+      if (h < H1) smg[h] = (float)max(sM[h] - (sL[h * LS + g] + ag), 0);
     }
     br_wave_sync();
   };
@@ -134,11 +136,11 @@ __global__ __launch_bounds__(64) void br_k_assign_long(BrParams p, BrArr a, BrOu
   // horizon-min margin of the worker each lane holds
   auto lane_minm = [&]() {  // four offsets per trip (padded offsets: envelope 0 against "no worker")
     int mn = INT32_MAX;
-    const int *row = sL + lane;
+    const int *row = sL + min(lane, LS - 1);  // lanes that hold no worker read the last column (their result is never used)
     for (int h = 0; h < HS; h += 4) {
       const int4 M4 = *reinterpret_cast<const int4 *>(sM + h);
-      const int l0 = row[(h + 0) * BR_LSTRIDE], l1 = row[(h + 1) * BR_LSTRIDE];
-      const int l2 = row[(h + 2) * BR_LSTRIDE], l3 = row[(h + 3) * BR_LSTRIDE];
+      const int l0 = row[(h + 0) * LS], l1 = row[(h + 1) * LS];
+      const int l2 = row[(h + 2) * LS], l3 = row[(h + 3) * LS];
       mn = min(mn, min(min(M4.x - l0, M4.y - l1), min(M4.z - l2, M4.w - l3)));
     }
     return max(mn - add, 0);  // min_h (M_h - sL_h) - add, clamped once: the same as clamping every offset
@@ -194,7 +196,7 @@ __global__ __launch_bounds__(64) void br_k_assign_long(BrParams p, BrArr a, BrOu
     const int ag = __builtin_amdgcn_readlane(add, g);
     for (int h0 = 0; h0 < H1; h0 += BR_WAVE) {
       const int h = h0 + lane;
-      if (h < H1) sM[h] = max(sM[h], sL[h * BR_LSTRIDE + g] + ag);
+      if (h < H1) sM[h] = max(sM[h], sL[h * LS + g] + ag);
     }
     br_wave_sync();
     cap -= (lane == g) ? k : 0;
@@ -492,7 +494,7 @@ __global__ __launch_bounds__(64) void br_k_assign_long(BrParams p, BrArr a, BrOu
 template <int E>
 static void br_launch_assign_long_one(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st) {
   const int HS = BR_HS(p.H);
-  const size_t lds = ((size_t)3 * E * BR_WAVE + BR_WAVE + 3 * (size_t)HS + (((size_t)HS * BR_LSTRIDE + 3) & ~(size_t)3) +
+  const size_t lds = ((size_t)3 * E * BR_WAVE + BR_WAVE + 3 * (size_t)HS + (((size_t)HS * BR_LSTRIDE(p.G) + 3) & ~(size_t)3) +
                       (p.R_max > 8 ? 1024 : 0)) * sizeof(int);
   const dim3 grid((unsigned)p.N), block(BR_WAVE);
   if (p.adv_t > 0)

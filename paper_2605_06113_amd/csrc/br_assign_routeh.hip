@@ -9,12 +9,10 @@ __global__ __launch_bounds__(256, E == 8 ? 4 : 1) void br_k_route_h(BrParams p, 
   extern __shared__ int lds_all[];
   const int w = threadIdx.x >> 6, inst = (int)blockIdx.x * 4 + w;
   if (inst >= p.N) return;
-  {
-    BrScoreIn<E, true> in;
-    br_score_wave_load<E, true>(p, a, inst, br_lane(), in);
-    br_score_wave_run<E, true>(p, o, inst, br_lane(), in);
-  }
-  br_assign_body<E, true, ADV>(p, a, o, lds_all + w * (3 * E * BR_WAVE + BR_WAVE + 8), inst);
+  BrScoreIn<E, true> in;  // queue lengths, prefill lengths and counts are loaded once, for both parts
+  br_score_wave_load<E, true>(p, a, inst, br_lane(), in);
+  br_score_wave_run<E, true>(p, o, inst, br_lane(), in);
+  br_assign_body<E, true, ADV>(p, a, o, lds_all + w * (3 * E * BR_WAVE + BR_WAVE + 8), inst, 0, &in);
 }
 
 template <int E>

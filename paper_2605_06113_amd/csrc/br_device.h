@@ -100,6 +100,37 @@ __device__ __forceinline__ int br_wave_sum(int x) {
   return __builtin_amdgcn_readlane(x, 63);
 }
 
+// Reductions over one row of 16 lanes (lanes 0..15 of the wave: clusters of up to 16 workers keep all of them
+// there): four butterfly steps leave the row's result in each of its lanes, two DPP steps and a bubble less than
+// the wave-wide forms.  What the other rows hold does not matter.
+__device__ __forceinline__ int br_row0_max(int x) {
+  x = max(x, br_dpp<0xB1, 0xF, true>(0, x));
+  x = max(x, br_dpp<0x4E, 0xF, true>(0, x));
+  x = max(x, br_dpp<0x141, 0xF, true>(0, x));
+  x = max(x, br_dpp<0x140, 0xF, true>(0, x));
+  return __builtin_amdgcn_readlane(x, 0);
+}
+
+__device__ __forceinline__ int br_row0_min(int x) {
+  x = min(x, br_dpp<0xB1, 0xF, true>(0, x));
+  x = min(x, br_dpp<0x4E, 0xF, true>(0, x));
+  x = min(x, br_dpp<0x141, 0xF, true>(0, x));
+  x = min(x, br_dpp<0x140, 0xF, true>(0, x));
+  return __builtin_amdgcn_readlane(x, 0);
+}
+
+// Number of lanes of the caller's row of 16 whose key is below the caller's (keys of one row pairwise
+// distinct, or INT32_MAX for lanes that do not take part): fifteen row rotations, no scalar traffic.
+template <int K>
+__device__ __forceinline__ int br_row_rank_step(int key, int acc) {
+  const int other = __builtin_amdgcn_update_dpp(0, key, 0x120 + K, 0xF, 0xF, false);  // row_ror:K
+  acc += other < key ? 1 : 0;
+  if constexpr (K < 15) return br_row_rank_step<K + 1>(key, acc);
+  else return acc;
+}
+
+__device__ __forceinline__ int br_row_rank(int key) { return br_row_rank_step<1>(key, 0); }
+
 __device__ __forceinline__ unsigned long long br_ballot(bool p) { return __builtin_amdgcn_ballot_w64(p); }
 
 __device__ __forceinline__ int br_lane() { return (int)(threadIdx.x & 63u); }

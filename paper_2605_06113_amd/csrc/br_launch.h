@@ -34,3 +34,7 @@ void br_launch_bypass(const BrParams &p, const BrArr &a, const BrOut &o, hipStre
 // comparison policies (Random, RR, P2C, JSQ): FIFO dispatch of the waiting queue, BR-0 contexts
 void br_launch_baseline(const BrParams &p, const BrArr &a, const BrOut &o, int *pol, int policy, unsigned long long seed,
                         hipStream_t st);
+// BR-0 with decode steps, queues of up to 512, windows of up to 8: round and decode steps on two waves per cluster;
+// the snapshot reductions (best_g / best_i, when asked for without the matrix) ride on the helper wave
+bool br_split_serves(const BrParams &p);
+void br_launch_route_split(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st);

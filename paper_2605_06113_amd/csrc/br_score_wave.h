@@ -12,7 +12,8 @@
 template <int E, bool BRH>
 struct BrScoreIn {
   static constexpr int NH = BRH ? BR_HP + 1 : 1;
-  int qn, L, cap;
+  int qn, q0, cnt, L, cap, n;  // queue length with and without this round's arrivals, arrivals taken; lane g: load,
+                               // free slots and request count of worker g as stored
   int m[NH];  // BR-H: margins of the step-start projection; BR-0: filled by br_score_wave_run
   int s[E];
 };
@@ -24,11 +25,14 @@ __device__ __forceinline__ void br_score_wave_load(const BrParams &p, const BrAr
   int cnt = a.count ? a.count[inst] : 0;
   cnt = br_uniform(min(max(cnt, 0), a.arr_cap));
   in.qn = q0 + min(cnt, p.Q - q0);
+  in.q0 = q0;
+  in.cnt = cnt;
   const int64_t qrow = (int64_t)inst * p.Q, arow = (int64_t)inst * a.arr_cap;
   const bool act = lane < p.G;
   const int64_t wrow = (int64_t)inst * p.G + lane;
   in.L = act ? p.L[wrow] : BR_LOW;
-  in.cap = act ? p.B - p.n[wrow] : 0;
+  in.n = act ? p.n[wrow] : p.B;
+  in.cap = act ? p.B - in.n : 0;
   if constexpr (BRH) {
 #pragma unroll
     for (int h = 0; h < BrScoreIn<E, BRH>::NH; ++h) in.m[h] = (act && h <= p.H) ? p.mh[wrow * (p.H + 1) + h] : 0;
