@@ -467,6 +467,80 @@ __global__ __launch_bounds__(512) void br_k_score(BrParams p, BrArr a, BrOut o, 
   }
 }
 
+// K2 with the matrix materialised: every (waiting request, worker) score of the step-start snapshot written to
+// HBM, request-major (F[inst][i][g]), and nothing else: the reductions run as their own launch without it.
+// An HBM-write stream: one block per cluster; margins and prefill lengths are staged in LDS once, then every
+// thread computes the four scores of one 16-byte store straight in the output's layout (element e of the
+// cluster's rows is request e / G, worker e % G, by a multiply-high with the rounded-up reciprocal of G, exact for
+// e < 2^17), so the matrix leaves in full-width contiguous stores and no tile is staged.  Rows at or beyond the
+// queue length are left untouched.
+template <bool BRH, bool LONG>
+__global__ __launch_bounds__(256) void br_k_score_matrix(BrParams p, BrArr a, BrOut o, unsigned recip_g) {
+  extern __shared__ int lds[];
+  const int G = p.G;
+  const int HS = LONG ? BR_HS(p.H) : BR_HP + 1;
+  int *sm = lds;                                   // [G][HS] margins (LONG: as floats)
+  float *sd = (float *)(sm + G * HS);              // LONG: [HS + 4] discounts
+  int *ss = sm + G * HS + (LONG ? HS + 4 : 0);     // [Q] prefill lengths
+  int *sL = ss + p.Q;                              // [G] loads (BR-0)
+  const int inst = blockIdx.x, tid = threadIdx.x;
+  const int q0 = min(max(p.qlen[inst], 0), p.Q);
+  int cnt = a.count ? a.count[inst] : 0;
+  cnt = min(max(cnt, 0), a.arr_cap);
+  const int qn = q0 + min(cnt, p.Q - q0);
+  if (!BRH && tid < G) sL[tid] = p.L[(int64_t)inst * G + tid];
+  for (int e = tid; e < G * HS; e += blockDim.x) {
+    const int g = e / HS, h = e - g * HS;
+    const int m = (BRH && h <= p.H) ? p.mh[((int64_t)inst * G + g) * (p.H + 1) + h] : 0;
+    sm[e] = LONG ? __float_as_int((float)m) : m;
+  }
+  if constexpr (LONG)
+    for (int h = tid; h < HS + 4; h += blockDim.x) sd[h] = h < HS ? p.dl[h] : 0.0f;
+  for (int i = tid; i < qn; i += blockDim.x) {
+    const int s = i < q0 ? p.qs[(int64_t)inst * p.Q + i] : a.s[(int64_t)inst * a.arr_cap + (i - q0)];
+    ss[i] = min(max(s, 1), BR_MAX_S_DEV);
+  }
+  __syncthreads();
+  if (!BRH) {  // M(k) = max_g L_g, m_g = M - L_g
+    if (tid < G) {
+      int M = sL[0];
+      for (int g = 1; g < G; ++g) M = max(M, sL[g]);
+      sm[tid * HS] = M - sL[tid];
+    }
+    __syncthreads();
+  }
+  int *Fi = (int *)o.F + (int64_t)inst * p.Q * G;   // 16-byte aligned: Q * G * 4 bytes per cluster with Q * G % 4 == 0 or a scalar tail
+  const int total = qn * G;
+  auto score_at = [&](int e) -> int {
+    const int i = G == 1 ? e : (int)__umulhi((unsigned)e, recip_g), g = e - i * G;
+    int key;
+    if constexpr (LONG) {
+      const int dv[1] = {ss[i]};
+      float Fv[1];
+      br_scoreh_long<1>(p.aD, p.beta, (const float *)(sm + g * HS), sd, HS, dv, Fv);
+      return __float_as_int(Fv[0]);
+    } else {
+      int m[BR_HP + 1];
+#pragma unroll
+      for (int h = 0; h <= BR_HP; ++h) m[h] = (BRH || h == 0) ? sm[g * (BR_HP + 1) + h] : 0;
+      key = br_score_key<BRH>(p, m, ss[i]);
+      return BRH ? __float_as_int(br_unord(key)) : key;
+    }
+  };
+  const bool vec = (((int64_t)inst * p.Q * G) & 3) == 0;   // the cluster's rows start on a 16-byte boundary
+  if (vec) {
+    for (int e = 4 * tid; e < total; e += 4 * blockDim.x) {
+      if (e + 3 < total) {
+        *reinterpret_cast<int4 *>(Fi + e) = make_int4(score_at(e), score_at(e + 1), score_at(e + 2), score_at(e + 3));
+      } else {
+        for (int k = e; k < total; ++k) Fi[k] = score_at(k);
+      }
+    }
+  } else {
+    for (int e = tid; e < total; e += blockDim.x) Fi[e] = score_at(e);
+  }
+}
+
 // K2 + K3 for a few clusters with long queues (single-instance serving): the block-per-cluster kernel above
 // leaves most of the chip idle and its two passes score every pair twice.  Here one wave takes a tile of 64
 // requests against a quarter of the workers (grid: tiles x 4 worker groups x clusters), scores each pair
@@ -740,7 +814,30 @@ hipError_t br_static_scratch_resolve(int **out) {
   return hipSuccess;
 }
 
+static void br_launch_reductions(const BrParams &p, const BrArr &a, const BrOut &o, int *partials, hipStream_t st);
+
 void br_launch_score(const BrParams &p, const BrArr &a, const BrOut &o, int *partials, hipStream_t st) {
+  if (o.F) {  // the matrix as a stream of its own; the reductions, if asked for, by whichever kernel serves the shape
+    const bool longh = p.H > BR_HP;
+    const size_t HS = longh ? BR_HS(p.H) : BR_HP + 1;
+    const size_t lds = ((size_t)p.G * HS + (longh ? HS + 4 : 0) + (size_t)p.Q + (size_t)p.G) * sizeof(int);
+    const unsigned recip = (unsigned)((0x100000000ull + (unsigned)p.G - 1u) / (unsigned)p.G);  // ceil(2^32 / G)
+    if (longh)
+      hipLaunchKernelGGL((br_k_score_matrix<true, true>), dim3((unsigned)p.N), dim3(256), lds, st, p, a, o, recip);
+    else if (p.H > 0)
+      hipLaunchKernelGGL((br_k_score_matrix<true, false>), dim3((unsigned)p.N), dim3(256), lds, st, p, a, o, recip);
+    else
+      hipLaunchKernelGGL((br_k_score_matrix<false, false>), dim3((unsigned)p.N), dim3(256), lds, st, p, a, o, recip);
+    if (!o.best_g && !o.best_i) return;
+    BrOut o2 = o;
+    o2.F = nullptr;
+    br_launch_reductions(p, a, o2, partials, st);
+    return;
+  }
+  br_launch_reductions(p, a, o, partials, st);
+}
+
+static void br_launch_reductions(const BrParams &p, const BrArr &a, const BrOut &o, int *partials, hipStream_t st) {
   int waves = (p.Q + 63) / 64;  // one wave per tile of 64 requests, at most 8 waves
   waves = waves < 1 ? 1 : (waves > 8 ? 8 : waves);
   const int want_tile = o.F != nullptr;
