@@ -541,7 +541,10 @@ def main():
     ap.add_argument("--two-calls", action="store_true",
                     help="time br_route_step + br_advance_decode instead of the fused br_route_advance")
     ap.add_argument("--no-two-calls-leg", action="store_true", help="skip the side measurement of the two-call step")
-    ap.add_argument("--no-brh", action="store_true", help="skip the batched BR-H side measurement")
+    ap.add_argument("--no-brh", action="store_true", help="skip the side legs")
+    ap.add_argument("--legs", default="all",
+                    help="comma-separated side legs to run (fmatrix,brh,brh_gate_off,h80,window16,window32,window32_all,bypass,"
+                         "replay,quality), default all")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (reference for scaling rocprofv3 byte counters)")
     ap.add_argument("--traffic-kib", type=float, default=None,
@@ -709,16 +712,18 @@ def main():
         res["two_calls"] = dict(entry="br_route_step + br_advance_decode", ms_per_step=e2 / K * 1e3,
                                 pairs_per_s=pairs_per_step * K / e2, kernels=kernel_table(k2, False))
     if not args.no_brh:
-        res["fmatrix"] = fmatrix_run(device, cfg, init, arr)
-        res["brh_batched"] = brh_run(device)
-        res["brh_batched_gate_off"] = brh_run(device, gate=0.0)   # hazards live: no request counts at the last offset
-        res["brh_batched_h80"] = brh_run(device, deployed=True)
-        res["window16"] = window_run(device)
-        res["window32"] = window_run(device, R_max=32)                       # reachable sums instead of masks
-        res["window32_all_stage2"] = window_run(device, R_max=32, S_greedy=512)
-        res["bypass"] = bypass_run(device, cfg, init, arr)
-        res["replay_batched"] = replay_run(device)
-        res["quality"] = quality_run(device)
+        legs = dict(fmatrix=lambda: fmatrix_run(device, cfg, init, arr), brh=lambda: brh_run(device),
+                    brh_gate_off=lambda: brh_run(device, gate=0.0),   # hazards live: no request counts at the last offset
+                    h80=lambda: brh_run(device, deployed=True), window16=lambda: window_run(device),
+                    window32=lambda: window_run(device, R_max=32),   # reachable sums instead of masks
+                    window32_all=lambda: window_run(device, R_max=32, S_greedy=512),
+                    bypass=lambda: bypass_run(device, cfg, init, arr), replay=lambda: replay_run(device),
+                    quality=lambda: quality_run(device))
+        keys = dict(brh="brh_batched", brh_gate_off="brh_batched_gate_off", h80="brh_batched_h80",
+                    window32_all="window32_all_stage2", replay="replay_batched")
+        want = list(legs) if args.legs == "all" else [x for x in args.legs.split(",") if x]
+        for name in want:
+            res[keys.get(name, name)] = legs[name]()
     if args.latency_steps > 0:
         res["latency"] = latency_run(args.latency_steps, device)
         res["latency_c1"] = c1_latency(device)
