@@ -299,8 +299,9 @@ static int32_t route(br_ctx *ctx, const br_arrivals *in, const br_step_out *out,
     o.best_i = out->best_i;
   }
   BrParams p = ctx->p;
-  // windows beyond 8 requests have no fused instantiation: the decode steps follow as their own launch
-  const bool split_adv = adv_t > 0 && p.R_max > 8;
+  // windows beyond 8 requests and long-horizon rounds shared by several waves have no fused instantiation: the
+  // decode steps follow as their own launch
+  const bool split_adv = adv_t > 0 && (p.R_max > 8 || (p.H > BR_HP && br_long_waves(p) > 1));
   p.adv_t = split_adv ? 0 : adv_t;
   int32_t rc = BR_OK;
   if (p.H > 0) rc = enqueue(ctx, BR_K_PROJECT, [&] { br_launch_project(p, ctx->st); }, br);

@@ -21,6 +21,14 @@
 //     whose margins no request in question reaches (exact zeros; br_long_active, br_scoreh_long_act).
 // Waiting set, sticky binding, epilogue and the optional decode steps are those of the short-horizon
 // kernel (br_sort.h, br_assign_common.h).
+//
+// With fewer clusters than the chip has room for waves (NW = 2 or 4 waves per cluster) the search
+// argmax_i F_g({i}), which is most of a round at these horizons, is shared: wave 0 runs the round; for each
+// search it posts the admissible length and the alive bits in LDS (the margins are there already), every wave
+// scores its share of the sorted positions between two block barriers, and wave 0 takes the best of the
+// partial results (the share of a later wave holds higher positions, so only a strictly better score wins).
+// The helper waves leave when wave 0 posts the end of the round; decode steps then follow as a launch of
+// their own.
 #include "br_device.h"
 #include "br_launch.h"
 #include "br_sort.h"
@@ -28,8 +36,50 @@
 
 #define BR_LSTRIDE(G) ((G) | 1)  // words between offsets in sL (odd; one spare "no worker" column when G is even)
 
-template <int E, bool ADV>
-__global__ __launch_bounds__(64) void br_k_assign_long(BrParams p, BrArr a, BrOut o) {
+// Best (score key, sorted position) among the alive, admissible requests of NB blocks of 64 sorted positions
+// (block jb + j in sv[J0 + j], alive bit J0 + j), lowest position on equal scores.  The longest alive request of
+// a block is its first alive one: offsets whose margin it does not reach add nothing for any request of the
+// block and are skipped for that block.
+template <int NS, int J0, int NB>
+__device__ __forceinline__ void br_long_slice_best(const BrParams &p, const float *smg, const float *sd, int HS, int lane,
+                                                   int qn, const int (&sv)[NS], unsigned alive, int jb, int room, int &bk,
+                                                   int &bp) {
+  constexpr int NV = NB >= 4 ? 4 : NB;
+  bk = BR_KEY_NONE, bp = INT32_MAX;
+#pragma unroll
+  for (int c = 0; c < NB; c += NV) {
+    if ((jb + c) * BR_WAVE < qn) {
+      int top[NV], dv[NV];
+      int any = 0;
+#pragma unroll
+      for (int u = 0; u < NV; ++u) {
+        const unsigned long long bal = br_ballot((alive >> (J0 + c + u)) & 1u);
+        const int first = __builtin_amdgcn_readlane(sv[J0 + c + u], bal != 0ull ? (int)__builtin_ctzll(bal) : 0);
+        top[u] = bal != 0ull ? first : 0;
+        dv[u] = sv[J0 + c + u];
+        any |= top[u];
+      }
+      if (any == 0) continue;
+      float Fv[NV];
+      br_scoreh_long_sel<NV>(p.aD, p.beta, smg, sd, HS, lane, top, dv, Fv);
+#pragma unroll
+      for (int u = 0; u < NV; ++u) {
+        const bool ok = ((alive >> (J0 + c + u)) & 1u) && dv[u] <= room;
+        const int key = ok ? br_ord(Fv[u]) : BR_KEY_NONE;
+        if (key > bk) {  // positions rise with the block within a lane: the first best stays
+          bk = key;
+          bp = (jb + c + u) * BR_WAVE + lane;
+        }
+      }
+    }
+  }
+}
+
+template <int E, bool ADV, int NW>
+__global__ __launch_bounds__(64 * NW) void br_k_assign_long(BrParams p, BrArr a, BrOut o) {
+  static_assert(NW == 1 || !ADV, "decode steps ride along only with one wave per cluster");
+  static_assert(E % NW == 0, "every wave takes whole blocks of 64 sorted positions");
+  constexpr int EW = E / NW;  // blocks of 64 sorted positions per wave in a shared search
   extern __shared__ int lds[];
   constexpr int NP = E * BR_WAVE;
   constexpr int IDX_MASK = (1 << BR_IDX_BITS) - 1;
@@ -41,12 +91,15 @@ __global__ __launch_bounds__(64) void br_k_assign_long(BrParams p, BrArr a, BrOu
   int *who = lds + 2 * NP;          // [NP] by arrival position: worker, or -1
   int *win = lds + 3 * NP;          // [64] Stage-1 level: k-th alive request (s << 11 | sorted position);
                                     //      Stage 2: the candidate window, same packing (16-byte aligned)
-  int *sM = win + BR_WAVE;          // [HS] envelope M_h
+  int *pm = win + BR_WAVE;          // [64] partial horizon-min margins (offsets split over the lanes)
+  int *sM = pm + BR_WAVE;           // [HS] envelope M_h
   float *smg = (float *)(sM + HS);  // [HS] margins of the worker in hand, as floats
   float *sd = smg + HS;             // [HS] discounts, zero beyond H
   const int LS = BR_LSTRIDE(p.G);
   int *sL = sM + 3 * HS;            // [HS][LS] step-start projections (rows beyond H: "no worker")
   int *hitab = sL + ((HS * LS + 3) & ~3);  // R_max > 8: [1024] sums of window entries 6.. by upper mask bits
+  int *mbox = hitab + (p.R_max > 8 ? 1024 : 0);  // NW > 1: [16] search mailbox: command, admissible length; results from word 4
+  int *salive = pm;                 // NW > 1: alive words of the lanes of wave 0 during a search (pm is idle then)
 
   const int lane = br_lane();
   const int G = p.G;
@@ -55,6 +108,29 @@ __global__ __launch_bounds__(64) void br_k_assign_long(BrParams p, BrArr a, BrOu
   cnt = br_uniform(min(max(cnt, 0), a.arr_cap));
   const int qn = q0 + min(cnt, p.Q - q0);
   const int64_t qrow = (int64_t)inst * p.Q, arow = (int64_t)inst * a.arr_cap;
+
+  if constexpr (NW > 1) {
+    const int w = (int)(threadIdx.x >> 6);
+    if (w != 0) {  // serves wave 0's searches: every wave of the block meets at both barriers of each, wave 0 ends the loop
+      __syncthreads();  // the sorted keys and the discounts are in LDS
+      int svh[EW];
+#pragma unroll
+      for (int j = 0; j < EW; ++j) svh[j] = skey[(w * EW + j) * BR_WAVE + lane] >> BR_IDX_BITS;
+      for (;;) {
+        __syncthreads();
+        if (mbox[0] == 0) break;
+        const int roomq = mbox[1];
+        const unsigned al = (unsigned)salive[lane] >> (w * EW);
+        int bk, bp;
+        br_long_slice_best<EW, 0, EW>(p, smg, sd, HS, lane, qn, svh, al, w * EW, roomq, bk, bp);
+        const int km = br_wave_max(bk);
+        const int pmn = km == BR_KEY_NONE ? INT32_MAX : br_wave_min(bk == km ? bp : INT32_MAX);
+        if (lane == 0) mbox[4 + 2 * w] = km, mbox[5 + 2 * w] = pmn;
+        __syncthreads();
+      }
+      return;
+    }
+  }
 
   float c0 = 0.0f;  // first estimate of a newly admitted request when the library maintains c_hat
   if (p.pred_mode == 2) c0 = br_survival(p, 0);
@@ -119,6 +195,7 @@ __global__ __launch_bounds__(64) void br_k_assign_long(BrParams p, BrArr a, BrOu
     if (pos < qn) alive |= 1u << j;
   }
   br_wave_sync();
+  if constexpr (NW > 1) __syncthreads();  // the helper waves read their share of the sorted keys
 
   int n_alive = qn;
   int stage1 = 0, pops = 0, guard = 0, wdrop = 0, admitted = 0;
@@ -133,15 +210,26 @@ __global__ __launch_bounds__(64) void br_k_assign_long(BrParams p, BrArr a, BrOu
     br_wave_sync();
   };
 
-  // horizon-min margin of the worker each lane holds
-  auto lane_minm = [&]() {  // four offsets per trip (padded offsets: envelope 0 against "no worker")
+  // horizon-min margin of the worker each lane holds.  With few workers the offsets are split over the lanes:
+  // lane c * GP + g takes every C-th group of four offsets of worker g (GP = workers rounded up to a power of
+  // two, C = 64 / GP), the partial minima meet in LDS.  Padded offsets: envelope 0 against "no worker".
+  const int GP = G <= 8 ? 8 : G <= 16 ? 16 : G <= 32 ? 32 : 64;
+  const int C = BR_WAVE / GP;
+  auto lane_minm = [&]() {
+    const int g = lane & (GP - 1), c = lane / GP;
     int mn = INT32_MAX;
-    const int *row = sL + min(lane, LS - 1);  // lanes that hold no worker read the last column (their result is never used)
-    for (int h = 0; h < HS; h += 4) {
+    const int *row = sL + min(g, LS - 1);  // lanes that stand for no worker read the last column (their result is never used)
+    for (int h = 4 * c; h < HS; h += 4 * C) {
       const int4 M4 = *reinterpret_cast<const int4 *>(sM + h);
       const int l0 = row[(h + 0) * LS], l1 = row[(h + 1) * LS];
       const int l2 = row[(h + 2) * LS], l3 = row[(h + 3) * LS];
       mn = min(mn, min(min(M4.x - l0, M4.y - l1), min(M4.z - l2, M4.w - l3)));
+    }
+    if (C > 1) {
+      pm[lane] = mn;
+      br_wave_sync();
+      for (int cc = 0; cc < C; ++cc) mn = min(mn, pm[cc * GP + g]);
+      br_wave_sync();
     }
     return max(mn - add, 0);  // min_h (M_h - sL_h) - add, clamped once: the same as clamping every offset
   };
@@ -149,35 +237,34 @@ __global__ __launch_bounds__(64) void br_k_assign_long(BrParams p, BrArr a, BrOu
   // argmax_i F_g({i}) over alive, admissible requests against the margins in smg (lowest sorted
   // position on ties); false when no request is admissible
   auto pick_single = [&](int room, int &pos, int &swin) -> bool {
-    int smax = 0;  // the longest request in question: offsets whose margin it does not reach add nothing
+    int bk, bp, km;
+    if constexpr (NW > 1) {
+      mbox[1] = room;
+      salive[lane] = (int)alive;
+      mbox[0] = 1;
+      __syncthreads();
+      br_long_slice_best<E, 0, EW>(p, smg, sd, HS, lane, qn, sv, alive, 0, room, bk, bp);
+      km = br_wave_max(bk);
+      pos = km == BR_KEY_NONE ? INT32_MAX : br_wave_min(bk == km ? bp : INT32_MAX);
+      __syncthreads();
 #pragma unroll
-    for (int j = 0; j < E; ++j) smax = max(smax, (((alive >> j) & 1u) && sv[j] <= room) ? sv[j] : 0);
-    smax = br_wave_max(smax);
-    if (smax == 0) return false;
-    unsigned long long act[3];
-    br_long_active(smg, HS, lane, smax, act);
-    int bk = BR_KEY_NONE, bp = INT32_MAX;
-#pragma unroll
-    for (int j0 = 0; j0 < E; j0 += 4) {
-      if (j0 * BR_WAVE < qn) {
-        const int dv[4] = {sv[j0], sv[j0 + 1], sv[j0 + 2], sv[j0 + 3]};
-        float Fv[4];
-        br_scoreh_long_act<4>(p.aD, p.beta, smg, sd, act, dv, Fv);
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const int j = j0 + u;
-          const bool ok = ((alive >> j) & 1u) && dv[u] <= room;
-          const int key = ok ? br_ord(Fv[u]) : BR_KEY_NONE;
-          if (key > bk) {  // positions rise with j within a lane: the first best stays
-            bk = key;
-            bp = j * BR_WAVE + lane;
-          }
-        }
+      for (int u = 1; u < NW; ++u) {
+        const int ku = mbox[4 + 2 * u], pu = mbox[5 + 2 * u];
+        if (ku > km) km = ku, pos = pu;  // positions of wave u lie above those of the waves before it
       }
+      if (km == BR_KEY_NONE) return false;
+    } else {
+      if (p.W > 0) {  // under the watermark the longest alive requests may all be out of the question
+        int smax = 0;
+#pragma unroll
+        for (int j = 0; j < E; ++j) smax = max(smax, (((alive >> j) & 1u) && sv[j] <= room) ? sv[j] : 0);
+        if (br_wave_max(smax) == 0) return false;
+      }
+      br_long_slice_best<E, 0, E>(p, smg, sd, HS, lane, qn, sv, alive, 0, room, bk, bp);
+      km = br_wave_max(bk);
+      if (km == BR_KEY_NONE) return false;
+      pos = br_wave_min(bk == km ? bp : INT32_MAX);
     }
-    const int km = br_wave_max(bk);
-    if (km == BR_KEY_NONE) return false;
-    pos = br_wave_min(bk == km ? bp : INT32_MAX);
     swin = br_uniform(skey[pos] >> BR_IDX_BITS);
     return true;
   };
@@ -292,6 +379,22 @@ __global__ __launch_bounds__(64) void br_k_assign_long(BrParams p, BrArr a, BrOu
 #pragma unroll
     for (int b = 0; b < 6; ++b) lbit[b] = (lane >> b) & 1;
     const int lpop = __builtin_popcount(lane);
+    // Certain guard: eq. (brh-Fscore) is concave in Delta with F(0) = 0, so F(Delta) <= F(s) Delta / s for every
+    // Delta >= s, and every subset of the window sums to at least the window's smallest entry s.  Scores are
+    // compared as computed in fp32: one evaluation has at most H + 5 roundings, each relative 2^-24 on terms
+    // bounded by (alpha D + beta D) Delta, so a computed score differs from the exact one by at most
+    // e(Delta) = (H + 5) 2^-24 (alpha D + beta D) Delta.  If the smallest entry's computed score is at or below
+    // -2.5 e(s), its exact score is below -1.5 e(s), every subset's exact score below -1.5 e(Delta) and every
+    // subset's computed score below zero: the pop goes to the starvation guard without the enumeration.
+    float guard_eps;
+    {
+      float Dsum = 0.0f;
+      for (int h = 0; h < HS; h += 4) {
+        const float4 q = *reinterpret_cast<const float4 *>(sd + h);
+        Dsum += (q.x + q.y) + (q.z + q.w);
+      }
+      guard_eps = 2.5f * (float)(p.H + 5) * 5.9604645e-8f * (p.aD + p.beta * Dsum);
+    }
     for (int it = 0; it < bound; ++it) {
       if (n_alive <= 0) break;
       const int capmax = br_wave_max(cap);
@@ -325,7 +428,16 @@ __global__ __launch_bounds__(64) void br_k_assign_long(BrParams p, BrArr a, BrOu
       const int nmask = 1 << w;
       int bestmask = 0, bestkey = BR_KEY_NONE;
       int wv[8], ws[8];
-      if (p.R_max > 8) {
+      bool guard_sure;
+      {
+        const int s_last[1] = {br_uniform(win[w - 1] >> BR_IDX_BITS)};
+        float F1[1];
+        br_scoreh_long_sel<1>(p.aD, p.beta, smg, sd, HS, lane, s_last, s_last, F1);
+        guard_sure = F1[0] <= -guard_eps * (float)s_last[0];
+      }
+      if (guard_sure) {
+        br_wave_sync();  // the window has been read before a later pop rewrites it
+      } else if (p.R_max > 8) {
         // Windows of up to 16 requests: lane l keeps the lower six mask bits, the upper bits run as passes
         // over a table of their partial sums (built here, 64 entries per step), four passes per trip; trips
         // whose upper bits alone exceed the cardinality limit are skipped.  A lane sees its masks in ascending
@@ -479,6 +591,10 @@ __global__ __launch_bounds__(64) void br_k_assign_long(BrParams p, BrArr a, BrOu
     }
   }
   br_wave_sync();
+  if constexpr (NW > 1) {
+    mbox[0] = 0;  // the round is over: the helper waves leave
+    __syncthreads();
+  }
 
   BrRoundCounts rc;
   rc.admitted = admitted;
@@ -491,16 +607,28 @@ __global__ __launch_bounds__(64) void br_k_assign_long(BrParams p, BrArr a, BrOu
   if constexpr (ADV) br_advance_cluster<4, true>(inst, lane, Lcur, nn);
 }
 
+// Waves per cluster: as many as still leave every cluster of the batch resident at once (registers allow about
+// 4 / 3 / 2 / 1 waves per SIMD for queues of up to 256 / 512 / 1024 / 2048 on 1024 SIMDs).
+int br_long_waves(const BrParams &p) {
+  const long long room = 1024ll * (p.Q <= 256 ? 4 : p.Q <= 512 ? 3 : p.Q <= 1024 ? 2 : 1);
+  return (long long)p.N * 4 <= room ? 4 : (long long)p.N * 2 <= room ? 2 : 1;
+}
+
 template <int E>
 static void br_launch_assign_long_one(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st) {
   const int HS = BR_HS(p.H);
-  const size_t lds = ((size_t)3 * E * BR_WAVE + BR_WAVE + 3 * (size_t)HS + (((size_t)HS * BR_LSTRIDE(p.G) + 3) & ~(size_t)3) +
-                      (p.R_max > 8 ? 1024 : 0)) * sizeof(int);
-  const dim3 grid((unsigned)p.N), block(BR_WAVE);
-  if (p.adv_t > 0)
-    hipLaunchKernelGGL((br_k_assign_long<E, true>), grid, block, lds, st, p, a, o);
+  const int nw = br_long_waves(p);
+  const size_t lds = ((size_t)3 * E * BR_WAVE + 2 * BR_WAVE + 3 * (size_t)HS + (((size_t)HS * BR_LSTRIDE(p.G) + 3) & ~(size_t)3) +
+                      (p.R_max > 8 ? 1024 : 0) + (nw > 1 ? 16 : 0)) * sizeof(int);
+  const dim3 grid((unsigned)p.N), block(BR_WAVE * nw);
+  if (nw == 4)
+    hipLaunchKernelGGL((br_k_assign_long<E, false, 4>), grid, block, lds, st, p, a, o);
+  else if (nw == 2)
+    hipLaunchKernelGGL((br_k_assign_long<E, false, 2>), grid, block, lds, st, p, a, o);
+  else if (p.adv_t > 0)
+    hipLaunchKernelGGL((br_k_assign_long<E, true, 1>), grid, block, lds, st, p, a, o);
   else
-    hipLaunchKernelGGL((br_k_assign_long<E, false>), grid, block, lds, st, p, a, o);
+    hipLaunchKernelGGL((br_k_assign_long<E, false, 1>), grid, block, lds, st, p, a, o);
 }
 
 void br_launch_assign_long(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st) {

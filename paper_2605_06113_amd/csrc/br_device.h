@@ -267,6 +267,59 @@ __device__ __forceinline__ void br_scoreh_long_act(float aD, float beta, const f
   for (int v = 0; v < NV; ++v) F[v] = __fsub_rn(__fmul_rn(aD, fd[v]), __fmul_rn(beta, pen[v]));
 }
 
+// The same walk with a bound per value: value v is known not to exceed bound[v] (0: the value is not in
+// question and its result is not used).  A four-offset group whose margins all lie at or above bound[v] adds
+// exact zeros to value v's penalty and is skipped for that value alone, so a lane that holds a long and a short
+// request pays the long walk only for the long one.  Lanes stand for groups when the masks are formed (one
+// 16-byte read each); the groups in use are then walked in ascending order with margins and discounts
+// broadcast, the next group requested before the current one is used.  Every lane of the wave must call with
+// the same bounds.  Results are the bits of the full walk.
+template <int NV>
+__device__ __forceinline__ void br_scoreh_long_sel(float aD, float beta, const float *m, const float *d, int HS, int lane,
+                                                   const int (&bound)[NV], const int (&delta)[NV], float (&F)[NV]) {
+  float pen[NV], fd[NV];
+  unsigned long long gm[NV], u = 0ull;
+  {
+    const bool in = lane * 4 < HS;  // HS <= 132: at most 33 groups
+    const float4 q = *reinterpret_cast<const float4 *>(m + (in ? lane * 4 : 0));
+    const float lo = fminf(fminf(q.x, q.y), fminf(q.z, q.w));
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+      pen[v] = 0.0f, fd[v] = (float)delta[v];
+      gm[v] = br_ballot(in && lo < (float)bound[v]);
+      u |= gm[v];
+    }
+  }
+  if (u != 0ull) {
+    int k = (int)__builtin_ctzll(u);
+    u &= u - 1ull;
+    float4 m4 = *reinterpret_cast<const float4 *>(m + 4 * k);
+    float4 d4 = *reinterpret_cast<const float4 *>(d + 4 * k);
+    for (;;) {
+      const bool more = u != 0ull;
+      const int kn = more ? (int)__builtin_ctzll(u) : k;
+      u &= u - 1ull;  // (u == 0 stays 0)
+      const float4 mn = *reinterpret_cast<const float4 *>(m + 4 * kn);
+      const float4 dn = *reinterpret_cast<const float4 *>(d + 4 * kn);
+#pragma unroll
+      for (int v = 0; v < NV; ++v) {
+        if ((gm[v] >> k) & 1ull) {
+          pen[v] = __fadd_rn(pen[v], __fmul_rn(d4.x, fmaxf(__fsub_rn(fd[v], m4.x), 0.0f)));
+          pen[v] = __fadd_rn(pen[v], __fmul_rn(d4.y, fmaxf(__fsub_rn(fd[v], m4.y), 0.0f)));
+          pen[v] = __fadd_rn(pen[v], __fmul_rn(d4.z, fmaxf(__fsub_rn(fd[v], m4.z), 0.0f)));
+          pen[v] = __fadd_rn(pen[v], __fmul_rn(d4.w, fmaxf(__fsub_rn(fd[v], m4.w), 0.0f)));
+        }
+      }
+      if (!more) break;
+      k = kn;
+      m4 = mn;
+      d4 = dn;
+    }
+  }
+#pragma unroll
+  for (int v = 0; v < NV; ++v) F[v] = __fsub_rn(__fmul_rn(aD, fd[v]), __fmul_rn(beta, pen[v]));
+}
+
 template <bool BRH>
 __device__ __forceinline__ int br_score_key(const BrParams &p, const int (&m)[BR_HP + 1], int delta) {
   if constexpr (BRH) return br_ord(br_scoreh(p, m, delta));
@@ -278,25 +331,32 @@ __device__ __forceinline__ int br_score_key(const BrParams &p, const int (&m)[BR
 // p_fin = (F(a+H) - F(a)) / (1 - F(a)), mu_rem = mean of (o_j - a) over a < o_j <= a+H, then the
 // composite, gate, floor and clip of eq. (composite) / "Refresh logic".  All counts and the sum of
 // remainders are exact integers below 2^24, so each quotient is one correctly rounded division.
-__device__ __forceinline__ int br_hist_rank(const BrParams &p, int x) {
-  int lo = 0, hi = p.hist_n;
-  while (lo < hi) {
-    const int mid = (lo + hi) >> 1;
-    if (p.hist[mid] <= x)
-      lo = mid + 1;
-    else
-      hi = mid;
+// Number of history entries <= x[q], NQ look-ups side by side: a fixed number of halving steps (set by the
+// history length alone, the same on every lane), each with the NQ loads in flight together, so that the
+// latency of a step is paid once for all of them.
+template <int NQ>
+__device__ __forceinline__ void br_hist_ranks(const BrParams &p, const int (&x)[NQ], int (&r)[NQ]) {
+  const int n = p.hist_n;
+  int step = 1;
+  while (step <= n) step <<= 1;
+#pragma unroll
+  for (int q = 0; q < NQ; ++q) r[q] = 0;
+  for (step >>= 1; step > 0; step >>= 1) {
+    int v[NQ];
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) v[q] = p.hist[min(r[q] + step, n) - 1];
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) r[q] += (r[q] + step <= n && v[q] <= x[q]) ? step : 0;
   }
-  return lo;
 }
 
-__device__ __forceinline__ float br_survival(const BrParams &p, int age) {
+// the estimate from the two ranks lo = #{o_j <= age}, hi = #{o_j <= age + H} and the prefix sums at both
+__device__ __forceinline__ float br_survival_at(const BrParams &p, int age, int lo, int hi, long long sum_lo, long long sum_hi) {
   const float Hf = (float)p.H;
-  const int lo = br_hist_rank(p, age), hi = br_hist_rank(p, age + p.H);
   const int surv = p.hist_n - lo, cnt = hi - lo;
   float pf = 0.0f, mu = 0.0f;
   if (surv > 0 && cnt > 0) {
-    const long long rem_sum = (p.hsum[hi] - p.hsum[lo]) - (long long)cnt * age;
+    const long long rem_sum = (sum_hi - sum_lo) - (long long)cnt * age;
     pf = __fdiv_rn((float)cnt, (float)surv);
     mu = __fdiv_rn((float)(int)rem_sum, (float)cnt);
   }
@@ -305,6 +365,13 @@ __device__ __forceinline__ float br_survival(const BrParams &p, int age) {
   c = c < 1.0f ? 1.0f : c;
   c = c > Hf ? Hf : c;
   return c;
+}
+
+__device__ __forceinline__ float br_survival(const BrParams &p, int age) {
+  const int x[2] = {age, age + p.H};
+  int r[2];
+  br_hist_ranks<2>(p, x, r);
+  return br_survival_at(p, age, r[0], r[1], p.hsum[r[0]], p.hsum[r[1]]);
 }
 
 // Appendix "Refresh logic", for a request that stays active over t more generated tokens: per token
@@ -325,6 +392,60 @@ __device__ __forceinline__ void br_refresh_update(const BrParams &p, int t, floa
       }
     }
   }
+}
+
+// The same for the four requests a lane holds (`on`: the request stays active).  One generated token, the usual
+// decode step, is taken for all four together: the look-ups of the requests that query the estimator run side by
+// side (eight ranks per lane in flight) instead of one after the other.  Every lane of the wave must call.
+__device__ __forceinline__ void br_refresh_update4(const BrParams &p, int t, const bool (&on)[4], float (&ch)[4],
+                                                   float (&age)[4], float (&since)[4]) {
+  if (t != 1) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+      if (on[k]) br_refresh_update(p, t, ch[k], age[k], since[k]);
+    return;
+  }
+  bool ask[4];
+  int x[8];
+  bool any = false;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    ask[k] = false;
+    if (on[k]) {
+      age[k] = __fadd_rn(age[k], 1.0f);
+      since[k] = __fadd_rn(since[k], 1.0f);
+      const float dec = __fsub_rn(ch[k], 1.0f);
+      ask[k] = (int)since[k] >= p.refresh || dec < 1.0f;
+      if (!ask[k]) ch[k] = dec;
+    }
+    any |= ask[k];
+    x[2 * k] = ask[k] ? (int)age[k] : 0;
+    x[2 * k + 1] = x[2 * k] + p.H;
+  }
+  if (br_ballot(any) == 0ull) return;
+  int r[8];
+  br_hist_ranks<8>(p, x, r);
+  long long hs[8];
+#pragma unroll
+  for (int q = 0; q < 8; ++q) hs[q] = p.hsum[r[q]];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    if (ask[k]) {
+      ch[k] = br_survival_at(p, x[2 * k], r[2 * k], r[2 * k + 1], hs[2 * k], hs[2 * k + 1]);
+      since[k] = 0.0f;
+    }
+  }
+}
+
+// the maintained rows (c_hat, age, since) of four consecutive requests: twelve floats, 16-byte aligned
+__device__ __forceinline__ void br_rows3_load(const float *q, float (&ch)[4], float (&age)[4], float (&since)[4]) {
+  const float4 a0 = *reinterpret_cast<const float4 *>(q);
+  const float4 a1 = *reinterpret_cast<const float4 *>(q + 4);
+  const float4 a2 = *reinterpret_cast<const float4 *>(q + 8);
+  ch[0] = a0.x, age[0] = a0.y, since[0] = a0.z;
+  ch[1] = a0.w, age[1] = a1.x, since[1] = a1.y;
+  ch[2] = a1.z, age[2] = a1.w, since[2] = a2.x;
+  ch[3] = a2.y, age[3] = a2.z, since[3] = a2.w;
 }
 
 // ---------------------------------------------------------------- decode step on one list chunk
@@ -372,17 +493,17 @@ __device__ __forceinline__ void br_adv_apply(const BrParams &p, int t, int e0, i
                                                       kv[2] + (stay[2] ? t : 0), kv[3] + (stay[3] ? t : 0));
       *reinterpret_cast<int4 *>(rw + e0) = make_int4(rem[0] - (stay[0] ? t : 0), rem[1] - (stay[1] ? t : 0),
                                                       rem[2] - (stay[2] ? t : 0), rem[3] - (stay[3] ? t : 0));
-      if constexpr (PRED) {
-        if (p.pred_mode == 2) {
-#pragma unroll
-          for (int k = 0; k < 4; ++k) {
-            if (stay[k]) {
-              float *q = pw + (int64_t)(e0 + k) * 3;
-              float ch = q[0], age = q[1], since = q[2];
-              br_refresh_update(p, t, ch, age, since);
-              q[0] = ch, q[1] = age, q[2] = since;
-            }
-          }
+    }
+    if constexpr (PRED) {
+      if (p.pred_mode == 2) {  // (every lane goes through the update: its look-ups are taken by the whole wave)
+        float ch[4] = {0.0f, 0.0f, 0.0f, 0.0f}, age[4] = {0.0f, 0.0f, 0.0f, 0.0f}, since[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        float *q = pw + (int64_t)e0 * 3;
+        if (e0 < ng) br_rows3_load(q, ch, age, since);
+        br_refresh_update4(p, t, stay, ch, age, since);
+        if (e0 < ng) {  // rows beyond the list go back as they came
+          *reinterpret_cast<float4 *>(q) = make_float4(ch[0], age[0], since[0], ch[1]);
+          *reinterpret_cast<float4 *>(q + 4) = make_float4(age[1], since[1], ch[2], age[2]);
+          *reinterpret_cast<float4 *>(q + 8) = make_float4(since[2], ch[3], age[3], since[3]);
         }
       }
     }
@@ -394,13 +515,20 @@ __device__ __forceinline__ void br_adv_apply(const BrParams &p, int t, int e0, i
     if constexpr (PRED) {
       // prediction rows move with their requests: all rows of the lane are read before the first is written
       float pr[4][BR_HP];
+      if (p.pred_mode == 2) {
+        float ch[4] = {0.0f, 0.0f, 0.0f, 0.0f}, age[4] = {0.0f, 0.0f, 0.0f, 0.0f}, since[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (e0 < ng) br_rows3_load(pw + (int64_t)e0 * 3, ch, age, since);
+        br_refresh_update4(p, t, stay, ch, age, since);
 #pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        if (stay[k]) {
+        for (int k = 0; k < 4; ++k) pr[k][0] = ch[k], pr[k][1] = age[k], pr[k][2] = since[k];
+      } else {
 #pragma unroll
-          for (int q = 0; q < BR_HP; ++q)
-            if (q < p.P) pr[k][q] = pw[(int64_t)(e0 + k) * p.P + q];
-          if (p.pred_mode == 2) br_refresh_update(p, t, pr[k][0], pr[k][1], pr[k][2]);
+        for (int k = 0; k < 4; ++k) {
+          if (stay[k]) {
+#pragma unroll
+            for (int q = 0; q < BR_HP; ++q)
+              if (q < p.P) pr[k][q] = pw[(int64_t)(e0 + k) * p.P + q];
+          }
         }
       }
       int pp = pos;

@@ -23,6 +23,8 @@ hipError_t br_static_scratch_resolve(int **out);
 void br_launch_assign(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st);
 // horizons beyond BR_HP: per-offset state in LDS, one wave per cluster
 void br_launch_assign_long(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st);
+// waves per cluster of that kernel (1, 2 or 4); with more than one the decode steps are a launch of their own
+int br_long_waves(const BrParams &p);
 // candidate windows of 9..16 requests (H <= BR_HP); no fused decode steps
 void br_launch_assign_bigr(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st);
 void br_launch_assign_br0(const BrParams &p, const BrArr &a, const BrOut &o, hipStream_t st);

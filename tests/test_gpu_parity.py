@@ -163,13 +163,16 @@ def test_random_rounds(case):
     (12, 6, 300, 8, dict(pred_mode=1)),
     (12, 10, 130, 3, dict(gate_pfin=0.5, gamma=0.64, beta=14.67, tie_heavy=True)),
     (16, 12, 256, 0, dict(R_max=12)),                    # wide windows: reductions and round as separate launches
-    (8, 10, 100, 40, dict(pred_mode=1, gamma=0.97)),     # long horizon: block-per-cluster score kernel
+    (8, 10, 100, 40, dict(pred_mode=1, gamma=0.97)),     # long horizon: block-per-cluster score kernel; two waves share a cluster's searches
+    (5, 8, 90, 24, dict(pred_mode=1, n_inst=2304)),      # long horizon, more clusters than share waves: one wave per cluster
+    (6, 8, 300, 16, dict(pred_mode=1, n_inst=1200, gate_pfin=0.0)),  # queues of up to 512: two waves at this batch size
 ])
 def test_many_small_clusters(G, B, Q, H, extra):
     """Batches of 2048 clusters and more with short queues take the one-wave-per-cluster score kernel
     (no matrix requested): per-request best worker and per-worker best request against the oracle,
     with ragged queue lengths, full workers and the watermark filter."""
-    N = 2048
+    extra = dict(extra)
+    N = extra.pop("n_inst", 2048)
     _say(f"many small clusters N={N} G={G} B={B} Q={Q} H={H} {extra}")
     cfg, init, arr = wl.random_case(500 + G + Q + H, N=N, G=G, B=B, max_wait=Q, H=H, fill=0.8, **extra)
     oc, r = run_pair(cfg, init, arr, matrix=False, tag="small clusters")
