@@ -6,6 +6,7 @@
  */
 #include "br_oracle.h"
 
+#include <math.h>
 #include <stdlib.h>
 #include <string.h>
 
@@ -40,14 +41,14 @@ static void scorer_init(scorer *S, const orc_params *P, int force_float) {
 }
 
 /* Sec. 4.1, eq. (brh-Fscore): alpha (1^T d) Delta - beta ((Delta 1 - m)_+)^T d, fp32,
- * penalty accumulated from h = 0 upwards. */
+ * penalty accumulated from h = 0 upwards, one fused multiply-add (a single rounding) per offset. */
 static float horizon_score(const scorer *S, const int64_t *m, int64_t delta) {
   float pen = 0.0f;
   int h;
   for (h = 0; h <= S->H; ++h) {
     int64_t over = delta - m[h];
     if (over < 0) over = 0;
-    pen = pen + S->d[h] * (float)over;
+    pen = fmaf(S->d[h], (float)over, pen);
   }
   return S->aD * (float)delta - S->beta * pen;
 }

@@ -29,7 +29,7 @@ def build(force: bool = False) -> str:
              or os.path.getmtime(_LIB) < max(os.path.getmtime(_SRC), os.path.getmtime(_HDR)))
     if force or stale:
         subprocess.check_call(["gcc", "-O2", "-ffp-contract=off", "-fPIC", "-shared", "-Wall",
-                               "-o", _LIB, _SRC])
+                               "-o", _LIB, _SRC, "-lm"])
     return _LIB
 
 

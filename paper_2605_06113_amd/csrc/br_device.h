@@ -169,8 +169,9 @@ __device__ __forceinline__ int br_score0(int G, int m, int delta) {
   return delta + (max(delta - m, 0) & 0x7fffff) * -(G & 0x7f);
 }
 
-// Sec. 4.1, eq. (brh-Fscore): alpha (1^T d) Delta - beta ((Delta 1 - m)_+)^T d, fp32, each
-// operation rounded on its own, penalty accumulated from h = 0 upwards.  Offsets beyond H carry
+// Sec. 4.1, eq. (brh-Fscore): alpha (1^T d) Delta - beta ((Delta 1 - m)_+)^T d, fp32: the penalty is
+// accumulated from h = 0 upwards with one fused multiply-add per offset (pen = fma(d_h, (Delta - m_h)_+, pen),
+// a single rounding), the two products and the difference of the last line are rounded one by one.  Offsets beyond H carry
 // a zero discount and add exactly +0.
 __device__ __forceinline__ float br_scoreh(const BrParams &p, const int (&m)[BR_HP + 1], int delta) {
   // The excess (Delta - m)_+ is formed in fp32, one operation less per offset than in integers and the same
@@ -181,11 +182,11 @@ __device__ __forceinline__ float br_scoreh(const BrParams &p, const int (&m)[BR_
   float pen = 0.0f;
 #pragma unroll
   for (int h = 0; h <= BR_HP / 2; ++h)
-    pen = __fadd_rn(pen, __fmul_rn(p.d[h], fmaxf(__fsub_rn(fd, (float)m[h]), 0.0f)));
+    pen = __fmaf_rn(p.d[h], fmaxf(__fsub_rn(fd, (float)m[h]), 0.0f), pen);
   if (p.H > BR_HP / 2) {  // short horizons: the remaining terms are +0 and leave the sum as it is
 #pragma unroll
     for (int h = BR_HP / 2 + 1; h <= BR_HP; ++h)
-      pen = __fadd_rn(pen, __fmul_rn(p.d[h], fmaxf(__fsub_rn(fd, (float)m[h]), 0.0f)));
+      pen = __fmaf_rn(p.d[h], fmaxf(__fsub_rn(fd, (float)m[h]), 0.0f), pen);
   }
   return __fsub_rn(__fmul_rn(p.aD, fd), __fmul_rn(p.beta, pen));
 }
@@ -212,10 +213,10 @@ __device__ __forceinline__ void br_scoreh_long(float aD, float beta, const float
     const float4 dn = *reinterpret_cast<const float4 *>(d + h + 4);
 #pragma unroll
     for (int v = 0; v < NV; ++v) {
-      pen[v] = __fadd_rn(pen[v], __fmul_rn(d4.x, fmaxf(__fsub_rn(fd[v], m4.x), 0.0f)));
-      pen[v] = __fadd_rn(pen[v], __fmul_rn(d4.y, fmaxf(__fsub_rn(fd[v], m4.y), 0.0f)));
-      pen[v] = __fadd_rn(pen[v], __fmul_rn(d4.z, fmaxf(__fsub_rn(fd[v], m4.z), 0.0f)));
-      pen[v] = __fadd_rn(pen[v], __fmul_rn(d4.w, fmaxf(__fsub_rn(fd[v], m4.w), 0.0f)));
+      pen[v] = __fmaf_rn(d4.x, fmaxf(__fsub_rn(fd[v], m4.x), 0.0f), pen[v]);
+      pen[v] = __fmaf_rn(d4.y, fmaxf(__fsub_rn(fd[v], m4.y), 0.0f), pen[v]);
+      pen[v] = __fmaf_rn(d4.z, fmaxf(__fsub_rn(fd[v], m4.z), 0.0f), pen[v]);
+      pen[v] = __fmaf_rn(d4.w, fmaxf(__fsub_rn(fd[v], m4.w), 0.0f), pen[v]);
     }
     m4 = mn;
     d4 = dn;
@@ -256,10 +257,10 @@ __device__ __forceinline__ void br_scoreh_long_act(float aD, float beta, const f
       const float4 d4 = *reinterpret_cast<const float4 *>(d + h);
 #pragma unroll
       for (int v = 0; v < NV; ++v) {
-        pen[v] = __fadd_rn(pen[v], __fmul_rn(d4.x, fmaxf(__fsub_rn(fd[v], m4.x), 0.0f)));
-        pen[v] = __fadd_rn(pen[v], __fmul_rn(d4.y, fmaxf(__fsub_rn(fd[v], m4.y), 0.0f)));
-        pen[v] = __fadd_rn(pen[v], __fmul_rn(d4.z, fmaxf(__fsub_rn(fd[v], m4.z), 0.0f)));
-        pen[v] = __fadd_rn(pen[v], __fmul_rn(d4.w, fmaxf(__fsub_rn(fd[v], m4.w), 0.0f)));
+        pen[v] = __fmaf_rn(d4.x, fmaxf(__fsub_rn(fd[v], m4.x), 0.0f), pen[v]);
+        pen[v] = __fmaf_rn(d4.y, fmaxf(__fsub_rn(fd[v], m4.y), 0.0f), pen[v]);
+        pen[v] = __fmaf_rn(d4.z, fmaxf(__fsub_rn(fd[v], m4.z), 0.0f), pen[v]);
+        pen[v] = __fmaf_rn(d4.w, fmaxf(__fsub_rn(fd[v], m4.w), 0.0f), pen[v]);
       }
     }
   }
@@ -304,10 +305,10 @@ __device__ __forceinline__ void br_scoreh_long_sel(float aD, float beta, const f
 #pragma unroll
       for (int v = 0; v < NV; ++v) {
         if ((gm[v] >> k) & 1ull) {
-          pen[v] = __fadd_rn(pen[v], __fmul_rn(d4.x, fmaxf(__fsub_rn(fd[v], m4.x), 0.0f)));
-          pen[v] = __fadd_rn(pen[v], __fmul_rn(d4.y, fmaxf(__fsub_rn(fd[v], m4.y), 0.0f)));
-          pen[v] = __fadd_rn(pen[v], __fmul_rn(d4.z, fmaxf(__fsub_rn(fd[v], m4.z), 0.0f)));
-          pen[v] = __fadd_rn(pen[v], __fmul_rn(d4.w, fmaxf(__fsub_rn(fd[v], m4.w), 0.0f)));
+          pen[v] = __fmaf_rn(d4.x, fmaxf(__fsub_rn(fd[v], m4.x), 0.0f), pen[v]);
+          pen[v] = __fmaf_rn(d4.y, fmaxf(__fsub_rn(fd[v], m4.y), 0.0f), pen[v]);
+          pen[v] = __fmaf_rn(d4.z, fmaxf(__fsub_rn(fd[v], m4.z), 0.0f), pen[v]);
+          pen[v] = __fmaf_rn(d4.w, fmaxf(__fsub_rn(fd[v], m4.w), 0.0f), pen[v]);
         }
       }
       if (!more) break;
@@ -374,65 +375,43 @@ __device__ __forceinline__ float br_survival(const BrParams &p, int age) {
   return br_survival_at(p, age, r[0], r[1], p.hsum[r[0]], p.hsum[r[1]]);
 }
 
-// Appendix "Refresh logic", for a request that stays active over t more generated tokens: per token
-// one step less of in-window contribution; the estimator is queried again every `refresh` tokens and
-// whenever c_hat would fall below its floor of one.
-__device__ __forceinline__ void br_refresh_update(const BrParams &p, int t, float &ch, float &age, float &since) {
-  for (int u = 0; u < t; ++u) {
-    age = __fadd_rn(age, 1.0f);
-    since = __fadd_rn(since, 1.0f);
-    if ((int)since >= p.refresh) {
-      ch = br_survival(p, (int)age);
-      since = 0.0f;
-    } else {
-      ch = __fsub_rn(ch, 1.0f);
-      if (ch < 1.0f) {
-        ch = br_survival(p, (int)age);
-        since = 0.0f;
-      }
-    }
-  }
-}
-
-// The same for the four requests a lane holds (`on`: the request stays active).  One generated token, the usual
-// decode step, is taken for all four together: the look-ups of the requests that query the estimator run side by
-// side (eight ranks per lane in flight) instead of one after the other.  Every lane of the wave must call.
+// Appendix "Refresh logic", for the four requests a lane holds (`on`: the request stays active over t more
+// generated tokens): per token one step less of in-window contribution; the estimator is queried again every
+// `refresh` tokens and whenever c_hat would fall below its floor of one.  The four are taken together token by
+// token, so that the look-ups of those that query the estimator run side by side (eight ranks per lane in flight)
+// instead of one after the other.  Every lane of the wave must call.
 __device__ __forceinline__ void br_refresh_update4(const BrParams &p, int t, const bool (&on)[4], float (&ch)[4],
                                                    float (&age)[4], float (&since)[4]) {
-  if (t != 1) {
+  for (int u = 0; u < t; ++u) {
+    bool ask[4];
+    int x[8];
+    bool any = false;
 #pragma unroll
-    for (int k = 0; k < 4; ++k)
-      if (on[k]) br_refresh_update(p, t, ch[k], age[k], since[k]);
-    return;
-  }
-  bool ask[4];
-  int x[8];
-  bool any = false;
-#pragma unroll
-  for (int k = 0; k < 4; ++k) {
-    ask[k] = false;
-    if (on[k]) {
-      age[k] = __fadd_rn(age[k], 1.0f);
-      since[k] = __fadd_rn(since[k], 1.0f);
-      const float dec = __fsub_rn(ch[k], 1.0f);
-      ask[k] = (int)since[k] >= p.refresh || dec < 1.0f;
-      if (!ask[k]) ch[k] = dec;
+    for (int k = 0; k < 4; ++k) {
+      ask[k] = false;
+      if (on[k]) {
+        age[k] = __fadd_rn(age[k], 1.0f);
+        since[k] = __fadd_rn(since[k], 1.0f);
+        const float dec = __fsub_rn(ch[k], 1.0f);
+        ask[k] = (int)since[k] >= p.refresh || dec < 1.0f;
+        if (!ask[k]) ch[k] = dec;
+      }
+      any |= ask[k];
+      x[2 * k] = ask[k] ? (int)age[k] : 0;
+      x[2 * k + 1] = x[2 * k] + p.H;
     }
-    any |= ask[k];
-    x[2 * k] = ask[k] ? (int)age[k] : 0;
-    x[2 * k + 1] = x[2 * k] + p.H;
-  }
-  if (br_ballot(any) == 0ull) return;
-  int r[8];
-  br_hist_ranks<8>(p, x, r);
-  long long hs[8];
+    if (br_ballot(any) == 0ull) continue;
+    int r[8];
+    br_hist_ranks<8>(p, x, r);
+    long long hs[8];
 #pragma unroll
-  for (int q = 0; q < 8; ++q) hs[q] = p.hsum[r[q]];
+    for (int q = 0; q < 8; ++q) hs[q] = p.hsum[r[q]];
 #pragma unroll
-  for (int k = 0; k < 4; ++k) {
-    if (ask[k]) {
-      ch[k] = br_survival_at(p, x[2 * k], r[2 * k], r[2 * k + 1], hs[2 * k], hs[2 * k + 1]);
-      since[k] = 0.0f;
+    for (int k = 0; k < 4; ++k) {
+      if (ask[k]) {
+        ch[k] = br_survival_at(p, x[2 * k], r[2 * k], r[2 * k + 1], hs[2 * k], hs[2 * k + 1]);
+        since[k] = 0.0f;
+      }
     }
   }
 }
@@ -486,6 +465,15 @@ __device__ __forceinline__ void br_adv_apply(const BrParams &p, int t, int e0, i
     bs[k] = br_ballot(stay[k]);
     nstay += __builtin_popcountll(bs[k]);
   }
+  // maintained estimates: the rows of the lane's four requests are read and brought up to date before anything
+  // is written (every lane goes through the update: its look-ups are taken by the whole wave)
+  float ch[4] = {0.0f, 0.0f, 0.0f, 0.0f}, age[4] = {0.0f, 0.0f, 0.0f, 0.0f}, since[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+  if constexpr (PRED) {
+    if (p.pred_mode == 2) {
+      if (e0 < ng) br_rows3_load(pw + (int64_t)e0 * 3, ch, age, since);
+      br_refresh_update4(p, t, stay, ch, age, since);
+    }
+  }
   const bool shifted = kept != chunk0;  // an earlier chunk of this list lost a request
   if (!shifted && br_ballot(any_leave) == 0ull) {
     if (e0 < ng) {  // same positions: 16-byte stores; slots beyond the list keep what they held
@@ -495,11 +483,8 @@ __device__ __forceinline__ void br_adv_apply(const BrParams &p, int t, int e0, i
                                                       rem[2] - (stay[2] ? t : 0), rem[3] - (stay[3] ? t : 0));
     }
     if constexpr (PRED) {
-      if (p.pred_mode == 2) {  // (every lane goes through the update: its look-ups are taken by the whole wave)
-        float ch[4] = {0.0f, 0.0f, 0.0f, 0.0f}, age[4] = {0.0f, 0.0f, 0.0f, 0.0f}, since[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+      if (p.pred_mode == 2) {
         float *q = pw + (int64_t)e0 * 3;
-        if (e0 < ng) br_rows3_load(q, ch, age, since);
-        br_refresh_update4(p, t, stay, ch, age, since);
         if (e0 < ng) {  // rows beyond the list go back as they came
           *reinterpret_cast<float4 *>(q) = make_float4(ch[0], age[0], since[0], ch[1]);
           *reinterpret_cast<float4 *>(q + 4) = make_float4(age[1], since[1], ch[2], age[2]);
@@ -516,9 +501,6 @@ __device__ __forceinline__ void br_adv_apply(const BrParams &p, int t, int e0, i
       // prediction rows move with their requests: all rows of the lane are read before the first is written
       float pr[4][BR_HP];
       if (p.pred_mode == 2) {
-        float ch[4] = {0.0f, 0.0f, 0.0f, 0.0f}, age[4] = {0.0f, 0.0f, 0.0f, 0.0f}, since[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-        if (e0 < ng) br_rows3_load(pw + (int64_t)e0 * 3, ch, age, since);
-        br_refresh_update4(p, t, stay, ch, age, since);
 #pragma unroll
         for (int k = 0; k < 4; ++k) pr[k][0] = ch[k], pr[k][1] = age[k], pr[k][2] = since[k];
       } else {

@@ -26,7 +26,7 @@
 //   - BR-0 with G > 1 falls strictly beyond the margin (eq. (br0-Fscore): slope -(G-1) in exact integers), so
 //     only the smallest reachable sum above the margin can win there, and the rows need no bit beyond
 //     margin + longest request;
-//   - every other reachable sum is scored as computed (BR-H in fp32, each operation rounded: no monotonicity is
+//   - every other reachable sum is scored as computed (BR-H in fp32 as the kernels round it: no monotonicity is
 //     assumed where roundings could reorder neighbours).
 // Equal best scores at several sums (or G = 1, whose score is flat beyond the margin) resolve to the lowest
 // mask over all of them, found by building the mask of each tied sum.

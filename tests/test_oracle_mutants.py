@@ -24,7 +24,7 @@ MUTANTS = [
      "int64_t over = m - delta;\n  if (over < 0) over = 0;\n  return delta"),
     # eq. (brh-Fscore)
     ("brh last offset dropped", "for (h = 0; h <= S->H; ++h) {\n    int64_t over", "for (h = 0; h < S->H; ++h) {\n    int64_t over"),
-    ("brh discount dropped", "pen = pen + S->d[h] * (float)over;", "pen = pen + (float)over;"),
+    ("brh discount dropped", "pen = fmaf(S->d[h], (float)over, pen);", "pen = pen + (float)over;"),
     ("brh discount sum starts late", "for (h = 0; h <= P->H; ++h) D = D + S->d[h];", "for (h = 1; h <= P->H; ++h) D = D + S->d[h];"),
     ("brh gamma ignored", "S->d[h] = S->d[h - 1] * P->gamma;", "S->d[h] = S->d[h - 1];"),
     ("brh alpha and beta swapped", "return S->aD * (float)delta - S->beta * pen;", "return S->beta * (float)delta - S->aD * pen;"),
@@ -95,7 +95,7 @@ def _build(tmp, name, text):
     with open(c, "w") as f:
         f.write(text)
     subprocess.check_call(["gcc", "-O2", "-ffp-contract=off", "-fPIC", "-shared", "-I", os.path.join(ROOT, "oracle"),
-                           "-o", so, c])
+                           "-o", so, c, "-lm"])
     return so
 
 
