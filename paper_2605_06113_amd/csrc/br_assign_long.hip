@@ -76,7 +76,8 @@ __device__ __forceinline__ void br_long_slice_best(const BrParams &p, const floa
 }
 
 template <int E, bool ADV, int NW>
-__global__ __launch_bounds__(64 * NW) void br_k_assign_long(BrParams p, BrArr a, BrOut o) {
+// (queues of up to 256: four waves per SIMD are asked for, which is what br_long_waves counts on)
+__global__ __launch_bounds__(64 * NW, E == 4 ? 4 : 1) void br_k_assign_long(BrParams p, BrArr a, BrOut o) {
   static_assert(NW == 1 || !ADV, "decode steps ride along only with one wave per cluster");
   static_assert(E % NW == 0, "every wave takes whole blocks of 64 sorted positions");
   constexpr int EW = E / NW;  // blocks of 64 sorted positions per wave in a shared search
@@ -99,7 +100,7 @@ __global__ __launch_bounds__(64 * NW) void br_k_assign_long(BrParams p, BrArr a,
   int *sL = sM + 3 * HS;            // [HS][LS] step-start projections (rows beyond H: "no worker")
   int *hitab = sL + ((HS * LS + 3) & ~3);  // R_max > 8: [1024] sums of window entries 6.. by upper mask bits
   int *mbox = hitab + (p.R_max > 8 ? 1024 : 0);  // NW > 1: [16] search mailbox: command, admissible length; results from word 4
-  int *salive = pm;                 // NW > 1: alive words of the lanes of wave 0 during a search (pm is idle then)
+  int *salive = pm;                 // alive words of the lanes of wave 0 during a search (pm is idle then)
 
   const int lane = br_lane();
   const int G = p.G;
@@ -234,10 +235,87 @@ __global__ __launch_bounds__(64 * NW) void br_k_assign_long(BrParams p, BrArr a,
     return max(mn - add, 0);  // min_h (M_h - sL_h) - add, clamped once: the same as clamping every offset
   };
 
+  // Rounding of one evaluation of eq. (brh-Fscore) in fp32: at most H + 5 roundings, each relative 2^-24 on terms
+  // bounded by (alpha D + beta D) Delta, so a computed score differs from the exact one by at most
+  // err_unit * Delta (a quarter of slack on top covers the rounding of this bound itself).
+  float err_unit;
+  {
+    float Dsum = 0.0f;
+    for (int h = 0; h < HS; h += 4) {
+      const float4 q = *reinterpret_cast<const float4 *>(sd + h);
+      Dsum += (q.x + q.y) + (q.z + q.w);
+    }
+    err_unit = 1.25f * (float)(p.H + 5) * 5.9604645e-8f * (p.aD + p.beta * Dsum);
+  }
+
   // argmax_i F_g({i}) over alive, admissible requests against the margins in smg (lowest sorted
-  // position on ties); false when no request is admissible
+  // position on ties); false when no request is admissible.
+  //
+  // The exact score is concave in the request's length, and the waiting set is sorted by length: the search
+  // brackets the maximum instead of scoring every request.  Probes: every E-th sorted position from the first
+  // request in question on (up to 64 lanes), waiting or not, scored by br_scoreh_long_approx; Fb is the best probe among the requests in question.  With e =
+  // err_unit times the longest length (a bound on the distance of either evaluation from the exact score): a probe
+  // that is longer than the best one and scores below Fb - 4 e has an exact score below the best probe's, by
+  // concavity the exact score cannot rise again beyond it, and every position at or before it computes (in the
+  // ordered evaluation) below what the best probe's request computes; likewise for a shorter probe and every
+  // position at or after it.  What lies strictly between the nearest such probes on both sides of the best one
+  // (at most 64 positions, else the full scan below takes over) is scored in the ordered evaluation, and the best
+  // request in question there, lowest position on equal scores, is the argmax over the whole waiting set:
+  // everything left out computes strictly below a score that was kept.
   auto pick_single = [&](int room, int &pos, int &swin) -> bool {
     int bk, bp, km;
+    {
+      int fa = -1, la = -1;  // first and last sorted position of a request in question
+#pragma unroll
+      for (int j = 0; j < E; ++j) {
+        if (j * BR_WAVE < qn) {
+          const unsigned long long bal = br_ballot(((alive >> j) & 1u) && sv[j] <= room);
+          if (bal != 0ull) {
+            if (fa < 0) fa = j * BR_WAVE + (int)__builtin_ctzll(bal);
+            la = j * BR_WAVE + 63 - (int)__builtin_clzll(bal);
+          }
+        }
+      }
+      if (fa < 0) return false;
+      salive[lane] = (int)alive;
+      br_wave_sync();
+      const int p1 = lane * E;  // probe position
+      const int e1 = skey[p1];
+      const int s1 = e1 >> BR_IDX_BITS;
+      const bool in1 = p1 < qn && p1 >= fa;  // (a probe before the first request in question brackets nothing that one does not)
+      const bool q1 = in1 && (((unsigned)salive[p1 & 63] >> (p1 >> 6)) & 1u) && s1 <= room;
+      const int top1 = br_uniform(skey[fa] >> BR_IDX_BITS);  // the longest request in question
+      const float F1 = br_scoreh_long_approx(p.aD, p.beta, smg, sd, HS, lane, top1, s1);
+      const int k1 = q1 ? br_ord(F1) : BR_KEY_NONE;
+      const int km1 = br_wave_max(k1);
+      if (km1 != BR_KEY_NONE) {
+        const int ls = (int)__builtin_ctzll(br_ballot(k1 == km1));
+        const float thr = br_unord(km1) - 4.0f * err_unit * (float)top1;
+        const unsigned long long ex = br_ballot(in1 && F1 < thr);
+        const unsigned long long before = ex & ((1ull << ls) - 1ull);
+        const unsigned long long after = ls < 63 ? ex >> (ls + 1) : 0ull;
+        const int lo = before != 0ull ? (63 - (int)__builtin_clzll(before)) * E + 1 : fa;
+        const int hi = after != 0ull ? min((ls + 1 + (int)__builtin_ctzll(after)) * E - 1, la) : la;
+        const int nc = hi - lo + 1;
+        if (nc <= BR_WAVE) {
+          const int p2 = min(lo + lane, NP - 1);
+          const int e2 = skey[p2];
+          const int s2[1] = {e2 >> BR_IDX_BITS};
+          const bool q2 = lane < nc && (((unsigned)salive[p2 & 63] >> (p2 >> 6)) & 1u) && s2[0] <= room;
+          const int top2[1] = {__builtin_amdgcn_readfirstlane(s2[0])};
+          float F2[1];
+          br_scoreh_long_sel<1>(p.aD, p.beta, smg, sd, HS, lane, top2, s2, F2);
+          const int k2 = q2 ? br_ord(F2[0]) : BR_KEY_NONE;
+          const int km2 = br_wave_max(k2);
+          const int l2 = (int)__builtin_ctzll(br_ballot(k2 == km2));  // positions rise with the lane: lowest first
+          pos = lo + l2;
+          swin = __builtin_amdgcn_readlane(s2[0], l2);
+          br_wave_sync();
+          return true;
+        }
+      }
+      br_wave_sync();
+    }
     if constexpr (NW > 1) {
       mbox[1] = room;
       salive[lane] = (int)alive;
@@ -380,21 +458,11 @@ __global__ __launch_bounds__(64 * NW) void br_k_assign_long(BrParams p, BrArr a,
     for (int b = 0; b < 6; ++b) lbit[b] = (lane >> b) & 1;
     const int lpop = __builtin_popcount(lane);
     // Certain guard: eq. (brh-Fscore) is concave in Delta with F(0) = 0, so F(Delta) <= F(s) Delta / s for every
-    // Delta >= s, and every subset of the window sums to at least the window's smallest entry s.  Scores are
-    // compared as computed in fp32: one evaluation has at most H + 5 roundings, each relative 2^-24 on terms
-    // bounded by (alpha D + beta D) Delta, so a computed score differs from the exact one by at most
-    // e(Delta) = (H + 5) 2^-24 (alpha D + beta D) Delta.  If the smallest entry's computed score is at or below
-    // -2.5 e(s), its exact score is below -1.5 e(s), every subset's exact score below -1.5 e(Delta) and every
-    // subset's computed score below zero: the pop goes to the starvation guard without the enumeration.
-    float guard_eps;
-    {
-      float Dsum = 0.0f;
-      for (int h = 0; h < HS; h += 4) {
-        const float4 q = *reinterpret_cast<const float4 *>(sd + h);
-        Dsum += (q.x + q.y) + (q.z + q.w);
-      }
-      guard_eps = 2.5f * (float)(p.H + 5) * 5.9604645e-8f * (p.aD + p.beta * Dsum);
-    }
+    // Delta >= s, and every subset of the window sums to at least the window's smallest entry s.  With the rounding
+    // bound e(Delta) = err_unit Delta (above): if the smallest entry's computed score is at or below -2 e(s), its
+    // exact score is below -e(s), every subset's exact score below -e(Delta) and every subset's computed score
+    // below zero: the pop goes to the starvation guard without the enumeration.
+    const float guard_eps = 2.0f * err_unit;
     for (int it = 0; it < bound; ++it) {
       if (n_alive <= 0) break;
       const int capmax = br_wave_max(cap);

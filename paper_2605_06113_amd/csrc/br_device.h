@@ -268,12 +268,49 @@ __device__ __forceinline__ void br_scoreh_long_act(float aD, float beta, const f
   for (int v = 0; v < NV; ++v) F[v] = __fsub_rn(__fmul_rn(aD, fd[v]), __fmul_rn(beta, pen[v]));
 }
 
+// One stage of a walk over four-offset groups: the next NB groups named by the set bits of `u` (taken off it),
+// their margins and discounts requested from LDS.  has[i]: the stage's i-th group exists.
+template <int NB>
+struct BrGroupStage {
+  int k[NB];
+  bool has[NB];
+  float4 m4[NB], d4[NB];
+  __device__ __forceinline__ void fetch(unsigned long long &u, const float *m, const float *d) {
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+      has[i] = u != 0ull;
+      k[i] = has[i] ? (int)__builtin_ctzll(u) : 0;
+      u &= u - 1ull;  // (u == 0 stays 0)
+      if (has[i]) {
+        m4[i] = *reinterpret_cast<const float4 *>(m + 4 * k[i]);
+        d4[i] = *reinterpret_cast<const float4 *>(d + 4 * k[i]);
+      }
+    }
+  }
+};
+
+// the four offsets of a group added to one penalty sum in ascending order
+__device__ __forceinline__ void br_group_add(const float4 &m4, const float4 &d4, float fd, float &pen) {
+  pen = __fmaf_rn(d4.x, fmaxf(__fsub_rn(fd, m4.x), 0.0f), pen);
+  pen = __fmaf_rn(d4.y, fmaxf(__fsub_rn(fd, m4.y), 0.0f), pen);
+  pen = __fmaf_rn(d4.z, fmaxf(__fsub_rn(fd, m4.z), 0.0f), pen);
+  pen = __fmaf_rn(d4.w, fmaxf(__fsub_rn(fd, m4.w), 0.0f), pen);
+}
+
+// the same into four separate partial sums
+__device__ __forceinline__ void br_group_add4(const float4 &m4, const float4 &d4, float fd, float4 &pen) {
+  pen.x = __fmaf_rn(d4.x, fmaxf(__fsub_rn(fd, m4.x), 0.0f), pen.x);
+  pen.y = __fmaf_rn(d4.y, fmaxf(__fsub_rn(fd, m4.y), 0.0f), pen.y);
+  pen.z = __fmaf_rn(d4.z, fmaxf(__fsub_rn(fd, m4.z), 0.0f), pen.z);
+  pen.w = __fmaf_rn(d4.w, fmaxf(__fsub_rn(fd, m4.w), 0.0f), pen.w);
+}
+
 // The same walk with a bound per value: value v is known not to exceed bound[v] (0: the value is not in
 // question and its result is not used).  A four-offset group whose margins all lie at or above bound[v] adds
 // exact zeros to value v's penalty and is skipped for that value alone, so a lane that holds a long and a short
 // request pays the long walk only for the long one.  Lanes stand for groups when the masks are formed (one
 // 16-byte read each); the groups in use are then walked in ascending order with margins and discounts
-// broadcast, the next group requested before the current one is used.  Every lane of the wave must call with
+// broadcast, reads requested ahead of their use.  Every lane of the wave must call with
 // the same bounds.  Results are the bits of the full walk.
 template <int NV>
 __device__ __forceinline__ void br_scoreh_long_sel(float aD, float beta, const float *m, const float *d, int HS, int lane,
@@ -291,34 +328,98 @@ __device__ __forceinline__ void br_scoreh_long_sel(float aD, float beta, const f
       u |= gm[v];
     }
   }
-  if (u != 0ull) {
-    int k = (int)__builtin_ctzll(u);
-    u &= u - 1ull;
-    float4 m4 = *reinterpret_cast<const float4 *>(m + 4 * k);
-    float4 d4 = *reinterpret_cast<const float4 *>(d + 4 * k);
-    for (;;) {
-      const bool more = u != 0ull;
-      const int kn = more ? (int)__builtin_ctzll(u) : k;
-      u &= u - 1ull;  // (u == 0 stays 0)
-      const float4 mn = *reinterpret_cast<const float4 *>(m + 4 * kn);
-      const float4 dn = *reinterpret_cast<const float4 *>(d + 4 * kn);
+  if constexpr (NV >= 4) {
+    // four values per lane: the arithmetic of a group covers the LDS latency of the next one
+    if (u != 0ull) {
+      int k = (int)__builtin_ctzll(u);
+      u &= u - 1ull;
+      float4 m4 = *reinterpret_cast<const float4 *>(m + 4 * k);
+      float4 d4 = *reinterpret_cast<const float4 *>(d + 4 * k);
+      for (;;) {
+        const bool more = u != 0ull;
+        const int kn = more ? (int)__builtin_ctzll(u) : k;
+        u &= u - 1ull;  // (u == 0 stays 0)
+        const float4 mn = *reinterpret_cast<const float4 *>(m + 4 * kn);
+        const float4 dn = *reinterpret_cast<const float4 *>(d + 4 * kn);
 #pragma unroll
-      for (int v = 0; v < NV; ++v) {
-        if ((gm[v] >> k) & 1ull) {
-          pen[v] = __fmaf_rn(d4.x, fmaxf(__fsub_rn(fd[v], m4.x), 0.0f), pen[v]);
-          pen[v] = __fmaf_rn(d4.y, fmaxf(__fsub_rn(fd[v], m4.y), 0.0f), pen[v]);
-          pen[v] = __fmaf_rn(d4.z, fmaxf(__fsub_rn(fd[v], m4.z), 0.0f), pen[v]);
-          pen[v] = __fmaf_rn(d4.w, fmaxf(__fsub_rn(fd[v], m4.w), 0.0f), pen[v]);
+        for (int v = 0; v < NV; ++v) {
+          if ((gm[v] >> k) & 1ull) {
+            pen[v] = __fmaf_rn(d4.x, fmaxf(__fsub_rn(fd[v], m4.x), 0.0f), pen[v]);
+            pen[v] = __fmaf_rn(d4.y, fmaxf(__fsub_rn(fd[v], m4.y), 0.0f), pen[v]);
+            pen[v] = __fmaf_rn(d4.z, fmaxf(__fsub_rn(fd[v], m4.z), 0.0f), pen[v]);
+            pen[v] = __fmaf_rn(d4.w, fmaxf(__fsub_rn(fd[v], m4.w), 0.0f), pen[v]);
+          }
+        }
+        if (!more) break;
+        k = kn;
+        m4 = mn;
+        d4 = dn;
+      }
+    }
+  } else {
+    // one or two values per lane: too little arithmetic per group to cover a read, so the groups are taken in
+    // stages of NB, two stages in turn: the reads of one are requested before the other is used
+    constexpr int NB = 2 / NV;
+    BrGroupStage<NB> A, B;
+    A.fetch(u, m, d);
+    for (;;) {
+      if (!A.has[0]) break;
+      B.fetch(u, m, d);
+#pragma unroll
+      for (int i = 0; i < NB; ++i) {
+        if (A.has[i]) {
+#pragma unroll
+          for (int v = 0; v < NV; ++v)
+            if (NV == 1 || ((gm[v] >> A.k[i]) & 1ull)) br_group_add(A.m4[i], A.d4[i], fd[v], pen[v]);
         }
       }
-      if (!more) break;
-      k = kn;
-      m4 = mn;
-      d4 = dn;
+      if (!B.has[0]) break;
+      A.fetch(u, m, d);
+#pragma unroll
+      for (int i = 0; i < NB; ++i) {
+        if (B.has[i]) {
+#pragma unroll
+          for (int v = 0; v < NV; ++v)
+            if (NV == 1 || ((gm[v] >> B.k[i]) & 1ull)) br_group_add(B.m4[i], B.d4[i], fd[v], pen[v]);
+        }
+      }
     }
   }
 #pragma unroll
   for (int v = 0; v < NV; ++v) F[v] = __fsub_rn(__fmul_rn(aD, fd[v]), __fmul_rn(beta, pen[v]));
+}
+
+// An approximation of the same score for one value per lane, for use where only a bound on the error matters:
+// the four offsets of a group feed four separate partial sums (independent chains instead of one), which are
+// added at the end.  Not the bits of br_scoreh_long: it has at most H / 4 + 8 roundings, each relative 2^-24 on
+// terms bounded by (alpha D + beta D) Delta, so it lies within the same distance of the exact score as the
+// ordered walk does.  `bound`: no value exceeds it (groups whose margins all lie at or above it are skipped).
+__device__ __forceinline__ float br_scoreh_long_approx(float aD, float beta, const float *m, const float *d, int HS, int lane,
+                                                       int bound, int delta) {
+  const float fd = (float)delta;
+  float4 pen = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+  unsigned long long u;
+  {
+    const bool in = lane * 4 < HS;
+    const float4 q = *reinterpret_cast<const float4 *>(m + (in ? lane * 4 : 0));
+    u = br_ballot(in && fminf(fminf(q.x, q.y), fminf(q.z, q.w)) < (float)bound);
+  }
+  BrGroupStage<2> A, B;
+  A.fetch(u, m, d);
+  for (;;) {
+    if (!A.has[0]) break;
+    B.fetch(u, m, d);
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+      if (A.has[i]) br_group_add4(A.m4[i], A.d4[i], fd, pen);
+    if (!B.has[0]) break;
+    A.fetch(u, m, d);
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+      if (B.has[i]) br_group_add4(B.m4[i], B.d4[i], fd, pen);
+  }
+  const float ps = __fadd_rn(__fadd_rn(pen.x, pen.y), __fadd_rn(pen.z, pen.w));
+  return __fsub_rn(__fmul_rn(aD, fd), __fmul_rn(beta, ps));
 }
 
 template <bool BRH>
