@@ -81,6 +81,9 @@ __global__ __launch_bounds__(64 * NW, E == 4 ? 4 : 1) void br_k_assign_long(BrPa
   static_assert(NW == 1 || !ADV, "decode steps ride along only with one wave per cluster");
   static_assert(E % NW == 0, "every wave takes whole blocks of 64 sorted positions");
   constexpr int EW = E / NW;  // blocks of 64 sorted positions per wave in a shared search
+  // four-offset groups of wave 0 when the probes of a bracketing search are shared: every NW-th, wave w takes the
+  // same pattern shifted by w
+  constexpr unsigned long long SHARE = NW == 1 ? ~0ull : NW == 2 ? 0x5555555555555555ull : 0x1111111111111111ull;
   extern __shared__ int lds[];
   constexpr int NP = E * BR_WAVE;
   constexpr int IDX_MASK = (1 << BR_IDX_BITS) - 1;
@@ -117,16 +120,22 @@ __global__ __launch_bounds__(64 * NW, E == 4 ? 4 : 1) void br_k_assign_long(BrPa
       int svh[EW];
 #pragma unroll
       for (int j = 0; j < EW; ++j) svh[j] = skey[(w * EW + j) * BR_WAVE + lane] >> BR_IDX_BITS;
+      const int sprobe = skey[lane * E] >> BR_IDX_BITS;  // the probe of this lane in a bracketing search
       for (;;) {
         __syncthreads();
-        if (mbox[0] == 0) break;
-        const int roomq = mbox[1];
-        const unsigned al = (unsigned)salive[lane] >> (w * EW);
-        int bk, bp;
-        br_long_slice_best<EW, 0, EW>(p, smg, sd, HS, lane, qn, svh, al, w * EW, roomq, bk, bp);
-        const int km = br_wave_max(bk);
-        const int pmn = km == BR_KEY_NONE ? INT32_MAX : br_wave_min(bk == km ? bp : INT32_MAX);
-        if (lane == 0) mbox[4 + 2 * w] = km, mbox[5 + 2 * w] = pmn;
+        const int cmd = mbox[0];
+        if (cmd == 0) break;
+        if (cmd == 2) {  // this wave's share of the probes' penalty sums
+          who[w * BR_WAVE + lane] = __float_as_int(br_long_penalty_part(smg, sd, HS, lane, mbox[2], sprobe, SHARE << w));
+        } else {         // this wave's share of a full scan
+          const int roomq = mbox[1];
+          const unsigned al = (unsigned)salive[lane] >> (w * EW);
+          int bk, bp;
+          br_long_slice_best<EW, 0, EW>(p, smg, sd, HS, lane, qn, svh, al, w * EW, roomq, bk, bp);
+          const int km = br_wave_max(bk);
+          const int pmn = km == BR_KEY_NONE ? INT32_MAX : br_wave_min(bk == km ? bp : INT32_MAX);
+          if (lane == 0) mbox[4 + 2 * w] = km, mbox[5 + 2 * w] = pmn;
+        }
         __syncthreads();
       }
       return;
@@ -253,7 +262,8 @@ __global__ __launch_bounds__(64 * NW, E == 4 ? 4 : 1) void br_k_assign_long(BrPa
   //
   // The exact score is concave in the request's length, and the waiting set is sorted by length: the search
   // brackets the maximum instead of scoring every request.  Probes: every E-th sorted position from the first
-  // request in question on (up to 64 lanes), waiting or not, scored by br_scoreh_long_approx; Fb is the best probe among the requests in question.  With e =
+  // request in question on (up to 64 lanes), waiting or not, scored by the order-free evaluation (br_long_penalty_part, shared out by offset groups when
+  // several waves serve the cluster); Fb is the best probe among the requests in question.  With e =
   // err_unit times the longest length (a bound on the distance of either evaluation from the exact score): a probe
   // that is longer than the best one and scores below Fb - 4 e has an exact score below the best probe's, by
   // concavity the exact score cannot rise again beyond it, and every position at or before it computes (in the
@@ -262,20 +272,28 @@ __global__ __launch_bounds__(64 * NW, E == 4 ? 4 : 1) void br_k_assign_long(BrPa
   // (at most 64 positions, else the full scan below takes over) is scored in the ordered evaluation, and the best
   // request in question there, lowest position on equal scores, is the argmax over the whole waiting set:
   // everything left out computes strictly below a score that was kept.
+  int span_fa = -1, span_la = -1;
+  bool span_dirty = true;
   auto pick_single = [&](int room, int &pos, int &swin) -> bool {
     int bk, bp, km;
     {
-      int fa = -1, la = -1;  // first and last sorted position of a request in question
+      // first and last sorted position of a request in question: kept from search to search while the alive set
+      // loses nothing at either end and no watermark narrows the set
+      if (span_dirty || p.W > 0) {
+        span_fa = -1, span_la = -1;
 #pragma unroll
-      for (int j = 0; j < E; ++j) {
-        if (j * BR_WAVE < qn) {
-          const unsigned long long bal = br_ballot(((alive >> j) & 1u) && sv[j] <= room);
-          if (bal != 0ull) {
-            if (fa < 0) fa = j * BR_WAVE + (int)__builtin_ctzll(bal);
-            la = j * BR_WAVE + 63 - (int)__builtin_clzll(bal);
+        for (int j = 0; j < E; ++j) {
+          if (j * BR_WAVE < qn) {
+            const unsigned long long bal = br_ballot(((alive >> j) & 1u) && sv[j] <= room);
+            if (bal != 0ull) {
+              if (span_fa < 0) span_fa = j * BR_WAVE + (int)__builtin_ctzll(bal);
+              span_la = j * BR_WAVE + 63 - (int)__builtin_clzll(bal);
+            }
           }
         }
+        span_dirty = false;
       }
+      const int fa = span_fa, la = span_la;
       if (fa < 0) return false;
       salive[lane] = (int)alive;
       br_wave_sync();
@@ -285,7 +303,19 @@ __global__ __launch_bounds__(64 * NW, E == 4 ? 4 : 1) void br_k_assign_long(BrPa
       const bool in1 = p1 < qn && p1 >= fa;  // (a probe before the first request in question brackets nothing that one does not)
       const bool q1 = in1 && (((unsigned)salive[p1 & 63] >> (p1 >> 6)) & 1u) && s1 <= room;
       const int top1 = br_uniform(skey[fa] >> BR_IDX_BITS);  // the longest request in question
-      const float F1 = br_scoreh_long_approx(p.aD, p.beta, smg, sd, HS, lane, top1, s1);
+      float pen1;
+      if constexpr (NW > 1) {  // the probes' penalty sums are shared out by offset groups (the order is free here)
+        mbox[2] = top1;
+        mbox[0] = 2;
+        __syncthreads();
+        pen1 = br_long_penalty_part(smg, sd, HS, lane, top1, s1, SHARE);
+        __syncthreads();
+#pragma unroll
+        for (int u = 1; u < NW; ++u) pen1 = __fadd_rn(pen1, __int_as_float(who[u * BR_WAVE + lane]));
+      } else {
+        pen1 = br_long_penalty_part(smg, sd, HS, lane, top1, s1, ~0ull);
+      }
+      const float F1 = br_scoreh_long_from(p.aD, p.beta, s1, pen1);
       const int k1 = q1 ? br_ord(F1) : BR_KEY_NONE;
       const int km1 = br_wave_max(k1);
       if (km1 != BR_KEY_NONE) {
@@ -352,6 +382,7 @@ __global__ __launch_bounds__(64 * NW, E == 4 ? 4 : 1) void br_k_assign_long(BrPa
     adm[pos] = (g << 16) | slot;  // every lane stores the same word
     const int jw = pos >> 6, lw = pos & 63;
     alive = (lane == lw) ? (alive & ~(1u << jw)) : alive;
+    span_dirty |= pos == span_fa || pos == span_la;
   };
 
   // load update: the admitted length enters every horizon offset of worker g; the envelope follows
@@ -430,6 +461,7 @@ __global__ __launch_bounds__(64 * NW, E == 4 ? 4 : 1) void br_k_assign_long(BrPa
         const int jf = pstar >> 6, lf = pstar & 63;
         const unsigned clear = ((1u << jf) - 1u) | ((lane <= lf) ? (1u << jf) : 0u);
         alive &= ~clear;
+        span_dirty = true;
         S_tot -= k0;
         n_alive -= k0;
         admitted += k0;
@@ -636,6 +668,7 @@ __global__ __launch_bounds__(64 * NW, E == 4 ? 4 : 1) void br_k_assign_long(BrPa
               const int e = win[b];
               const int pb = e & IDX_MASK;
               alive = (lane == (pb & 63)) ? (alive & ~(1u << (pb >> 6))) : alive;
+              span_dirty = true;
               delta += e >> BR_IDX_BITS;
             }
           br_wave_sync();  // the window has been read before a later pop rewrites it
@@ -651,6 +684,7 @@ __global__ __launch_bounds__(64 * NW, E == 4 ? 4 : 1) void br_k_assign_long(BrPa
             if ((bestmask >> b) & 1) {
               const int pb = wv[b] & IDX_MASK;
               alive = (lane == (pb & 63)) ? (alive & ~(1u << (pb >> 6))) : alive;
+              span_dirty = true;
               delta += ws[b];
             }
         }
@@ -662,6 +696,9 @@ __global__ __launch_bounds__(64 * NW, E == 4 ? 4 : 1) void br_k_assign_long(BrPa
   if constexpr (NW > 1) {
     mbox[0] = 0;  // the round is over: the helper waves leave
     __syncthreads();
+#pragma unroll
+    for (int u = 1; u < NW; ++u) who[u * BR_WAVE + lane] = -1;  // (held the helpers' partial sums)
+    br_wave_sync();
   }
 
   BrRoundCounts rc;

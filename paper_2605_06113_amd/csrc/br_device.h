@@ -391,18 +391,21 @@ __device__ __forceinline__ void br_scoreh_long_sel(float aD, float beta, const f
 
 // An approximation of the same score for one value per lane, for use where only a bound on the error matters:
 // the four offsets of a group feed four separate partial sums (independent chains instead of one), which are
-// added at the end.  Not the bits of br_scoreh_long: it has at most H / 4 + 8 roundings, each relative 2^-24 on
-// terms bounded by (alpha D + beta D) Delta, so it lies within the same distance of the exact score as the
-// ordered walk does.  `bound`: no value exceeds it (groups whose margins all lie at or above it are skipped).
-__device__ __forceinline__ float br_scoreh_long_approx(float aD, float beta, const float *m, const float *d, int HS, int lane,
-                                                       int bound, int delta) {
+// added at the end, and the groups may be shared out: br_long_penalty_part returns the penalty over the groups
+// named in `share` (bit k: offsets 4k .. 4k+3), br_scoreh_long_from the score from the sum of such parts.  Not
+// the bits of br_scoreh_long: with the parts of up to four sharers it has at most H / 4 + 12 roundings, each
+// relative 2^-24 on terms bounded by (alpha D + beta D) Delta, so it lies within the same distance of the exact
+// score as the ordered walk does.  `bound`: no value exceeds it (groups whose margins all lie at or above it are
+// skipped).
+__device__ __forceinline__ float br_long_penalty_part(const float *m, const float *d, int HS, int lane, int bound, int delta,
+                                                      unsigned long long share) {
   const float fd = (float)delta;
   float4 pen = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
   unsigned long long u;
   {
     const bool in = lane * 4 < HS;
     const float4 q = *reinterpret_cast<const float4 *>(m + (in ? lane * 4 : 0));
-    u = br_ballot(in && fminf(fminf(q.x, q.y), fminf(q.z, q.w)) < (float)bound);
+    u = br_ballot(in && fminf(fminf(q.x, q.y), fminf(q.z, q.w)) < (float)bound) & share;
   }
   BrGroupStage<2> A, B;
   A.fetch(u, m, d);
@@ -418,8 +421,11 @@ __device__ __forceinline__ float br_scoreh_long_approx(float aD, float beta, con
     for (int i = 0; i < 2; ++i)
       if (B.has[i]) br_group_add4(B.m4[i], B.d4[i], fd, pen);
   }
-  const float ps = __fadd_rn(__fadd_rn(pen.x, pen.y), __fadd_rn(pen.z, pen.w));
-  return __fsub_rn(__fmul_rn(aD, fd), __fmul_rn(beta, ps));
+  return __fadd_rn(__fadd_rn(pen.x, pen.y), __fadd_rn(pen.z, pen.w));
+}
+
+__device__ __forceinline__ float br_scoreh_long_from(float aD, float beta, int delta, float penalty) {
+  return __fsub_rn(__fmul_rn(aD, (float)delta), __fmul_rn(beta, penalty));
 }
 
 template <bool BRH>
