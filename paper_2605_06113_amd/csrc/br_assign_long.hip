@@ -152,10 +152,15 @@ __global__ __launch_bounds__(64 * NW, E == 4 ? 4 : 1) void br_k_assign_long(BrPa
   int cap = p.B - nn;
   int Lcur = act ? p.Lh[wrow * H1] : BR_LOW;  // L_g(k) + what this round admits
   int add = 0;                                // tokens admitted to this lane's worker in this round
-  for (int h0 = 0; h0 < HS; h0 += BR_WAVE) {
-    const int h = h0 + lane;
+  // envelope: lane l also keeps the offsets l, l + 64, l + 128 in registers (the LDS copy serves the reads that
+  // need other lanes' offsets); Lg: the same offsets of the step-start projection of the worker in hand
+  int Mr[3] = {0, 0, 0}, Lg[3] = {0, 0, 0};
+#pragma unroll
+  for (int u = 0; u < 3; ++u) {
+    const int h = u * BR_WAVE + lane;
     if (h < HS) {
-      sM[h] = h < H1 ? p.Mh[(int64_t)inst * H1 + h] : 0;
+      Mr[u] = h < H1 ? p.Mh[(int64_t)inst * H1 + h] : 0;
+      sM[h] = Mr[u];
       sd[h] = p.dl[h];
       smg[h] = 0.0f;
     }
@@ -213,9 +218,13 @@ __global__ __launch_bounds__(64 * NW, E == 4 ? 4 : 1) void br_k_assign_long(BrPa
   // margins of worker g against the current envelope, into smg (lanes = offsets)
   auto margins_of = [&](int g) {
     const int ag = __builtin_amdgcn_readlane(add, g);
-    for (int h0 = 0; h0 < H1; h0 += BR_WAVE) {
-      const int h = h0 + lane;
-      if (h < H1) smg[h] = (float)max(sM[h] - (sL[h * LS + g] + ag), 0);
+#pragma unroll
+    for (int u = 0; u < 3; ++u) {
+      const int h = u * BR_WAVE + lane;
+      if (h < H1) {
+        Lg[u] = sL[h * LS + g];
+        smg[h] = (float)max(Mr[u] - (Lg[u] + ag), 0);
+      }
     }
     br_wave_sync();
   };
@@ -385,14 +394,19 @@ __global__ __launch_bounds__(64 * NW, E == 4 ? 4 : 1) void br_k_assign_long(BrPa
     span_dirty |= pos == span_fa || pos == span_la;
   };
 
-  // load update: the admitted length enters every horizon offset of worker g; the envelope follows
+  // load update: the admitted length enters every horizon offset of worker g; the envelope follows.  Worker g is
+  // the one whose margins were formed last (margins_of(g)): its projections are still in Lg.
   auto add_load = [&](int g, int delta, int k) {
     add += (lane == g) ? delta : 0;
     Lcur += (lane == g) ? delta : 0;
     const int ag = __builtin_amdgcn_readlane(add, g);
-    for (int h0 = 0; h0 < H1; h0 += BR_WAVE) {
-      const int h = h0 + lane;
-      if (h < H1) sM[h] = max(sM[h], sL[h * LS + g] + ag);
+#pragma unroll
+    for (int u = 0; u < 3; ++u) {
+      const int h = u * BR_WAVE + lane;
+      if (h < H1) {
+        Mr[u] = max(Mr[u], Lg[u] + ag);
+        sM[h] = Mr[u];
+      }
     }
     br_wave_sync();
     cap -= (lane == g) ? k : 0;
