@@ -127,7 +127,7 @@ def cpu_baseline(cfg, init, arr, min_seconds=8.0):
                   us_per_instance_step=elapsed / (reps * cfg.n_inst) * 1e6,
                   sample=f"{reps} x the full batch of {cfg.n_inst} instances (route + decode step), {elapsed:.1f} s")
 
-    # (ii) all usable cores (the GPU machine gives a one-GPU job 16): the same single-threaded oracle in T worker
+    # (ii) all usable cores (os.sched_getaffinity, at most 16): the same single-threaded oracle in T worker
     # processes, one contiguous slice of the instances each (this process never touches the GPU, so it may fork)
     import multiprocessing as mp
     T = max(1, min(info["usable_cpus"], 16, cfg.n_inst))
@@ -551,7 +551,7 @@ def main():
                     help="HBM KiB per launch of the dominant kernel from rocprofv3 --pmc runs, if known")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build measures one GPU only (instances shard across GPUs with no exchange); "
+        print("bench.py: the library runs on one GPU only (instances shard across GPUs with no exchange); "
               "run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
