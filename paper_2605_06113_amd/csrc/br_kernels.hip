@@ -323,7 +323,10 @@ __global__ __launch_bounds__(256) void br_k_envelope(BrParams p) {
 // contiguous stores.  Pass B maps lanes to (request sub-slot, worker) and keeps a running best
 // request per worker, combined across lanes and waves at the end.
 // LONG (horizons beyond BR_HP): the margins keep BR_HS(H) entries per worker, the discounts sit in LDS next
-// to them and a score loops over the offsets (br_scoreh_long).
+// to them and a score loops over the offsets (br_scoreh_long), skipping the four-offset groups whose margins no
+// request of the tile reaches.  want_tile == 2 (LONG, the cluster in one block, no matrix asked for): a score
+// costs 3 (H + 1) operations here, so every pair is scored once: pass A stages its keys in the LDS tile and the
+// running best request per worker is taken from the tile, tile by tile, instead of a second scoring pass.
 template <bool BRH, bool LONG = false>
 __global__ __launch_bounds__(512) void br_k_score(BrParams p, BrArr a, BrOut o, int want_tile) {
   extern __shared__ int lds[];
@@ -372,6 +375,16 @@ __global__ __launch_bounds__(512) void br_k_score(BrParams p, BrArr a, BrOut o, 
     __syncthreads();
   }
 
+  // running best request per worker when pass B reads the staged keys (want_tile == 2): lane = (sub-slot, worker)
+  const bool once = LONG && want_tile == 2 && o.best_i;
+  int Gp1 = 1;
+  while (Gp1 < G) Gp1 <<= 1;
+  const int nsub1 = BR_WAVE / Gp1, sub1 = lane / Gp1, gl1 = lane - sub1 * Gp1;
+  const bool act1 = gl1 < G;
+  const bool free1 = act1 && scap[act1 ? gl1 : 0] > 0;
+  const int Lg1 = act1 ? sL[gl1] : 0;
+  int bk1 = BR_KEY_NONE, bs1 = 0, bi1 = -1;
+
   // pass A: one request per lane, loop over workers
   int *tile = tiles + wave * (BR_WAVE * (G + 1));
   for (int t0 = (split * nw + wave) * BR_WAVE; t0 < qn; t0 += nsplit * nw * BR_WAVE) {
@@ -379,12 +392,14 @@ __global__ __launch_bounds__(512) void br_k_score(BrParams p, BrArr a, BrOut o, 
     const bool valid = i < qn;
     const int s = valid ? ss[i] : 1;
     int bk = BR_KEY_NONE, bg = -1;
+    int tile_top[1] = {0};
+    if constexpr (LONG) tile_top[0] = br_wave_max(valid ? s : 0);  // the longest request of the tile
     for (int g = 0; g < G; ++g) {
       int key;
       if constexpr (LONG) {
         const int dv[1] = {s};
         float Fv[1];
-        br_scoreh_long<1>(p.aD, p.beta, (const float *)(sm + g * HS), sd, HS, dv, Fv);
+        br_scoreh_long_sel<1>(p.aD, p.beta, (const float *)(sm + g * HS), sd, HS, lane, tile_top, dv, Fv);
         key = br_ord(Fv[0]);
       } else {
         int m[BR_HP + 1];
@@ -400,7 +415,22 @@ __global__ __launch_bounds__(512) void br_k_score(BrParams p, BrArr a, BrOut o, 
       }
     }
     if (valid && o.best_g) o.best_g[(int64_t)inst * p.Q + i] = bg;
-    if (want_tile) {
+    if (once) {  // this tile's keys against the running best of every worker (ascending requests within a lane)
+      br_wave_sync();
+      const int rows = min(BR_WAVE, qn - t0);
+      for (int r = sub1; r < rows; r += nsub1) {
+        const int sr = ss[t0 + r];
+        const int key = tile[r * (G + 1) + (act1 ? gl1 : 0)];
+        const bool ok = free1 && (p.W <= 0 || Lg1 + sr <= p.W);
+        if (ok && (key > bk1 || (key == bk1 && sr > bs1))) {
+          bk1 = key;
+          bs1 = sr;
+          bi1 = t0 + r;
+        }
+      }
+      br_wave_sync();  // the tile is rewritten by the wave's next trip
+    }
+    if (want_tile == 1) {
       const int rows = min(BR_WAVE, qn - t0);
       int *Fi = (int *)o.F + ((int64_t)inst * p.Q + t0) * G;
       for (int e = lane; e < rows * G; e += BR_WAVE) {
@@ -427,7 +457,8 @@ __global__ __launch_bounds__(512) void br_k_score(BrParams p, BrArr a, BrOut o, 
     const int Lg = act ? sL[g] : 0;
     const bool free_slot = act && scap[g] > 0;
     int bk = BR_KEY_NONE, bs = 0, bi = -1;
-    for (int i = wave * nsub + sub; i < qn; i += nw * nsub) {
+    if (once) bk = bk1, bs = bs1, bi = bi1;  // (one block holds the cluster: the lane layout is the one above)
+    for (int i = wave * nsub + sub; i < qn && !once; i += nw * nsub) {
       const int s = ss[i];
       int key;
       if constexpr (LONG) {  // lanes hold different workers: each reads its own row of margins
@@ -876,20 +907,26 @@ static void br_launch_reductions(const BrParams &p, const BrArr &a, const BrOut 
     }
     return;
   }
-  auto lds_words = [&](int w) {
+  auto lds_words = [&](int w, bool tile) {
     const size_t HS = longh ? BR_HS(p.H) : BR_HP + 1;
     size_t words = (size_t)p.G * HS + (longh ? HS : 0) + 2 * (size_t)p.G + (size_t)p.Q + 3 * 64 * (size_t)w;
-    if (want_tile) words += (size_t)w * 64 * (size_t)(p.G + 1);
+    if (tile) words += (size_t)w * 64 * (size_t)(p.G + 1);
     return words;
   };
-  while (waves > 1 && lds_words(waves) * 4 > 60 * 1024) --waves;  // stay within the default 64 KiB of LDS per block
-  const size_t lds = lds_words(waves) * 4;
+  while (waves > 1 && lds_words(waves, want_tile) * 4 > 60 * 1024) --waves;  // stay within the default 64 KiB of LDS per block
+  size_t lds = lds_words(waves, want_tile) * 4;
   // few clusters: spread each over several blocks (at most 8, at most one per worker) to fill more CUs
   int nsplit = 1;
   while (nsplit < 8 && nsplit * 2 <= p.G && (int64_t)p.N * nsplit * 2 <= 512 && p.Q > 64 * waves * nsplit) nsplit *= 2;
   const dim3 grid((unsigned)p.N, (unsigned)nsplit);
+  // long horizons, the cluster in one block, room for the staged keys: every pair is scored once
+  int mode = want_tile;
+  if (longh && !want_tile && nsplit == 1 && o.best_i && lds_words(waves, true) * 4 <= 60 * 1024) {
+    mode = 2;
+    lds = lds_words(waves, true) * 4;
+  }
   if (longh)
-    hipLaunchKernelGGL((br_k_score<true, true>), grid, dim3(64 * waves), lds, st, p, a, o, want_tile);
+    hipLaunchKernelGGL((br_k_score<true, true>), grid, dim3(64 * waves), lds, st, p, a, o, mode);
   else if (p.H > 0)
     hipLaunchKernelGGL(br_k_score<true>, grid, dim3(64 * waves), lds, st, p, a, o, want_tile);
   else
