@@ -1,6 +1,6 @@
 // Two-stage assignment of one scheduling round for horizons beyond the offsets the register kernel
 // carries (Appendix, Alg. BR-H; H up to 128, the deployed value of Sec. 6 is 80), one wavefront per
-// cluster.
+// cluster runs the round (others may serve its searches, below).
 //
 // The round is the loop of Alg. BR-H: Stage 1 gives the worker with the most free slots (then the
 // lightest, then the lowest index) its best single request while free capacity exceeds S_greedy (taken a
@@ -15,20 +15,24 @@
 //     admission adds its length at every offset (constant-s approximation of Sec. 4.1), so worker g's
 //     current projection is sL[h][g] + add_g with one register add_g per lane;
 //   - the envelope M_h and the margins of the worker in hand are LDS arrays maintained with lanes
-//     mapped to offsets;
-//   - a score walks the offsets in order with margins and discounts broadcast from LDS, four per load,
-//     for four waiting requests (or four subset sums) per lane at a time, and skips the groups of offsets
-//     whose margins no request in question reaches (exact zeros; br_long_active, br_scoreh_long_act).
+//     mapped to offsets (lane l also keeps the envelope at offsets l, l + 64, l + 128 and the projections of
+//     the worker in hand in registers, so that the update after an admission needs no LDS read);
+//   - a score walks the offsets in order with margins and discounts broadcast from LDS, four per load, and
+//     skips the groups of offsets whose margins no value in question reaches (exact zeros);
+//   - the single best request argmax_i F_g({i}) is found by bracketing, not by scoring the whole waiting set
+//     (pick_single: the score is concave in the length, the waiting set is sorted by length);
+//   - Stage 2 goes straight to the starvation guard when the window's smallest entry scores clearly below
+//     zero (then every subset does).
 // Waiting set, sticky binding, epilogue and the optional decode steps are those of the short-horizon
 // kernel (br_sort.h, br_assign_common.h).
 //
-// With fewer clusters than the chip has room for waves (NW = 2 or 4 waves per cluster) the search
-// argmax_i F_g({i}), which is most of a round at these horizons, is shared: wave 0 runs the round; for each
-// search it posts the admissible length and the alive bits in LDS (the margins are there already), every wave
-// scores its share of the sorted positions between two block barriers, and wave 0 takes the best of the
-// partial results (the share of a later wave holds higher positions, so only a strictly better score wins).
-// The helper waves leave when wave 0 posts the end of the round; decode steps then follow as a launch of
-// their own.
+// With fewer clusters than the chip has room for waves (NW = 2 or 4 waves per cluster) the searches, which
+// are most of a round at these horizons, are shared: wave 0 runs the round and posts a command in LDS (the
+// margins are there already), every wave does its share between two block barriers: of the probes' offset
+// groups in a bracketing search (the order of that sum is free), or of the sorted positions in a full scan
+// (wave 0 takes the best of the partial results; the share of a later wave holds higher positions, so only a
+// strictly better score wins).  The helper waves leave when wave 0 posts the end of the round; decode steps
+// then follow as a launch of their own.
 #include "br_device.h"
 #include "br_launch.h"
 #include "br_sort.h"
