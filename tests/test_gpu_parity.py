@@ -128,6 +128,12 @@ CASES = [
     (8, 16, 96, 80, dict(pred_mode=3, gate_pfin=0.5, gamma=0.97)),
     # the largest LDS footprint: longest queue, longest horizon, widest window
     (3, 6, 2048, 128, dict(pred_mode=1, R_max=16, gamma=0.99)),
+    # many equal lengths at long horizons: the bracketing search cannot separate equal scores and hands over to
+    # the full scan (shared by the cluster's waves), for every queue size class
+    (8, 24, 256, 40, dict(pred_mode=1, tie_heavy=True)),
+    (5, 30, 512, 24, dict(pred_mode=1, tie_heavy=True, gamma=1.0)),
+    (9, 20, 1024, 100, dict(pred_mode=3, tie_heavy=True, gate_pfin=0.0)),
+    (4, 40, 2048, 16, dict(pred_mode=1, tie_heavy=True, token_watermark=30000)),
 ]
 
 
