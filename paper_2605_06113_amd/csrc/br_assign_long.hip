@@ -287,7 +287,14 @@ __global__ __launch_bounds__(64 * NW, E == 4 ? 4 : 1) void br_k_assign_long(BrPa
   // everything left out computes strictly below a score that was kept.
   int span_fa = -1, span_la = -1;
   bool span_dirty = true;
-  auto pick_single = [&](int room, int &pos, int &swin) -> bool {
+  // `sure_pos` >= 0 (Stage 2): the sorted position of the window's smallest entry.  The search then first decides,
+  // from the probe at or after that position (a request no longer than that entry), whether the pop is certain to
+  // end in the starvation guard: eq. (brh-Fscore) is concave with F(0) = 0, so F(Delta) <= F(s) Delta / s for every
+  // Delta >= s; if that probe scores at or below -3 e(s) in the order-free evaluation, its exact score is at or
+  // below -2 e(s), every subset of the window (all of them sum to at least s) has an exact score at or below
+  // -2 e(Delta) and computes below zero.  If so the search goes on and returns the guard's pick; if not, it stops
+  // with *unsure set and the caller enumerates the subsets.
+  auto pick_single = [&](int room, int &pos, int &swin, int sure_pos = -1, bool *unsure = nullptr) -> bool {
     int bk, bp, km;
     {
       // first and last sorted position of a request in question: kept from search to search while the alive set
@@ -307,7 +314,7 @@ __global__ __launch_bounds__(64 * NW, E == 4 ? 4 : 1) void br_k_assign_long(BrPa
         span_dirty = false;
       }
       const int fa = span_fa, la = span_la;
-      if (fa < 0) return false;
+      if (fa < 0) return false;  // (no request in question: no subset of the window is admissible either)
       salive[lane] = (int)alive;
       br_wave_sync();
       const int p1 = lane * E;  // probe position
@@ -329,6 +336,20 @@ __global__ __launch_bounds__(64 * NW, E == 4 ? 4 : 1) void br_k_assign_long(BrPa
         pen1 = br_long_penalty_part(smg, sd, HS, lane, top1, s1, ~0ull);
       }
       const float F1 = br_scoreh_long_from(p.aD, p.beta, s1, pen1);
+      if (sure_pos >= 0) {
+        const int lw = (sure_pos + E - 1) / E;  // first probe at or after the window's smallest entry
+        bool sure = false;
+        if (lw < BR_WAVE && lw * E < qn) {
+          const float Fw = __builtin_amdgcn_readlane(F1, lw);
+          const int sw = __builtin_amdgcn_readlane(s1, lw);
+          sure = Fw <= -3.0f * err_unit * (float)sw;
+        }
+        if (!sure) {
+          *unsure = true;
+          br_wave_sync();
+          return false;
+        }
+      }
       const int k1 = q1 ? br_ord(F1) : BR_KEY_NONE;
       const int km1 = br_wave_max(k1);
       if (km1 != BR_KEY_NONE) {
@@ -507,12 +528,6 @@ __global__ __launch_bounds__(64 * NW, E == 4 ? 4 : 1) void br_k_assign_long(BrPa
 #pragma unroll
     for (int b = 0; b < 6; ++b) lbit[b] = (lane >> b) & 1;
     const int lpop = __builtin_popcount(lane);
-    // Certain guard: eq. (brh-Fscore) is concave in Delta with F(0) = 0, so F(Delta) <= F(s) Delta / s for every
-    // Delta >= s, and every subset of the window sums to at least the window's smallest entry s.  With the rounding
-    // bound e(Delta) = err_unit Delta (above): if the smallest entry's computed score is at or below -2 e(s), its
-    // exact score is below -e(s), every subset's exact score below -e(Delta) and every subset's computed score
-    // below zero: the pop goes to the starvation guard without the enumeration.
-    const float guard_eps = 2.0f * err_unit;
     for (int it = 0; it < bound; ++it) {
       if (n_alive <= 0) break;
       const int capmax = br_wave_max(cap);
@@ -546,13 +561,11 @@ __global__ __launch_bounds__(64 * NW, E == 4 ? 4 : 1) void br_k_assign_long(BrPa
       const int nmask = 1 << w;
       int bestmask = 0, bestkey = BR_KEY_NONE;
       int wv[8], ws[8];
-      bool guard_sure;
-      {
-        const int s_last[1] = {br_uniform(win[w - 1] >> BR_IDX_BITS)};
-        float F1[1];
-        br_scoreh_long_sel<1>(p.aD, p.beta, smg, sd, HS, lane, s_last, s_last, F1);
-        guard_sure = F1[0] <= -guard_eps * (float)s_last[0];
-      }
+      // certain guard (decided inside the search from its probes): then `picked` holds the guard's pick already
+      int gpos = 0, gswin = 0;
+      bool unsure = false;
+      const bool picked = pick_single(room, gpos, gswin, br_uniform(win[w - 1] & IDX_MASK), &unsure);
+      const bool guard_sure = !unsure;
       if (guard_sure) {
         br_wave_sync();  // the window has been read before a later pop rewrites it
       } else if (p.R_max > 8) {
@@ -667,8 +680,8 @@ __global__ __launch_bounds__(64 * NW, E == 4 ? 4 : 1) void br_k_assign_long(BrPa
 
       if (bestmask == 0 || bestkey <= 0) {  // starvation guard: the single best request anyway
         ++guard;
-        int pos = 0, swin = 0;
-        if (!pick_single(room, pos, swin)) {
+        int pos = gpos, swin = gswin;
+        if (!(guard_sure ? picked : pick_single(room, pos, swin))) {
           drop_worker(g, capmax);
           continue;
         }
