@@ -229,12 +229,15 @@ int32_t br_route_step(br_ctx *ctx, const br_arrivals *in, const br_step_out *out
 int32_t br_advance_decode(br_ctx *ctx, int32_t n_steps);
 
 /*
- * One decode step of the serving loop in a single launch: the round of br_route_step followed by
+ * One decode step of the serving loop in a single call: the round of br_route_step followed by
  * n_steps decode steps of br_advance_decode (Sec. 2.2; Alg. BR-0 / Alg. BR-H), with exactly their
  * results: same outputs (written as br_route_step writes them, statistics describe the state
  * right after the round) and same workspace contents afterwards as the two calls in sequence.
- * The wave that has routed a cluster applies the decode steps to that cluster's lists, so clusters
- * that finish their round early stream their lists while others are still routing.
+ * Where the shape allows, the assignment launch itself applies the decode steps (the wave that has
+ * routed a cluster goes on to that cluster's lists, so clusters that finish their round early stream
+ * their lists while others are still routing; small BR-0 batches use a second wave per cluster for
+ * them); candidate windows beyond 8 requests and long-horizon rounds that several waves share are
+ * followed by the decode kernel as a launch of its own on the same stream.
  * Arguments, ownership and errors as for br_route_step; n_steps >= 0 (0: identical to
  * br_route_step), BR_EINVAL otherwise.
  */
