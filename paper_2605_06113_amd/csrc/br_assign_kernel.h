@@ -50,6 +50,44 @@ struct Log2E {
   static constexpr int v = E == 4 ? 2 : E == 8 ? 3 : E == 16 ? 4 : 5;
 };
 
+// Subset scan of a window of up to 16 requests (Stage 2, BIGR), this wave's share of it: lane l keeps the lower
+// six mask bits, the upper bits c run as passes over the table `hitab` of their partial sums, four passes per
+// trip; the wave takes the trips wv, wv + nwv, ... (trips whose upper bits alone exceed the cardinality limit are
+// skipped).  A lane sees its masks in ascending order and keeps the first best: returns the lane's best key and
+// its lowest mask.
+template <bool BRH>
+__device__ __forceinline__ void br_bigr_scan(const BrParams &p, const int (&mg)[BR_HP + 1], const int *win, const int *hitab,
+                                             int w, int kmax, int room, int lane, int wv, int nwv, int &bk, int &bm) {
+  const int nhi = w > 6 ? 1 << (w - 6) : 1;
+  const int nmask = 1 << w;
+  int base = 0;
+  for (int b = 0; b < min(w, 6); ++b) base += ((lane >> b) & 1) * (win[b] >> BR_IDX_BITS);
+  const int klim = kmax - __builtin_popcount(lane);  // bits the upper part of a mask may still add on this lane
+  const bool lane_ok = lane < nmask;                  // (windows below six requests use the lower lanes only)
+  bk = BR_KEY_NONE, bm = INT32_MAX;
+  for (int c0 = 4 * wv; c0 < nhi; c0 += 4 * nwv) {  // four passes per trip: one 16-byte table read, independent scores
+    if (__builtin_popcount(c0) > kmax) continue;     // c0 + u has at least the bits of c0: too many for every lane
+    const int4 h4 = *reinterpret_cast<const int4 *>(hitab + c0);
+    const int hd[4] = {h4.x, h4.y, h4.z, h4.w};
+    int key[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int c = c0 + u;
+      const int delta = base + hd[u];
+      bool ok = lane_ok && c < nhi && __builtin_popcount(c) <= klim && delta <= room;
+      if (c == 0) ok = ok && lane != 0;  // the empty subset
+      const int k = br_score_key<BRH>(p, mg, ok ? delta : 0);
+      key[u] = ok ? k : BR_KEY_NONE;
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+      if (key[u] > bk) {
+        bk = key[u];
+        bm = (c0 + u) * BR_WAVE + lane;
+      }
+  }
+}
+
 // One cluster's round on one wave.  `lds`: this wave's 3*E*64 + 72 words.  COOP (queues of up to 2048):
 // the block has four waves; all of them sort the waiting set together (br_sort_desc_block4), wave 0 runs
 // the round with the sorted keys read back from LDS and hands every full search over the waiting set
@@ -59,8 +97,11 @@ template <int E, bool BRH, bool ADV, bool COOP = false, bool BIGR = false>
 // prefill lengths in arrival order, worker loads and counts), or null: the round then loads them itself.
 // `split`: the cluster's BR_SPLIT_WORDS of LDS in a split kernel (another wave applies the decode steps to the old
 // list entries meanwhile), or null.
+// `shared` (BIGR without COOP, one cluster per block of four waves): waves 1-3 serve the subset scans of wave 0,
+// every fourth trip each, through the mailbox `svc` and two block barriers per scan.
 __device__ __forceinline__ void br_assign_body(const BrParams &p, const BrArr &a, const BrOut &o, int *lds, int inst,
-                                               int w = 0, const BrScoreIn<E, BRH> *pre = nullptr, int *split = nullptr) {
+                                               int w = 0, const BrScoreIn<E, BRH> *pre = nullptr, int *split = nullptr,
+                                               bool shared = false) {
   static_assert(!COOP || E == 32, "the four-wave sort covers 4 x 512 keys");
   constexpr int NP = E * BR_WAVE;
   constexpr int NH = BRH ? BR_HP + 1 : 1;
@@ -84,6 +125,24 @@ __device__ __forceinline__ void br_assign_body(const BrParams &p, const BrArr &a
   int *sres = salive + BR_WAVE;             // [8]  per wave: best key, its lowest sorted position
 
   const int lane = br_lane();
+  if constexpr (BIGR && !COOP) {
+    if (shared && w != 0) {  // one pass per scan; every wave of the block meets at both barriers, wave 0 ends the loop
+      for (;;) {
+        __syncthreads();
+        if (svc[0] == 0) break;
+        int mgq[BR_HP + 1];
+#pragma unroll
+        for (int h = 0; h <= BR_HP; ++h) mgq[h] = svc[1 + h];
+        int bk, bm;
+        br_bigr_scan<BRH>(p, mgq, win, hitab, svc[3 + BR_HP], svc[4 + BR_HP], svc[2 + BR_HP], lane, w, 4, bk, bm);
+        const int km = br_wave_max(bk);
+        const int mm = km == BR_KEY_NONE ? INT32_MAX : br_wave_min(bk == km ? bm : INT32_MAX);
+        if (lane == 0) svc[16 + 2 * w] = km, svc[17 + 2 * w] = mm;
+        __syncthreads();
+      }
+      return;
+    }
+  }
   const int G = p.G;
   int q0, cnt;
   if (pre) {
@@ -722,37 +781,33 @@ __device__ __forceinline__ void br_assign_body(const BrParams &p, const BrArr &a
             for (int b = 6; b < w; ++b) sum += ((c >> (b - 6)) & 1) * (win[b] >> BR_IDX_BITS);
             if (c < nhi) hitab[c] = sum;
           }
-          int base = 0;
-          for (int b = 0; b < min(w, 6); ++b) base += ((lane >> b) & 1) * (win[b] >> BR_IDX_BITS);
           br_wave_sync();
           const int kmax = min(capmax, p.R_max);
-          const int nmask = 1 << w;
-          int bk = BR_KEY_NONE, bm = INT32_MAX;
-          const int klim = kmax - lpop;         // bits the upper part of a mask may still add on this lane
-          const bool lane_ok = lane < nmask;    // (windows below six requests use the lower lanes only)
-          for (int c0 = 0; c0 < nhi; c0 += 4) {  // four passes per trip: one 16-byte table read, independent scores
-            if (__builtin_popcount(c0) > kmax) continue;  // c0 + u has at least the bits of c0: too many for every lane
-            const int4 h4 = *reinterpret_cast<const int4 *>(hitab + c0);
-            const int hd[4] = {h4.x, h4.y, h4.z, h4.w};
-            int key[4];
+          int bk, bm;
+          bool shared_scan = false;
+          if constexpr (!COOP) shared_scan = shared && nhi >= 16;  // (a few trips are not worth two barriers)
+          if (shared_scan) {
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-              const int c = c0 + u;
-              const int delta = base + hd[u];
-              bool ok = lane_ok && c < nhi && __builtin_popcount(c) <= klim && delta <= room;
-              if (c == 0) ok = ok && lane != 0;  // the empty subset
-              const int k = br_score_key<BRH>(p, mg, ok ? delta : 0);
-              key[u] = ok ? k : BR_KEY_NONE;
-            }
-#pragma unroll
-            for (int u = 0; u < 4; ++u)
-              if (key[u] > bk) {
-                bk = key[u];
-                bm = (c0 + u) * BR_WAVE + lane;
-              }
+            for (int h = 0; h <= BR_HP; ++h) svc[1 + h] = mg[h];
+            svc[2 + BR_HP] = room, svc[3 + BR_HP] = w, svc[4 + BR_HP] = kmax;
+            svc[0] = 1;
+            __syncthreads();
+            br_bigr_scan<BRH>(p, mg, win, hitab, w, kmax, room, lane, 0, 4, bk, bm);
+          } else {
+            br_bigr_scan<BRH>(p, mg, win, hitab, w, kmax, room, lane, 0, 1, bk, bm);
           }
           bestkey = br_wave_max(bk);
           bestmask = bestkey == BR_KEY_NONE ? 0 : br_wave_min(bk == bestkey ? bm : INT32_MAX);
+          if (shared_scan) {  // the best of the four shares: lowest mask among equal scores
+            __syncthreads();
+            int mbest = bestkey == BR_KEY_NONE ? INT32_MAX : bestmask;
+#pragma unroll
+            for (int u = 1; u < 4; ++u) {
+              const int ku = svc[16 + 2 * u], mu = svc[17 + 2 * u];
+              if (ku > bestkey || (ku == bestkey && mu < mbest)) bestkey = ku, mbest = mu;
+            }
+            bestmask = bestkey == BR_KEY_NONE ? 0 : mbest;
+          }
         }
       } else if (!guard_sure) {
         br_wave_sync();
@@ -869,6 +924,12 @@ __device__ __forceinline__ void br_assign_body(const BrParams &p, const BrArr &a
   rc.guard = guard;
   rc.wdrop = wdrop;
   rc.I_before = I_before;
+  if constexpr (BIGR && !COOP) {
+    if (shared) {
+      svc[0] = 0;  // the round is over: the waves that served the scans leave
+      __syncthreads();
+    }
+  }
   if constexpr (COOP) {
     svc[0] = 0;  // the round is over: the waves that served the searches go on to the epilogue
     __syncthreads();
@@ -896,12 +957,15 @@ __device__ __forceinline__ void br_assign_body(const BrParams &p, const BrArr &a
 // BIGR: candidate windows of 9..16 requests (R_max > 8); a separate instantiation so that the kernels for
 // the deployed window sizes keep their registers and code size.
 template <int E, bool BRH, bool ADV, bool BIGR = false>
-__global__ __launch_bounds__(256, (BRH && E == 8 && !BIGR) ? 4 : 1) void br_k_assign(BrParams p, BrArr a, BrOut o) {
+// `share` (BIGR, queues of up to 1024): one cluster per block, its four waves share the subset scans
+__global__ __launch_bounds__(256, (BRH && E == 8 && !BIGR) ? 4 : 1) void br_k_assign(BrParams p, BrArr a, BrOut o, int share) {
   extern __shared__ int lds_all[];
   constexpr int WORDS = 3 * E * BR_WAVE + BR_WAVE + (BIGR ? 32 + 1024 : 8) + (E == 32 ? 96 : 0);  // skey, adm, who, slots, win (+ table, + mailbox) per wave
   const int w = threadIdx.x >> 6;
   if constexpr (E == 32)  // one cluster per block, four waves for the sort
     br_assign_body<E, BRH, ADV, true, BIGR>(p, a, o, lds_all, (int)blockIdx.x, w);
+  else if (BIGR && share)
+    br_assign_body<E, BRH, ADV, false, BIGR>(p, a, o, lds_all, (int)blockIdx.x, w, nullptr, nullptr, true);
   else
     br_assign_body<E, BRH, ADV, false, BIGR>(p, a, o, lds_all + w * WORDS, (int)(blockIdx.x * (blockDim.x >> 6)) + w);
 }
@@ -915,12 +979,20 @@ static void br_launch_assign_one(const BrParams &p, const BrArr &a, const BrOut 
                       (dp ? BR_DP_LDS_WORDS : 0)) * sizeof(int);
   const dim3 grid((unsigned)((p.N + wpb - 1) / wpb)), block(E == 32 ? 4 * BR_WAVE : BR_WAVE * wpb);
   if constexpr (BIGR) {  // no fused decode steps for these: the caller launches the decode kernel
-    hipLaunchKernelGGL((br_k_assign<E, BRH, false, true>), grid, block, lds, st, p, a, o);
+    // windows of 9..16 requests on a batch that leaves room on the chip (registers allow about 4 / 3 / 2 waves per
+    // SIMD for queues of up to 256 / 512 / 1024, one less for BR-H): a block of four waves per cluster, the scans shared
+    const long long room = 1024ll * max(1, (E == 4 ? 4 : E == 8 ? 3 : 2) - (BRH ? 1 : 0));
+    if (E <= 16 && !dp && (long long)p.N * 4 <= room) {
+      const size_t lds1 = ((size_t)3 * E * BR_WAVE + BR_WAVE + 32 + 1024 + 32) * sizeof(int);
+      hipLaunchKernelGGL((br_k_assign<E, BRH, false, true>), dim3((unsigned)p.N), dim3(4 * BR_WAVE), lds1, st, p, a, o, 1);
+    } else {
+      hipLaunchKernelGGL((br_k_assign<E, BRH, false, true>), grid, block, lds, st, p, a, o, 0);
+    }
   } else {
     if (p.adv_t > 0)
-      hipLaunchKernelGGL((br_k_assign<E, BRH, true>), grid, block, lds, st, p, a, o);
+      hipLaunchKernelGGL((br_k_assign<E, BRH, true>), grid, block, lds, st, p, a, o, 0);
     else
-      hipLaunchKernelGGL((br_k_assign<E, BRH, false>), grid, block, lds, st, p, a, o);
+      hipLaunchKernelGGL((br_k_assign<E, BRH, false>), grid, block, lds, st, p, a, o, 0);
   }
 }
 
