@@ -97,8 +97,9 @@ template <int E, bool BRH, bool ADV, bool COOP = false, bool BIGR = false>
 // prefill lengths in arrival order, worker loads and counts), or null: the round then loads them itself.
 // `split`: the cluster's BR_SPLIT_WORDS of LDS in a split kernel (another wave applies the decode steps to the old
 // list entries meanwhile), or null.
-// `shared` (BIGR without COOP, one cluster per block of four waves): waves 1-3 serve the subset scans of wave 0,
-// every fourth trip each, through the mailbox `svc` and two block barriers per scan.
+// `shared` (BIGR without COOP, one cluster per block of four waves): waves 1-3 serve the subset searches of wave 0
+// (every fourth trip of a mask scan, every fourth run of 64 words of the rows of reachable sums) through the
+// mailbox `svc` and two block barriers per search.
 __device__ __forceinline__ void br_assign_body(const BrParams &p, const BrArr &a, const BrOut &o, int *lds, int inst,
                                                int w = 0, const BrScoreIn<E, BRH> *pre = nullptr, int *split = nullptr,
                                                bool shared = false) {
@@ -120,7 +121,7 @@ __device__ __forceinline__ void br_assign_body(const BrParams &p, const BrArr &a
   // COOP: mailbox of the searches that wave 0 hands to all four waves (one per 512 sorted positions)
   int *svc = win + (BIGR ? 32 + 1024 : 8);  // [16] 0: 1 = search, 0 = round over; 1..9: margins; 10: room
   // BIGR with windows beyond 16 requests: bit rows of the subset search (present when R_max > 16), after the rest
-  int *dprows = lds + 3 * NP + BR_WAVE + 32 + 1024 + (COOP ? 96 : 0);
+  int *dprows = lds + 3 * NP + BR_WAVE + 32 + 1024 + (COOP ? 96 : (shared ? 32 : 0));
   int *salive = svc + 16;                   // [64] wave 0's alive bits, one word per lane
   int *sres = salive + BR_WAVE;             // [8]  per wave: best key, its lowest sorted position
 
@@ -129,15 +130,20 @@ __device__ __forceinline__ void br_assign_body(const BrParams &p, const BrArr &a
     if (shared && w != 0) {  // one pass per scan; every wave of the block meets at both barriers, wave 0 ends the loop
       for (;;) {
         __syncthreads();
-        if (svc[0] == 0) break;
-        int mgq[BR_HP + 1];
+        const int cmd = svc[0];
+        if (cmd == 0) break;
+        if (cmd == 2) {  // this wave's words of the rows of reachable sums
+          br_dp_build_helper(p, win, svc, dprows, p.dp + (size_t)inst * br_dp_cluster_words(min(p.B, p.R_max)), lane, w);
+        } else {         // this wave's trips of a mask scan
+          int mgq[BR_HP + 1];
 #pragma unroll
-        for (int h = 0; h <= BR_HP; ++h) mgq[h] = svc[1 + h];
-        int bk, bm;
-        br_bigr_scan<BRH>(p, mgq, win, hitab, svc[3 + BR_HP], svc[4 + BR_HP], svc[2 + BR_HP], lane, w, 4, bk, bm);
-        const int km = br_wave_max(bk);
-        const int mm = km == BR_KEY_NONE ? INT32_MAX : br_wave_min(bk == km ? bm : INT32_MAX);
-        if (lane == 0) svc[16 + 2 * w] = km, svc[17 + 2 * w] = mm;
+          for (int h = 0; h <= BR_HP; ++h) mgq[h] = svc[1 + h];
+          int bk, bm;
+          br_bigr_scan<BRH>(p, mgq, win, hitab, svc[3 + BR_HP], svc[4 + BR_HP], svc[2 + BR_HP], lane, w, 4, bk, bm);
+          const int km = br_wave_max(bk);
+          const int mm = km == BR_KEY_NONE ? INT32_MAX : br_wave_min(bk == km ? bm : INT32_MAX);
+          if (lane == 0) svc[16 + 2 * w] = km, svc[17 + 2 * w] = mm;
+        }
         __syncthreads();
       }
       return;
@@ -769,8 +775,10 @@ __device__ __forceinline__ void br_assign_body(const BrParams &p, const BrArr &a
           // windows of 17..32 requests: reachable sums instead of masks (br_subset_dp.h)
           br_wave_sync();
           unsigned dm = 0u;
+          int *share = nullptr;
+          if constexpr (!COOP) share = shared ? svc : nullptr;
           br_subset_dp<BRH>(p, mg, win, w, min(capmax, p.R_max), room, lane, dprows,
-                            p.dp + (size_t)inst * br_dp_cluster_words(min(p.B, p.R_max)), dm, bestkey);
+                            p.dp + (size_t)inst * br_dp_cluster_words(min(p.B, p.R_max)), dm, bestkey, share);
           bestmask = (int)dm;
         } else if (!guard_sure) {
           br_wave_sync();
@@ -982,8 +990,8 @@ static void br_launch_assign_one(const BrParams &p, const BrArr &a, const BrOut 
     // windows of 9..16 requests on a batch that leaves room on the chip (registers allow about 4 / 3 / 2 waves per
     // SIMD for queues of up to 256 / 512 / 1024, one less for BR-H): a block of four waves per cluster, the scans shared
     const long long room = 1024ll * max(1, (E == 4 ? 4 : E == 8 ? 3 : 2) - (BRH ? 1 : 0));
-    if (E <= 16 && !dp && (long long)p.N * 4 <= room) {
-      const size_t lds1 = ((size_t)3 * E * BR_WAVE + BR_WAVE + 32 + 1024 + 32) * sizeof(int);
+    if (E <= 16 && (long long)p.N * 4 <= room) {
+      const size_t lds1 = ((size_t)3 * E * BR_WAVE + BR_WAVE + 32 + 1024 + 32 + (dp ? BR_DP_LDS_WORDS : 0)) * sizeof(int);
       hipLaunchKernelGGL((br_k_assign<E, BRH, false, true>), dim3((unsigned)p.N), dim3(4 * BR_WAVE), lds1, st, p, a, o, 1);
     } else {
       hipLaunchKernelGGL((br_k_assign<E, BRH, false, true>), grid, block, lds, st, p, a, o, 0);

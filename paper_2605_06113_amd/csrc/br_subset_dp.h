@@ -96,13 +96,90 @@ __device__ __forceinline__ unsigned br_dp_mask_of(const unsigned char *first, co
   return mask;
 }
 
+// The rows of reachable sums for the window `win` (w requests), at most kmax per subset, sums up to R (nw words per
+// row, `stride` words between rows), and the first-request table.  nwv waves may share the work (LDS rows of one
+// block): wave wv takes the words lane + 64 (wv + nwv t) of every row, and `sync` is then a block barrier: row
+// j-1 is rewritten only after every wave has read it for row j.  UN words per lane and trip.
+template <int UN, class RowPtr, class Sync>
+__device__ __forceinline__ void br_dp_build(const int *win, int w, int kmax, int R, int nw, RowPtr rows, int stride,
+                                            unsigned char *first, int lane, int wv, int nwv, Sync sync) {
+  constexpr int RW = BR_DP_ROW_WORDS;
+  const unsigned lastmask = (R & 31) == 31 ? 0xffffffffu : (2u << (R & 31)) - 1u;
+  for (int j = 0; j <= kmax; ++j)
+    for (int i = lane + BR_WAVE * wv; i < nw; i += BR_WAVE * nwv) rows[j * stride + i] = i == 0 ? 1 : 0;  // the empty subset
+  sync();
+  for (int b = 0; b < w; ++b) {
+    const int s = win[b] >> BR_IDX_BITS;
+    if (s > R) continue;  // every subset that holds it lies beyond the rows
+    const int q = s >> 5, r = s & 31;
+    // every row takes every request: row j then always contains row j-1 ("at most j requests")
+    for (int j = kmax; j >= 1; --j) {
+      auto src = rows + (j - 1) * stride;
+      auto dst = rows + j * stride;
+      unsigned char *fj = first + (size_t)(j - 1) * (RW * 32);
+      for (int i0 = q + lane + BR_WAVE * wv; i0 < nw; i0 += UN * BR_WAVE * nwv) {
+        unsigned lo[UN], hi[UN], old[UN];
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+          const int i = i0 + u * BR_WAVE * nwv;
+          const bool in = i < nw;
+          lo[u] = in ? (unsigned)src[i - q] : 0u;
+          hi[u] = (in && i - q >= 1) ? (unsigned)src[i - q - 1] : 0u;
+          old[u] = in ? (unsigned)dst[i] : 0u;
+        }
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+          const int i = i0 + u * BR_WAVE * nwv;
+          unsigned v = r ? (lo[u] << r) | (hi[u] >> (32 - r)) : lo[u];
+          if (i == nw - 1) v &= lastmask;
+          unsigned fresh = v & ~old[u];
+          if (i < nw && fresh != 0u) {
+            dst[i] = (int)(old[u] | fresh);
+            while (fresh != 0u) {
+              const int bit = (int)__builtin_ctz(fresh);
+              fresh &= fresh - 1u;
+              fj[i * 32 + bit] = (unsigned char)b;
+            }
+          }
+        }
+      }
+      // row j-1 is rewritten next, after every lane has read it here; row j is read again by the next request
+      sync();
+    }
+  }
+}
+
+// Between the rows of a build that a block shares in the workspace: every wave's stores to the row just written are
+// visible to the others before any of them goes on.
+__device__ __forceinline__ void br_dp_sync_ws() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  __syncthreads();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+}
+
+// A helper wave's part of a shared build: the plan comes from the mailbox `svc` (words 11..15: w, kmax, R, nw,
+// 1 = rows in the workspace), as wave 0 posted it in br_subset_dp.
+__device__ __forceinline__ void br_dp_build_helper(const BrParams &p, const int *win, const int *svc, int *rows_lds, int *ws,
+                                                   int lane, int wv) {
+  const int KM = min(p.B, p.R_max);
+  unsigned char *first = (unsigned char *)(ws + (size_t)(KM + 1) * BR_DP_ROW_WORDS);
+  const int nw = svc[14];
+  if (svc[15])
+    br_dp_build<4>(win, svc[11], svc[12], svc[13], nw, ws, BR_DP_ROW_WORDS, first, lane, wv, 4, [] { br_dp_sync_ws(); });
+  else
+    br_dp_build<1>(win, svc[11], svc[12], svc[13], nw, rows_lds, nw, first, lane, wv, 4, [] { __syncthreads(); });
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // the first-request bytes are visible to wave 0 after the barrier
+}
+
 // `win`: the window in LDS, entry b = s << 11 | sorted position, b < w (17..32); kmax = most requests the subset
 // may hold; `room`: largest admissible sum; `rows_lds`: BR_DP_LDS_WORDS words of LDS; `ws`: this cluster's
 // br_dp_cluster_words(KM) words of workspace.  Returns the chosen mask (0: no admissible subset) and its score key.
+// `svc` (or null): the mailbox of a block whose four waves share LDS builds: wave 0 (the caller) posts the plan,
+// the others join through br_dp_build_helper between the block barriers.
 template <bool BRH>
 __device__ __forceinline__ void br_subset_dp(const BrParams &p, const int (&mg)[BR_HP + 1], const int *win, int w,
                                              int kmax, int room, int lane, int *rows_lds, int *ws, unsigned &bestmask,
-                                             int &bestkey) {
+                                             int &bestkey, int *svc = nullptr) {
   constexpr int RW = BR_DP_ROW_WORDS;
   bestmask = 0u;
   bestkey = BR_KEY_NONE;
@@ -128,54 +205,9 @@ __device__ __forceinline__ void br_subset_dp(const BrParams &p, const int (&mg)[
     return;
   }
   const int nw = (R >> 5) + 1;
-  const unsigned lastmask = (R & 31) == 31 ? 0xffffffffu : (2u << (R & 31)) - 1u;
 
-  // rows: (kmax + 1) rows of `stride` words, LDS or workspace; UN words per lane and trip (workspace rows: four,
-  // so that their loads overlap; LDS rows are short and near: one)
-  auto run = [&](auto rows, const int stride, auto sync, auto unroll) {
-    constexpr int UN = decltype(unroll)::value;
-    for (int j = 0; j <= kmax; ++j)
-      for (int i = lane; i < nw; i += BR_WAVE) rows[j * stride + i] = i == 0 ? 1 : 0;  // the empty subset
-    sync();
-    for (int b = 0; b < w; ++b) {
-      const int s = win[b] >> BR_IDX_BITS;
-      if (s > R) continue;  // every subset that holds it lies beyond the rows
-      const int q = s >> 5, r = s & 31;
-      // every row takes every request: row j then always contains row j-1 ("at most j requests")
-      for (int j = kmax; j >= 1; --j) {
-        auto src = rows + (j - 1) * stride;
-        auto dst = rows + j * stride;
-        unsigned char *fj = first + (size_t)(j - 1) * (RW * 32);
-        for (int i0 = q + lane; i0 < nw; i0 += UN * BR_WAVE) {
-          unsigned lo[UN], hi[UN], old[UN];
-#pragma unroll
-          for (int u = 0; u < UN; ++u) {
-            const int i = i0 + u * BR_WAVE;
-            const bool in = i < nw;
-            lo[u] = in ? (unsigned)src[i - q] : 0u;
-            hi[u] = (in && i - q >= 1) ? (unsigned)src[i - q - 1] : 0u;
-            old[u] = in ? (unsigned)dst[i] : 0u;
-          }
-#pragma unroll
-          for (int u = 0; u < UN; ++u) {
-            const int i = i0 + u * BR_WAVE;
-            unsigned v = r ? (lo[u] << r) | (hi[u] >> (32 - r)) : lo[u];
-            if (i == nw - 1) v &= lastmask;
-            unsigned fresh = v & ~old[u];
-            if (i < nw && fresh != 0u) {
-              dst[i] = (int)(old[u] | fresh);
-              while (fresh != 0u) {
-                const int bit = (int)__builtin_ctz(fresh);
-                fresh &= fresh - 1u;
-                fj[i * 32 + bit] = (unsigned char)b;
-              }
-            }
-          }
-        }
-        // row j-1 is rewritten next, after every lane has read it here; row j is read again by the next request
-        sync();
-      }
-    }
+  // scoring over the finished rows: (kmax + 1) rows of `stride` words, LDS or workspace
+  auto run = [&](auto rows, const int stride) {
     auto last = rows + kmax * stride;
 
     // ---- scoring
@@ -243,13 +275,36 @@ __device__ __forceinline__ void br_subset_dp(const BrParams &p, const int (&mg)[
   };
 
   if ((kmax + 1) * nw <= BR_DP_LDS_WORDS) {
-    // LDS operations of one wave execute in order: a wave-level fence is all the exchange between lanes needs,
-    // and the byte stores to first[][] stay in flight behind it
-    run(rows_lds, nw, [] { br_wave_sync(); }, std::integral_constant<int, 1>{});
+    if (svc != nullptr) {  // the block's four waves build the rows together
+      svc[11] = w, svc[12] = kmax, svc[13] = R, svc[14] = nw, svc[15] = 0;
+      svc[0] = 2;
+      __syncthreads();
+      br_dp_build<1>(win, w, kmax, R, nw, rows_lds, nw, first, lane, 0, 4, [] { __syncthreads(); });
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+      __syncthreads();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");  // the helpers' first-request bytes
+    } else {
+      // LDS operations of one wave execute in order: a wave-level fence is all the exchange between lanes needs,
+      // and the byte stores to first[][] stay in flight behind it
+      br_dp_build<1>(win, w, kmax, R, nw, rows_lds, nw, first, lane, 0, 1, [] { br_wave_sync(); });
+    }
+    run(rows_lds, nw);
   } else {
-    run(ws, RW, [] {
-      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
-      __builtin_amdgcn_wave_barrier();
-    }, std::integral_constant<int, 4>{});
+    // workspace rows: four words per lane and trip, so that their loads overlap
+    if (svc != nullptr) {
+      svc[11] = w, svc[12] = kmax, svc[13] = R, svc[14] = nw, svc[15] = 1;
+      svc[0] = 2;
+      __syncthreads();
+      br_dp_build<4>(win, w, kmax, R, nw, ws, RW, first, lane, 0, 4, [] { br_dp_sync_ws(); });
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+      __syncthreads();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    } else {
+      br_dp_build<4>(win, w, kmax, R, nw, ws, RW, first, lane, 0, 1, [] {
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+        __builtin_amdgcn_wave_barrier();
+      });
+    }
+    run(ws, RW);
   }
 }
