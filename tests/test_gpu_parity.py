@@ -172,6 +172,9 @@ def test_random_rounds(case):
     (8, 10, 100, 40, dict(pred_mode=1, gamma=0.97)),     # long horizon: block-per-cluster score kernel; two waves share a cluster's searches
     (5, 8, 90, 24, dict(pred_mode=1, n_inst=2304)),      # long horizon, more clusters than share waves: one wave per cluster
     (6, 8, 300, 16, dict(pred_mode=1, n_inst=1200, gate_pfin=0.0)),  # queues of up to 512: two waves at this batch size
+    # windows beyond 16 requests on batches too large for a block of four waves per cluster: one wave builds the rows
+    (4, 6, 60, 0, dict(R_max=20, n_inst=1100, S_greedy=4)),
+    (5, 7, 70, 4, dict(R_max=24, n_inst=1100, gate_pfin=0.0, S_greedy=5)),
 ])
 def test_many_small_clusters(G, B, Q, H, extra):
     """Batches of 2048 clusters and more with short queues take the one-wave-per-cluster score kernel
