@@ -150,16 +150,52 @@ __device__ __forceinline__ void br_assign_body(const BrParams &p, const BrArr &a
     }
   }
   const int G = p.G;
+  // Loads: everything that does not need the queue length is requested before the first result is used, and the
+  // waiting set then comes in one batch of unconditional loads (below): two memory round trips for the cluster.
+  const bool act = lane < G;
+  const int64_t wrow = (int64_t)inst * G + lane;
+  int q0_raw = 0, cnt_raw = 0, n_raw = p.B, L_raw[NH];
+#pragma unroll
+  for (int h = 0; h < NH; ++h) L_raw[h] = BR_LOW;
+  const int64_t wrow_ld = act ? wrow : (int64_t)inst * G;  // lanes without a worker read worker 0's words (unused)
+  if (!pre) {
+    q0_raw = p.qlen[inst];
+    cnt_raw = a.count ? a.count[inst] : 0;
+    n_raw = p.n[wrow_ld];
+    if constexpr (!BRH) L_raw[0] = p.L[wrow_ld];
+  }
+  if constexpr (BRH) {
+#pragma unroll
+    for (int h = 0; h < NH; ++h) L_raw[h] = p.Lh[wrow_ld * (p.H + 1) + min(h, p.H)];
+  }
+  if (!act) {
+    n_raw = p.B;
+#pragma unroll
+    for (int h = 0; h < NH; ++h) L_raw[h] = BR_LOW;
+  }
   int q0, cnt;
   if (pre) {
     q0 = pre->q0, cnt = pre->cnt;
   } else {
-    q0 = br_uniform(min(max(p.qlen[inst], 0), p.Q));
-    cnt = a.count ? a.count[inst] : 0;
-    cnt = br_uniform(min(max(cnt, 0), a.arr_cap));
+    q0 = br_uniform(min(max(q0_raw, 0), p.Q));
+    cnt = br_uniform(min(max(cnt_raw, 0), a.arr_cap));
   }
   const int qn = q0 + min(cnt, p.Q - q0);
   const int64_t qrow = (int64_t)inst * p.Q, arow = (int64_t)inst * a.arr_cap;
+  // the waiting set's prefill lengths, unclamped: addresses by select, an entry beyond the set reads the cluster's
+  // first queue word (COOP and `pre`: loaded elsewhere)
+  int s_raw[E];
+  if constexpr (!COOP) {
+    if (!pre) {
+#pragma unroll
+      for (int j = 0; j < E; ++j) {
+        const int i = j * BR_WAVE + lane;
+        const bool ina = i >= q0 && i < qn;
+        const int32_t *src = ina ? a.s + (arow + (i - q0)) : p.qs + (qrow + (i < q0 ? i : 0));
+        s_raw[j] = *src;
+      }
+    }
+  }
 
   // first estimate of a newly admitted request when the library maintains c_hat (age 0)
   float c0 = 0.0f;
@@ -170,13 +206,20 @@ __device__ __forceinline__ void br_assign_body(const BrParams &p, const BrArr &a
   unsigned xk[E];
   if constexpr (COOP) {
     unsigned x8[8];
+    int s8[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {  // one batch of unconditional loads (an entry beyond the set reads the first queue word)
+      const int i = w * 512 + j * BR_WAVE + lane;
+      const bool ina = i >= q0 && i < qn;
+      const int32_t *src = ina ? a.s + (arow + (i - q0)) : p.qs + (qrow + (i < q0 ? i : 0));
+      s8[j] = *src;
+    }
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       const int i = w * 512 + j * BR_WAVE + lane;
       unsigned key = 0;
       if (i < qn) {
-        int s = i < q0 ? p.qs[qrow + i] : a.s[arow + (i - q0)];
-        s = min(max(s, 1), BR_MAX_S_DEV);
+        const int s = min(max(s8[j], 1), BR_MAX_S_DEV);
         key = ((unsigned)s << BR_IDX_BITS) | (unsigned)(IDX_MASK - i);
       }
       x8[j] = key;
@@ -235,17 +278,15 @@ __device__ __forceinline__ void br_assign_body(const BrParams &p, const BrArr &a
   }
 
   // ---- worker state, one worker per lane
-  const bool act = lane < G;
-  const int64_t wrow = (int64_t)inst * G + lane;
-  int nn = act ? min(max(pre ? pre->n : p.n[wrow], 0), p.B) : p.B;
+  int nn = act ? min(max(pre ? pre->n : n_raw, 0), p.B) : p.B;
   int cap = p.B - nn;
   const int nn_start = nn;
   int Lh[NH], Mh[NH];
   if constexpr (BRH) {
 #pragma unroll
-    for (int h = 0; h < NH; ++h) Lh[h] = act ? p.Lh[wrow * (p.H + 1) + min(h, p.H)] : BR_LOW;
+    for (int h = 0; h < NH; ++h) Lh[h] = L_raw[h];
   } else {
-    Lh[0] = act ? (pre ? pre->L : p.L[wrow]) : BR_LOW;
+    Lh[0] = act ? (pre ? pre->L : L_raw[0]) : BR_LOW;
   }
 #pragma unroll
   for (int h = 0; h < NH; ++h) Mh[h] = br_wave_max(Lh[h]);
@@ -291,8 +332,7 @@ __device__ __forceinline__ void br_assign_body(const BrParams &p, const BrArr &a
         if (pre) {
           s = pre->s[j];  // already clamped
         } else {
-          s = i < q0 ? p.qs[qrow + i] : a.s[arow + (i - q0)];
-          s = min(max(s, 1), BR_MAX_S_DEV);
+          s = min(max(s_raw[j], 1), BR_MAX_S_DEV);
         }
         key = ((unsigned)s << BR_IDX_BITS) | (unsigned)(IDX_MASK - i);
       }

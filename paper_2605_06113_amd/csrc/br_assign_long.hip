@@ -186,13 +186,20 @@ __global__ __launch_bounds__(64 * NW, E == 4 ? 4 : 1) void br_k_assign_long(BrPa
   // ---- waiting set, sorted in registers (largest prefill first, arrival order among equals)
   const bool run = S_tot > 0 && qn > 0;
   unsigned xk[E];
+  int s_raw[E];
+#pragma unroll
+  for (int j = 0; j < E; ++j) {  // one batch of unconditional loads (an entry beyond the set reads the first queue word)
+    const int i = j * BR_WAVE + lane;
+    const bool ina = i >= q0 && i < qn;
+    const int32_t *src = ina ? a.s + (arow + (i - q0)) : p.qs + (qrow + (i < q0 ? i : 0));
+    s_raw[j] = *src;
+  }
 #pragma unroll
   for (int j = 0; j < E; ++j) {
     const int i = j * BR_WAVE + lane;
     unsigned key = 0;
     if (i < qn) {
-      int s = i < q0 ? p.qs[qrow + i] : a.s[arow + (i - q0)];
-      s = min(max(s, 1), BR_MAX_S_DEV);
+      const int s = min(max(s_raw[j], 1), BR_MAX_S_DEV);
       key = ((unsigned)s << BR_IDX_BITS) | (unsigned)(IDX_MASK - i);
     }
     xk[j] = key;

@@ -21,30 +21,47 @@ struct BrScoreIn {
 template <int E, bool BRH>
 __device__ __forceinline__ void br_score_wave_load(const BrParams &p, const BrArr &a, int inst, int lane,
                                                    BrScoreIn<E, BRH> &in) {
-  const int q0 = br_uniform(min(max(p.qlen[inst], 0), p.Q));
-  int cnt = a.count ? a.count[inst] : 0;
-  cnt = br_uniform(min(max(cnt, 0), a.arr_cap));
-  in.qn = q0 + min(cnt, p.Q - q0);
-  in.q0 = q0;
-  in.cnt = cnt;
+  // every load that does not need the queue length is requested before the first result is used, and the waiting
+  // set comes in one batch of unconditional loads (addresses chosen by select, an entry beyond the set reads the
+  // cluster's first queue word): two memory round trips for the whole cluster
+  const int q0_raw = p.qlen[inst];
+  const int cnt_raw = a.count ? a.count[inst] : 0;
   const int64_t qrow = (int64_t)inst * p.Q, arow = (int64_t)inst * a.arr_cap;
   const bool act = lane < p.G;
   const int64_t wrow = (int64_t)inst * p.G + lane;
-  in.L = act ? p.L[wrow] : BR_LOW;
-  in.n = act ? p.n[wrow] : p.B;
+  const int64_t wrow_ld = act ? wrow : (int64_t)inst * p.G;  // lanes without a worker read worker 0's words (unused)
+  const int L_raw = p.L[wrow_ld], n_raw = p.n[wrow_ld];
+  int m_raw[BrScoreIn<E, BRH>::NH];
+  if constexpr (BRH) {
+#pragma unroll
+    for (int h = 0; h < BrScoreIn<E, BRH>::NH; ++h) m_raw[h] = p.mh[wrow_ld * (p.H + 1) + min(h, p.H)];
+  }
+  in.L = act ? L_raw : BR_LOW;
+  in.n = act ? n_raw : p.B;
   in.cap = act ? p.B - in.n : 0;
   if constexpr (BRH) {
 #pragma unroll
-    for (int h = 0; h < BrScoreIn<E, BRH>::NH; ++h) in.m[h] = (act && h <= p.H) ? p.mh[wrow * (p.H + 1) + h] : 0;
+    for (int h = 0; h < BrScoreIn<E, BRH>::NH; ++h) in.m[h] = (act && h <= p.H) ? m_raw[h] : 0;
   } else {
     in.m[0] = 0;
+  }
+  const int q0 = br_uniform(min(max(q0_raw, 0), p.Q));
+  const int cnt = br_uniform(min(max(cnt_raw, 0), a.arr_cap));
+  in.qn = q0 + min(cnt, p.Q - q0);
+  in.q0 = q0;
+  in.cnt = cnt;
+  int v[E];
+#pragma unroll
+  for (int e = 0; e < E; ++e) {
+    const int i = e * BR_WAVE + lane;
+    const bool ina = i >= q0 && i < in.qn;
+    const int32_t *src = ina ? a.s + (arow + (i - q0)) : p.qs + (qrow + (i < q0 ? i : 0));
+    v[e] = *src;
   }
 #pragma unroll
   for (int e = 0; e < E; ++e) {
     const int i = e * BR_WAVE + lane;
-    int v = 1;
-    if (i < in.qn) v = i < q0 ? p.qs[qrow + i] : a.s[arow + (i - q0)];
-    in.s[e] = min(max(v, 1), BR_MAX_S_DEV);
+    in.s[e] = i < in.qn ? min(max(v[e], 1), BR_MAX_S_DEV) : 1;
   }
 }
 
